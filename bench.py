@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the Loki decode-attention hot path on one MI355X.
+
+One "step" is one pass of the whole path (query rotation + low-rank scoring, top-k select,
+gather attention, combine) over one batch of synthetic input resident in HBM.  The workload
+is the Llama-2-7B-shaped configuration (batch 16, 32 heads, D=128, S=4096, bf16, d=32,
+k=1024) unless --workload names another one.  Prints ONE JSON line.
+
+Timed region: W warm-up steps, then exactly K steps between two device synchronisations;
+consecutive steps use different copies of the KV cache so that no step finds its rows in
+the 256 MB last-level cache.  A second pass of K steps records HIP events around every
+kernel (on the launch stream, through the library's profile hook) for the roofline of the
+dominant kernel; the dense baseline is timed the same way.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(w, select_mode):
+    """Bytes the method itself must move (Section 4.2 cost model in bytes): the low-rank slab
+    once per KV unit plus k full K and V rows per selecting head."""
+    e = w.elem_bytes
+    units = w.B * w.Hkv
+    sel_heads = units if (select_mode == 1 or w.G == 1) else w.B * w.Hq
+    score = units * w.S * w.d * e
+    gather = sel_heads * w.k * 2 * w.D * e
+    dense = units * w.S * 2 * w.D * e
+    return {"score": score, "gather_attend": gather, "step": score + gather, "dense_attend": dense}
+
+
+def cpu_baseline(w, x, select_mode, budget_s=20.0):
+    """The oracle as it stands, timed on the host on a bounded sample of (batch, KV head)
+    units of the same workload, scaled to the full unit count."""
+    from oracle import loki_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    units = [(b, h) for b in range(w.B) for h in range(w.Hkv)]
+    t0 = time.perf_counter()
+    done = 0
+    for u in units:
+        O.loki_decode_batch(x["q"], x["P"], x["khat"], x["v"], w.d, w.k, select_mode, units=[u])
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    us_per_step = dt / done * len(units) * 1e6
+    return {"value": us_per_step, "unit": "us/step", "cores": int(cores), "kind": "oracle",
+            "sample": f"{done} of {len(units)} (batch, KV head) units of {w.name}, "
+                      f"{dt:.1f} s, scaled to all units"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="llama2_7b")
+    ap.add_argument("--select-mode", type=int, default=0)
+    ap.add_argument("--copies", type=int, default=3, help="KV-cache copies cycled through")
+    ap.add_argument("--d", type=int, default=None)
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path needs no collective; "
+              "it shards by (batch, KV head)); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_02542_amd import api, synth
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    api.lib()  # fail loudly if the HIP library is not built
+
+    cfgs = synth.paper_configs()
+    if args.workload not in cfgs:
+        raise SystemExit(f"unknown workload {args.workload}; choose from {sorted(cfgs)}")
+    w = cfgs[args.workload]
+    if args.d is not None:
+        w = w.replace(d=args.d)
+    if args.k is not None:
+        w = w.replace(k=args.k)
+    mode = args.select_mode
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+    log(f"[bench] generating {w}")
+    t0 = time.perf_counter()
+    x = synth.make_inputs(w, threads=min(16, os.cpu_count() or 8))
+    log(f"[bench] inputs in {time.perf_counter() - t0:.1f} s; uploading {args.copies} cache copies")
+
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, w.D, w.d, w.S, tdt)
+    kh = torch.from_numpy(x["khat"]).to("cuda").to(tdt)
+    vv = torch.from_numpy(x["v"]).to("cuda").to(tdt)
+    caches = []
+    for _ in range(args.copies):
+        klo = kh[..., :w.d].contiguous()
+        khi = kh[..., w.d:].contiguous() if w.d < w.D else None
+        caches.append((klo, khi, vv.clone(), kh.clone()))
+    del kh, vv
+    q = torch.from_numpy(x["q"]).to("cuda").to(tdt)
+    P = torch.from_numpy(x["P"]).to("cuda")
+    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+    wsd = torch.empty(max(api.loki_workspace_bytes(lay, w.S, 0, 0, -1), 256), dtype=torch.uint8,
+                      device="cuda")
+    out = torch.empty((w.B, w.Hq, w.D), dtype=tdt, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def loki_step(i):
+        klo, khi, v, _ = caches[i % len(caches)]
+        api.loki_decode_attn(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, out, None, stream)
+
+    def dense_step(i):
+        _, _, v, kf = caches[i % len(caches)]
+        api.dense_decode_attn(lay, q, kf, v, w.S, wsd, out, stream)
+
+    def timed(step_fn, steps, warmup):
+        for i in range(warmup):
+            step_fn(i)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for i in range(steps):
+            step_fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / steps
+
+    def per_kernel(step_fn, steps):
+        prof = api.Profile()
+        acc, order = {}, []
+        prof.attach()
+        try:
+            for i in range(steps):
+                step_fn(i)
+                for name, ms in prof.read():
+                    if name not in acc:
+                        acc[name] = []
+                        order.append(name)
+                    acc[name].append(ms)
+        finally:
+            api.Profile.detach()
+            prof.close()
+        return {n: float(np.mean(acc[n])) * 1e3 for n in order}  # microseconds
+
+    log("[bench] timing loki")
+    t_loki = timed(loki_step, args.steps, args.warmup)
+    log(f"[bench] loki {t_loki * 1e6:.1f} us/step; per-kernel pass")
+    k_loki = per_kernel(loki_step, args.steps)
+    t_dense, k_dense = None, {}
+    if not args.no_dense:
+        log("[bench] timing dense baseline")
+        t_dense = timed(dense_step, args.steps, args.warmup)
+        k_dense = per_kernel(dense_step, args.steps)
+        log(f"[bench] dense {t_dense * 1e6:.1f} us/step")
+
+    ab = algorithmic_bytes(w, mode)
+    dominant = max((n for n in k_loki if n in ab), key=lambda n: k_loki[n])
+    achieved = ab[dominant] / (k_loki[dominant] * 1e-6) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(f"{w.name}:{dominant}")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                "algorithmic_bytes": ab[dominant], "kernel_us": k_loki[dominant]}
+
+    result = {
+        "metric": "loki_decode_attn_us_per_step",
+        "value": t_loki * 1e6,
+        "unit": "us/step",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": t_loki * 1e3,
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "S": w.S,
+                   "d": w.d, "k": w.k, "select_mode": mode, "cache_copies": args.copies},
+        "tokens_heads_per_s": w.B * w.Hq / t_loki,
+        "step_hbm_gbps": ab["step"] / t_loki / 1e9,
+        "step_hbm_frac": ab["step"] / t_loki / 1e9 / HBM_PEAK_GBPS,
+        "kernels_us": k_loki,
+        "dense_us_per_step": t_dense * 1e6 if t_dense else None,
+        "dense_hbm_gbps": ab["dense_attend"] / t_dense / 1e9 if t_dense else None,
+        "dense_kernels_us": k_dense,
+        "speedup_vs_dense": (t_dense / t_loki) if t_dense else None,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample")
+        result["cpu_baseline"] = cpu_baseline(w, x, mode)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * loki.h — C ABI of the MI355X (gfx950) Loki decode-attention library.
+ *
+ * Loki (arXiv 2406.02542) speeds up the decode step of attention: the key cache
+ * holds keys rotated into a fixed PCA basis P (Khat = K P); per step the query
+ * is rotated (qhat = q P), approximate scores are taken against the first d
+ * columns of Khat only, the k best-scoring tokens are selected, and exact
+ * softmax attention runs over those k rows in the rotated space (Algorithm 1,
+ * Section 4.2; exactness of the rotated scores is Lemma 4.1).
+ *
+ * Conventions common to every call
+ *   - All data pointers are DEVICE pointers unless marked "host".  `stream` is a
+ *     hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
+ *     work on `stream` and return without synchronising.
+ *   - The caller owns every buffer, including the workspace.  The library
+ *     allocates no device memory and keeps no state between calls; calls on
+ *     different streams with different workspaces may overlap.
+ *   - Every entry point returns a loki_status.  Arguments are validated on the
+ *     host before anything is launched; on any non-zero status nothing was
+ *     enqueued, except LOKI_ERR_HIP, which reports a launch error.
+ *   - Head dimension D must be 128.  Storage type is fp32 or bf16 for q, the
+ *     caches and the output; P is always fp32; all accumulation is fp32 and the
+ *     output is rounded once (nearest-even) to the storage type.
+ *   - NaN or Inf in the inputs: behaviour unspecified.
+ *
+ * Cache layout (per batch b and KV head h; S_cap rows are allocated, S are live)
+ *     klo [B, Hkv, S_cap, d_split]       first d_split columns of Khat
+ *     khi [B, Hkv, S_cap, D - d_split]   remaining columns of Khat
+ *     v   [B, Hkv, S_cap, D]             values, not rotated
+ *   Together klo and khi hold each rotated key exactly once (Section 4.2:
+ *   the cache is no larger than the original one, plus P).  d_split must be a
+ *   multiple of 16 bytes / element size; base pointers must be 16-byte aligned.
+ *   khi is unused (may be NULL) when d_split == D.
+ *
+ * Projection P [Hkv, D, D], row-major, fp32: qhat_j = sum_i q_i P[h][i][j]; the
+ * columns are the principal components, most important first.  Query head hq
+ * uses KV head hq / (Hq / Hkv).
+ */
+#ifndef LOKI_H
+#define LOKI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LOKI_OK = 0,
+  LOKI_ERR_INVALID_ARG = 1,     /* null pointer, size out of range, Hq % Hkv != 0 ...   */
+  LOKI_ERR_UNSUPPORTED = 2,     /* D != 128, unknown dtype, d not loadable in 16-B units  */
+  LOKI_ERR_ALIGNMENT = 3,       /* a base pointer is not 16-byte aligned                  */
+  LOKI_ERR_WORKSPACE = 4,       /* workspace smaller than loki_workspace_bytes reports    */
+  LOKI_ERR_HIP = 5              /* the HIP runtime reported an error at launch            */
+} loki_status;
+
+enum { LOKI_F32 = 0, LOKI_BF16 = 1 };
+
+/* How the k rows are chosen when several query heads share a KV head (the paper's
+ * Algorithm 1 is written for one query head and does not treat grouped queries).
+ *   PER_QUERY_HEAD: each query head ranks and picks its own k rows (literal reading).
+ *   PER_KV_GROUP:   one set per KV head, ranked by the maximum over the group's
+ *                   approximate scores; every query head of the group attends over it.
+ * Both are identical when Hq == Hkv. */
+enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
+
+typedef struct {
+  int32_t B;        /* sequences in the batch                         */
+  int32_t Hq;       /* query heads                                    */
+  int32_t Hkv;      /* KV heads; Hq % Hkv == 0                        */
+  int32_t D;        /* head dimension (128)                           */
+  int32_t d_split;  /* columns of Khat kept in the low-rank slab klo  */
+  int32_t S_cap;    /* rows allocated per (b, h) in klo / khi / v     */
+  int32_t dtype;    /* LOKI_F32 or LOKI_BF16                          */
+} loki_layout;
+
+/* Library version, major*10000 + minor*100 + patch. */
+int loki_version(void);
+
+/* Static, human-readable name of a status code (host pointer, never NULL). */
+const char* loki_status_string(int status);
+
+/* Bytes of the three cache arrays for a layout.  Host-only; touches no GPU. */
+int loki_cache_bytes(const loki_layout* layout, size_t* klo_bytes, size_t* khi_bytes,
+                     size_t* v_bytes);
+
+/* Bytes of workspace loki_decode_attn needs for (S, d, k, select_mode) and
+ * dense_decode_attn needs for S (pass d = 0, k = 0, select_mode = -1 for the
+ * dense baseline).  Host-only; touches no GPU.  The workspace holds the
+ * approximate scores, the selected indices, qhat and the partial softmax
+ * results of split rows; its contents are undefined between calls. */
+int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int select_mode,
+                         size_t* bytes);
+
+/*
+ * Algorithm 1 lines 3-4: rotate n_new new keys per (b, h) into the PCA basis and
+ * store them in the cache, khat = k P_h, rounded to the storage type.
+ *   k_new [B, Hkv, n_new, D]  keys in the model's basis (storage type)
+ *   P     [Hkv, D, D]         fp32
+ *   klo, khi                  cache slabs; rows [pos, pos + n_new) of every (b, h)
+ *                             are overwritten, other rows are untouched
+ * Requires 0 <= pos, 1 <= n_new, pos + n_new <= S_cap.  Values are appended by the
+ * caller directly (V is not transformed).
+ */
+int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                     void* khi, int pos, int n_new, void* stream);
+
+/*
+ * Algorithm 1 lines 3 and 5-9 for every (b, query head): the decode step.
+ *   q    [B, Hq, D]   queries in the model's basis (storage type)
+ *   P    [Hkv, D, D]  fp32
+ *   klo, khi, v       the cache; rows [0, S) are read
+ *   S                 live rows, 1 <= S <= S_cap (the new token's key is already
+ *                     in the cache and competes like any other row)
+ *   d                 ranking columns; must equal layout->d_split
+ *   k                 rows kept, 1 <= k <= S
+ *   select_mode       LOKI_SELECT_*
+ *   workspace         >= loki_workspace_bytes(layout, S, d, k, select_mode), 256-B aligned
+ *   out  [B, Hq, D]   softmax(qhat Khat'^T / sqrt(D)) V' over the selected rows
+ *                     (storage type)
+ *   out_idx           NULL, or int32 [B, Hsel, k] (Hsel = Hq or Hkv by select_mode):
+ *                     receives the selected positions in ascending order.  Ranking is
+ *                     by signed value of the unscaled approximate score computed in
+ *                     fp32; among equal scores the lowest position is kept.
+ */
+int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
+                     const void* khi, const void* v, int S, int d, int k, int select_mode,
+                     void* workspace, size_t workspace_bytes, void* out, int32_t* out_idx,
+                     void* stream);
+
+/*
+ * Section 2, Eq. 1: full attention over all S rows, the baseline Loki is compared
+ * with.  Works on an unsplit key cache.
+ *   q      [B, Hq, D]
+ *   k_full [B, Hkv, S_cap, D]   keys (any basis consistent with q; storage type)
+ *   v      [B, Hkv, S_cap, D]
+ *   out    [B, Hq, D]           softmax(q K^T / sqrt(D)) V
+ * layout->d_split is ignored.  Query heads of a group share one pass over K and V.
+ */
+int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S, void* workspace, size_t workspace_bytes, void* out, void* stream);
+
+/*
+ * Stage timing for benchmarks.  A profile owns HIP events; when one is attached
+ * with loki_profile_attach, the next decode / dense / rotate calls made from the
+ * same host thread record an event before and after every kernel they launch (on
+ * the call's stream).  loki_profile_read synchronises on the last event and
+ * returns, for the most recent call, the number of kernels and the elapsed
+ * milliseconds of each (ms[i] for the i-th kernel, in launch order; names[i]
+ * points at a static string).  Detach with loki_profile_attach(NULL).
+ */
+typedef struct loki_profile loki_profile;
+enum { LOKI_PROFILE_MAX_KERNELS = 8 };
+int loki_profile_create(loki_profile** out);
+int loki_profile_destroy(loki_profile* p);
+int loki_profile_attach(loki_profile* p);
+int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** names);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOKI_H */

@@ -1,0 +1,244 @@
+"""Thin Python binding over libloki.so's C ABI (include/loki.h).
+
+Argument marshalling only: torch supplies device memory and the stream, every
+step of the path runs in the HIP kernels.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libloki.so")
+
+LOKI_F32, LOKI_BF16 = 0, 1
+SELECT_PER_QUERY_HEAD, SELECT_PER_KV_GROUP = 0, 1
+PROFILE_MAX_KERNELS = 8
+
+
+class LokiError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+class Layout(ctypes.Structure):
+    """Mirror of ``loki_layout``."""
+
+    _fields_ = [("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("d_split", ctypes.c_int32), ("S_cap", ctypes.c_int32),
+                ("dtype", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libloki.so (built by ``paper_2406_02542_amd.build``); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2406_02542_amd.build` "
+            "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    LP = ctypes.POINTER(Layout)
+    L.loki_version.restype = i32
+    L.loki_version.argtypes = []
+    L.loki_status_string.restype = ctypes.c_char_p
+    L.loki_status_string.argtypes = [i32]
+    L.loki_cache_bytes.restype = i32
+    L.loki_cache_bytes.argtypes = [LP, ctypes.POINTER(sz), ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.loki_workspace_bytes.restype = i32
+    L.loki_workspace_bytes.argtypes = [LP, i32, i32, i32, i32, ctypes.POINTER(sz)]
+    L.loki_rotate_keys.restype = i32
+    L.loki_rotate_keys.argtypes = [LP, vp, vp, vp, vp, i32, i32, vp]
+    L.loki_decode_attn.restype = i32
+    L.loki_decode_attn.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    L.dense_decode_attn.restype = i32
+    L.dense_decode_attn.argtypes = [LP, vp, vp, vp, i32, vp, sz, vp, vp]
+    L.loki_profile_create.restype = i32
+    L.loki_profile_create.argtypes = [ctypes.POINTER(vp)]
+    L.loki_profile_destroy.restype = i32
+    L.loki_profile_destroy.argtypes = [vp]
+    L.loki_profile_attach.restype = i32
+    L.loki_profile_attach.argtypes = [vp]
+    L.loki_profile_read.restype = i32
+    L.loki_profile_read.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float),
+                                    ctypes.POINTER(ctypes.c_char_p)]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().loki_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return lib().loki_version()
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise LokiError(status, where)
+
+
+def make_layout(B: int, Hq: int, Hkv: int, D: int, d_split: int, S_cap: int,
+                dtype: torch.dtype) -> Layout:
+    if dtype == torch.float32:
+        code = LOKI_F32
+    elif dtype == torch.bfloat16:
+        code = LOKI_BF16
+    else:
+        raise ValueError(f"unsupported storage dtype {dtype}")
+    return Layout(B, Hq, Hkv, D, d_split, S_cap, code)
+
+
+def _torch_dtype(layout: Layout) -> torch.dtype:
+    return torch.float32 if layout.dtype == LOKI_F32 else torch.bfloat16
+
+
+def _ptr(t: Optional[torch.Tensor], name: str, dtype: Optional[torch.dtype] = None,
+         numel: Optional[int] = None) -> Optional[int]:
+    """Device pointer of a tensor after checking it is what the C side assumes."""
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name} holds {t.numel()} elements, the call reads/writes {numel}")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return s.cuda_stream
+
+
+def loki_cache_bytes(layout: Layout):
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib().loki_cache_bytes(ctypes.byref(layout), ctypes.byref(a), ctypes.byref(b),
+                                  ctypes.byref(c)), "loki_cache_bytes")
+    return a.value, b.value, c.value
+
+
+def loki_workspace_bytes(layout: Layout, S: int, d: int, k: int, select_mode: int) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().loki_workspace_bytes(ctypes.byref(layout), S, d, k, select_mode, ctypes.byref(n)),
+           "loki_workspace_bytes")
+    return n.value
+
+
+def alloc_cache(layout: Layout, device="cuda"):
+    """Allocates (klo, khi, v) tensors of the layout's shape (zero-filled)."""
+    dt = _torch_dtype(layout)
+    B, H, S, D, d = layout.B, layout.Hkv, layout.S_cap, layout.D, layout.d_split
+    klo = torch.zeros((B, H, S, d), dtype=dt, device=device)
+    khi = torch.zeros((B, H, S, D - d), dtype=dt, device=device) if d < D else None
+    v = torch.zeros((B, H, S, D), dtype=dt, device=device)
+    return klo, khi, v
+
+
+def alloc_workspace(layout: Layout, S: int, d: int, k: int, select_mode: int,
+                    device="cuda") -> torch.Tensor:
+    n = loki_workspace_bytes(layout, S, d, k, select_mode)
+    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+
+
+def loki_rotate_keys(layout: Layout, k_new: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                     khi: Optional[torch.Tensor], pos: int, n_new: int, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    _check(lib().loki_rotate_keys(
+        ctypes.byref(layout),
+        _ptr(k_new, "k_new", dt, rows * n_new * layout.D),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
+        _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
+        pos, n_new, _stream_ptr(stream)), "loki_rotate_keys")
+
+
+def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                     khi: Optional[torch.Tensor], v: torch.Tensor, S: int, d: int, k: int,
+                     select_mode: int, workspace: torch.Tensor, out: torch.Tensor,
+                     out_idx: Optional[torch.Tensor] = None, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    hsel = layout.Hq if select_mode == SELECT_PER_QUERY_HEAD else layout.Hkv
+    _check(lib().loki_decode_attn(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
+        _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S, d, k, select_mode,
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+        _ptr(out, "out", dt, nq),
+        _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k),
+        _stream_ptr(stream)), "loki_decode_attn")
+
+
+def dense_decode_attn(layout: Layout, q: torch.Tensor, k_full: torch.Tensor, v: torch.Tensor,
+                      S: int, workspace: Optional[torch.Tensor], out: torch.Tensor,
+                      stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    _check(lib().dense_decode_attn(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(k_full, "k_full", dt, rows * layout.S_cap * layout.D),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S,
+        _ptr(workspace, "workspace", torch.uint8),
+        workspace.numel() if workspace is not None else 0,
+        _ptr(out, "out", dt, nq),
+        _stream_ptr(stream)), "dense_decode_attn")
+
+
+class Profile:
+    """Owns a ``loki_profile``; while attached, every library call made from this
+    thread records HIP events around each kernel it launches."""
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        _check(lib().loki_profile_create(ctypes.byref(h)), "loki_profile_create")
+        self._h = h
+
+    def attach(self):
+        _check(lib().loki_profile_attach(self._h), "loki_profile_attach")
+
+    @staticmethod
+    def detach():
+        _check(lib().loki_profile_attach(None), "loki_profile_attach")
+
+    def read(self):
+        """[(kernel name, milliseconds)] of the most recent profiled call."""
+        n = ctypes.c_int()
+        ms = (ctypes.c_float * PROFILE_MAX_KERNELS)()
+        names = (ctypes.c_char_p * PROFILE_MAX_KERNELS)()
+        _check(lib().loki_profile_read(self._h, ctypes.byref(n), ms, names), "loki_profile_read")
+        return [(names[i].decode(), float(ms[i])) for i in range(n.value)]
+
+    def close(self):
+        if self._h is not None:
+            lib().loki_profile_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

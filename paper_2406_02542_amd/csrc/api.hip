@@ -1,0 +1,329 @@
+// C ABI of the Loki decode-attention library: argument validation, workspace planning and
+// kernel sequencing.  See include/loki.h for the contract of every entry point.
+#include "../../include/loki.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "launch.h"
+
+namespace loki {
+
+static inline int div_up(int a, int b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int score_rows_per_block(const Shape& s) {
+  const int units = s.B * s.Hkv;
+  int nchunks = div_up(8 * kNumCU, units);
+  const int max_chunks = div_up(s.S, 2 * kScoreRowsPerStep);
+  if (nchunks > max_chunks) nchunks = max_chunks;
+  if (nchunks < 1) nchunks = 1;
+  const int rows = div_up(s.S, nchunks);
+  return div_up(rows, kScoreRowsPerStep) * kScoreRowsPerStep;
+}
+
+int gather_splits(const Shape& s, int select_mode) {
+  const int heads = (select_mode == 1) ? s.B * s.Hkv : s.B * s.Hq;
+  int n = div_up(4 * kNumCU, heads);
+  const int max_n = s.k / 128 > 0 ? s.k / 128 : 1;
+  if (n > max_n) n = max_n;
+  const int min_n = div_up(s.k, kMaxGatherChunk);
+  if (n < min_n) n = min_n;
+  return n;
+}
+
+int dense_splits(const Shape& s) {
+  const int units = s.B * s.Hkv;
+  int n = div_up(8 * kNumCU, units);
+  const int max_n = s.S / 256 > 0 ? s.S / 256 : 1;
+  if (n > max_n) n = max_n;
+  return n < 1 ? 1 : n;
+}
+
+Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base) {
+  Workspace w{};
+  char* p = static_cast<char*>(base);
+  size_t off = 0;
+  const size_t heads_q = (size_t)s.B * s.Hq;
+  auto take = [&](size_t bytes) {
+    char* r = p ? p + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  };
+  if (select_mode >= 0) {
+    const size_t heads_sel = (select_mode == 1) ? (size_t)s.B * s.Hkv : heads_q;
+    w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
+    w.scores = reinterpret_cast<float*>(take(heads_sel * s.S * sizeof(float)));
+    w.sel_idx = reinterpret_cast<int32_t*>(take(heads_sel * s.k * sizeof(int32_t)));
+  }
+  w.partial = reinterpret_cast<float*>(
+      take(nsplit > 1 ? heads_q * nsplit * (size_t)(kD + 2) * sizeof(float) : 0));
+  w.total_bytes = off;
+  return w;
+}
+
+// ---- stage timing ---------------------------------------------------------------------
+}  // namespace loki
+
+struct loki_profile {
+  hipEvent_t ev[2 * LOKI_PROFILE_MAX_KERNELS];
+  const char* names[LOKI_PROFILE_MAX_KERNELS];
+  int n;
+};
+
+namespace loki {
+
+static thread_local loki_profile* t_profile = nullptr;
+
+struct StageTimer {
+  hipStream_t st;
+  explicit StageTimer(hipStream_t s) : st(s) {
+    if (t_profile) t_profile->n = 0;
+  }
+  void begin(const char* name) {
+    loki_profile* p = t_profile;
+    if (!p || p->n >= LOKI_PROFILE_MAX_KERNELS) return;
+    p->names[p->n] = name;
+    (void)hipEventRecord(p->ev[2 * p->n], st);
+  }
+  void end() {
+    loki_profile* p = t_profile;
+    if (!p || p->n >= LOKI_PROFILE_MAX_KERNELS) return;
+    (void)hipEventRecord(p->ev[2 * p->n + 1], st);
+    p->n++;
+  }
+};
+
+static int check_layout(const loki_layout* L, Shape* s) {
+  if (!L) return LOKI_ERR_INVALID_ARG;
+  if (L->B < 1 || L->Hq < 1 || L->Hkv < 1 || L->S_cap < 1) return LOKI_ERR_INVALID_ARG;
+  if (L->Hq % L->Hkv != 0) return LOKI_ERR_INVALID_ARG;
+  if (L->dtype != LOKI_F32 && L->dtype != LOKI_BF16) return LOKI_ERR_UNSUPPORTED;
+  if (L->D != 128) return LOKI_ERR_UNSUPPORTED;
+  const int eb = L->dtype == LOKI_F32 ? 4 : 2;
+  if (L->d_split < 1 || L->d_split > L->D) return LOKI_ERR_INVALID_ARG;
+  if ((L->d_split * eb) % 16 != 0) return LOKI_ERR_UNSUPPORTED;
+  const int G = L->Hq / L->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return LOKI_ERR_UNSUPPORTED;
+  // element counts must fit the kernels' 64-bit row arithmetic with 32-bit row indices
+  if ((long long)L->B * L->Hq > 0x7fffffffLL / 128) return LOKI_ERR_INVALID_ARG;
+  s->B = L->B;
+  s->Hq = L->Hq;
+  s->Hkv = L->Hkv;
+  s->G = G;
+  s->S_cap = L->S_cap;
+  s->S = 0;
+  s->d = L->d_split;
+  s->k = 0;
+  s->dtype = L->dtype;
+  s->elem_bytes = eb;
+  return LOKI_OK;
+}
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+}  // namespace loki
+
+using namespace loki;
+
+extern "C" {
+
+int loki_version(void) { return 100; }
+
+const char* loki_status_string(int status) {
+  switch (status) {
+    case LOKI_OK: return "ok";
+    case LOKI_ERR_INVALID_ARG: return "invalid argument";
+    case LOKI_ERR_UNSUPPORTED: return "unsupported configuration";
+    case LOKI_ERR_ALIGNMENT: return "pointer not sufficiently aligned";
+    case LOKI_ERR_WORKSPACE: return "workspace too small";
+    case LOKI_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int loki_cache_bytes(const loki_layout* layout, size_t* klo_bytes, size_t* khi_bytes,
+                     size_t* v_bytes) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!klo_bytes || !khi_bytes || !v_bytes) return LOKI_ERR_INVALID_ARG;
+  const size_t rows = (size_t)s.B * s.Hkv * s.S_cap;
+  *klo_bytes = rows * s.d * s.elem_bytes;
+  *khi_bytes = rows * (128 - s.d) * s.elem_bytes;
+  *v_bytes = rows * 128 * s.elem_bytes;
+  return LOKI_OK;
+}
+
+int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int select_mode,
+                         size_t* bytes) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!bytes) return LOKI_ERR_INVALID_ARG;
+  if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
+  s.S = S;
+  if (select_mode < 0) {
+    *bytes = plan_workspace(s, -1, dense_splits(s), nullptr).total_bytes;
+    return LOKI_OK;
+  }
+  if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
+    return LOKI_ERR_INVALID_ARG;
+  if (d != s.d) return LOKI_ERR_UNSUPPORTED;
+  if (k < 1 || k > S) return LOKI_ERR_INVALID_ARG;
+  s.k = k;
+  *bytes = plan_workspace(s, select_mode, gather_splits(s, select_mode), nullptr).total_bytes;
+  return LOKI_OK;
+}
+
+int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                     void* khi, int pos, int n_new, void* stream) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!k_new || !P || !klo) return LOKI_ERR_INVALID_ARG;
+  if (s.d < 128 && !khi) return LOKI_ERR_INVALID_ARG;
+  if (pos < 0 || n_new < 1 || (long long)pos + n_new > s.S_cap) return LOKI_ERR_INVALID_ARG;
+  if (!aligned16(k_new) || !aligned16(P) || !aligned16(klo) || !aligned16(khi))
+    return LOKI_ERR_ALIGNMENT;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  StageTimer tm(st);
+  tm.begin("rotate_keys");
+  const hipError_t e = launch_rotate(s, k_new, P, klo, khi, pos, n_new, st);
+  tm.end();
+  return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+}
+
+int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
+                     const void* khi, const void* v, int S, int d, int k, int select_mode,
+                     void* workspace, size_t workspace_bytes, void* out, int32_t* out_idx,
+                     void* stream) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!q || !P || !klo || !v || !out || !workspace) return LOKI_ERR_INVALID_ARG;
+  if (s.d < 128 && !khi) return LOKI_ERR_INVALID_ARG;
+  if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
+    return LOKI_ERR_INVALID_ARG;
+  if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
+  if (k < 1 || k > S) return LOKI_ERR_INVALID_ARG;
+  if (d != s.d) return LOKI_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(P) || !aligned16(klo) || !aligned16(khi) || !aligned16(v) ||
+      !aligned16(out) || !aligned16(out_idx))
+    return LOKI_ERR_ALIGNMENT;
+  if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+  s.S = S;
+  s.k = k;
+  if (s.G == 1) select_mode = LOKI_SELECT_PER_QUERY_HEAD;  // identical; one code path
+  const int nsplit = gather_splits(s, select_mode);
+  const Workspace w = plan_workspace(s, select_mode, nsplit, workspace);
+  if (w.total_bytes > workspace_bytes) return LOKI_ERR_WORKSPACE;
+
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int heads_sel = (select_mode == 1) ? s.B * s.Hkv : s.B * s.Hq;
+  int32_t* idx = out_idx ? out_idx : w.sel_idx;
+  StageTimer tm(st);
+  hipError_t e;
+  tm.begin("score");
+  e = launch_score(s, select_mode, q, P, klo, w.scores, w.qhat, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  tm.begin("select");
+  e = launch_select(s, heads_sel, w.scores, idx, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  tm.begin("gather_attend");
+  e = launch_gather(s, select_mode, nsplit, w.qhat, klo, khi, v, idx, w.partial, out, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  if (nsplit > 1) {
+    tm.begin("combine");
+    e = launch_combine(s, nsplit, w.partial, out, st);
+    tm.end();
+    if (e != hipSuccess) return LOKI_ERR_HIP;
+  }
+  return LOKI_OK;
+}
+
+int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S, void* workspace, size_t workspace_bytes, void* out, void* stream) {
+  Shape s;
+  loki_layout L;
+  if (!layout) return LOKI_ERR_INVALID_ARG;
+  L = *layout;
+  L.d_split = 128;  // ignored by the dense path
+  const int rc = check_layout(&L, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!q || !k_full || !v || !out) return LOKI_ERR_INVALID_ARG;
+  if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_full) || !aligned16(v) || !aligned16(out))
+    return LOKI_ERR_ALIGNMENT;
+  s.S = S;
+  const int nsplit = dense_splits(s);
+  const Workspace w = plan_workspace(s, -1, nsplit, workspace);
+  if (nsplit > 1) {
+    if (!workspace) return LOKI_ERR_INVALID_ARG;
+    if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+    if (w.total_bytes > workspace_bytes) return LOKI_ERR_WORKSPACE;
+  }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  StageTimer tm(st);
+  hipError_t e;
+  tm.begin("dense_attend");
+  e = launch_dense(s, nsplit, q, k_full, v, w.partial, out, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  if (nsplit > 1) {
+    tm.begin("combine");
+    e = launch_combine(s, nsplit, w.partial, out, st);
+    tm.end();
+    if (e != hipSuccess) return LOKI_ERR_HIP;
+  }
+  return LOKI_OK;
+}
+
+int loki_profile_create(loki_profile** out) {
+  if (!out) return LOKI_ERR_INVALID_ARG;
+  loki_profile* p = new (std::nothrow) loki_profile();
+  if (!p) return LOKI_ERR_INVALID_ARG;
+  p->n = 0;
+  for (int i = 0; i < 2 * LOKI_PROFILE_MAX_KERNELS; ++i) {
+    if (hipEventCreate(&p->ev[i]) != hipSuccess) {
+      for (int j = 0; j < i; ++j) (void)hipEventDestroy(p->ev[j]);
+      delete p;
+      return LOKI_ERR_HIP;
+    }
+  }
+  *out = p;
+  return LOKI_OK;
+}
+
+int loki_profile_destroy(loki_profile* p) {
+  if (!p) return LOKI_ERR_INVALID_ARG;
+  if (t_profile == p) t_profile = nullptr;
+  for (int i = 0; i < 2 * LOKI_PROFILE_MAX_KERNELS; ++i) (void)hipEventDestroy(p->ev[i]);
+  delete p;
+  return LOKI_OK;
+}
+
+int loki_profile_attach(loki_profile* p) {
+  t_profile = p;
+  return LOKI_OK;
+}
+
+int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** names) {
+  if (!p || !n_kernels || !ms) return LOKI_ERR_INVALID_ARG;
+  *n_kernels = p->n;
+  if (p->n == 0) return LOKI_OK;
+  if (hipEventSynchronize(p->ev[2 * p->n - 1]) != hipSuccess) return LOKI_ERR_HIP;
+  for (int i = 0; i < p->n; ++i) {
+    if (hipEventElapsedTime(&ms[i], p->ev[2 * i], p->ev[2 * i + 1]) != hipSuccess)
+      return LOKI_ERR_HIP;
+    if (names) names[i] = p->names[i];
+  }
+  return LOKI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Device-side helpers shared by the Loki kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "launch.h"
+
+namespace loki {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kNegBig = -1.0e30f;  // "no row seen yet" sentinel for running maxima (finite on purpose)
+
+// ---- storage types: one 16-byte chunk holds EPC elements ---------------------------------
+struct F32 {
+  using store_t = float;
+  static constexpr int kBytes = 4;
+  static constexpr int EPC = 4;
+  __device__ static inline void unpack(const uint4& r, float (&f)[4]) {
+    f[0] = __uint_as_float(r.x);
+    f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z);
+    f[3] = __uint_as_float(r.w);
+  }
+  __device__ static inline float load1(const store_t* p) { return *p; }
+  __device__ static inline void store1(store_t* p, float x) { *p = x; }
+};
+
+struct BF16 {
+  using store_t = uint16_t;
+  static constexpr int kBytes = 2;
+  static constexpr int EPC = 8;
+  __device__ static inline void unpack(const uint4& r, float (&f)[8]) {
+    f[0] = __uint_as_float(r.x << 16);
+    f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16);
+    f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16);
+    f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16);
+    f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  __device__ static inline float load1(const store_t* p) {
+    return __uint_as_float(static_cast<uint32_t>(*p) << 16);
+  }
+  // fp32 -> bf16, round to nearest, ties to even; NaN stays NaN
+  __device__ static inline uint16_t round(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<uint16_t>(u >> 16);
+  }
+  __device__ static inline void store1(store_t* p, float x) { *p = round(x); }
+};
+
+__device__ inline uint4 load16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+
+// ---- cross-lane movement through DPP (no LDS traffic) ----------------------------------
+template <int CTRL>
+__device__ inline float dpp_mov(float x) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm:[1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141; // lane i <- lane 7-i inside each 8
+constexpr int kDppRowMirror = 0x140;     // lane i <- lane 15-i inside each 16
+
+// Sum over each aligned group of LANES consecutive lanes (LANES a power of two); every lane
+// of the group receives the total.  All 64 lanes must be active.
+template <int LANES>
+__device__ inline float group_allreduce_sum(float x) {
+  if constexpr (LANES >= 2) x += dpp_mov<kDppQuadXor1>(x);
+  if constexpr (LANES >= 4) x += dpp_mov<kDppQuadXor2>(x);
+  if constexpr (LANES >= 8) x += dpp_mov<kDppRowHalfMirror>(x);
+  if constexpr (LANES >= 16) x += dpp_mov<kDppRowMirror>(x);
+  if constexpr (LANES >= 32) x += __shfl_xor(x, 16);
+  if constexpr (LANES >= 64) x += __shfl_xor(x, 32);
+  return x;
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Order-preserving map float -> uint32 (larger float <=> larger key); -0 is folded onto +0.
+__device__ inline uint32_t float_to_key(float a) {
+  uint32_t u = __float_as_uint(a);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+}  // namespace loki

@@ -1,0 +1,54 @@
+// Host-side launch interface between the C ABI (api.hip) and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace loki {
+
+constexpr int kD = 128;  // head dimension the kernels are written for
+
+struct Shape {
+  int B, Hq, Hkv, G;  // G = Hq / Hkv
+  int S, S_cap;
+  int d, k;
+  int dtype;        // 0 f32, 1 bf16
+  int elem_bytes;   // 4 or 2
+};
+
+// Grid-shaping decisions; pure functions of the shape so that workspace sizing (host only)
+// and the launchers agree.
+constexpr int kNumCU = 256;              // MI355X
+constexpr int kScoreRowsPerStep = 256;   // rows one 256-thread block scores per step
+constexpr int kMaxGatherChunk = 2048;    // selected rows one attend block may own (LDS index list)
+
+int score_rows_per_block(const Shape& s);
+int gather_splits(const Shape& s, int select_mode);
+int dense_splits(const Shape& s);
+
+struct Workspace {
+  float* qhat;       // [B*Hq, 128]
+  float* scores;     // [B*Hsel, S]
+  int32_t* sel_idx;  // [B*Hsel, k]
+  float* partial;    // [B*Hq, nsplit, 130]
+  size_t total_bytes;
+};
+// Lays the workspace out from `base` (may be null to only size it).
+Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base);
+
+hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
+                        const void* klo, float* scores, float* qhat, hipStream_t st);
+hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
+                         hipStream_t st);
+hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
+                         const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
+                         float* partial, void* out, hipStream_t st);
+hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
+                        const void* v, float* partial, void* out, hipStream_t st);
+hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,
+                          hipStream_t st);
+hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
+                         int pos, int n_new, hipStream_t st);
+
+}  // namespace loki

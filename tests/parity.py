@@ -1,0 +1,135 @@
+"""Shared helpers of the GPU parity tests: upload synthetic inputs, call the HIP path
+through the C-ABI binding, and compare with the CPU oracle under the stated tolerances.
+
+Tolerances (absolute, on outputs of magnitude O(1)):
+  fp32 storage: 1e-5.  bf16 storage: 2e-2 (the output is rounded once to bf16, whose
+  half-ulp at |x| < 4 is 2^-7 * 2 = 1.6e-2 worst case, typically 4e-3).
+Index sets must be equal except for swaps among scores within 1e-3 relative of the
+k-th largest score t: |a_p - t| <= 1e-3 * max(|t|, 1e-3 * rms(a)) for every position in
+the symmetric difference (the rms floor covers t ~ 0).  Where such swaps occur the
+output is compared with the oracle's attention evaluated on the GPU's own index set.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import loki_oracle as O
+from paper_2406_02542_amd import api, synth
+
+OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
+TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(TORCH_DT[dtype]).contiguous()
+
+
+class DeviceCase:
+    """A workload's tensors on the GPU in the library's layout."""
+
+    def __init__(self, w: synth.Workload, inputs: dict, S_cap: int | None = None):
+        self.w = w
+        self.inputs = inputs
+        S_cap = S_cap or w.S
+        self.layout = api.make_layout(w.B, w.Hq, w.Hkv, w.D, w.d, S_cap, TORCH_DT[w.dtype])
+        self.klo, self.khi, self.v = api.alloc_cache(self.layout)
+        kh = to_dev(inputs["khat"], w.dtype)
+        self.klo[:, :, :w.S, :] = kh[..., :w.d]
+        if self.khi is not None:
+            self.khi[:, :, :w.S, :] = kh[..., w.d:]
+        self.v[:, :, :w.S, :] = to_dev(inputs["v"], w.dtype)
+        self.kfull = torch.zeros((w.B, w.Hkv, S_cap, w.D), dtype=TORCH_DT[w.dtype], device="cuda")
+        self.kfull[:, :, :w.S, :] = kh
+        del kh
+        self.q = to_dev(inputs["q"], w.dtype)
+        self.P = torch.from_numpy(inputs["P"]).to("cuda").contiguous()
+
+    def run_loki(self, mode: int, want_idx: bool = True):
+        w = self.w
+        ws = api.alloc_workspace(self.layout, w.S, w.d, w.k, mode)
+        out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")
+        hsel = w.Hq if (mode == 0 or w.G == 1) else w.Hkv
+        idx = torch.full((w.B, hsel, w.k), -7, dtype=torch.int32, device="cuda") if want_idx else None
+        api.loki_decode_attn(self.layout, self.q, self.P, self.klo, self.khi, self.v, w.S, w.d, w.k,
+                             mode, ws, out, idx)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy().astype(np.float64), (idx.cpu().numpy() if want_idx else None)
+
+    def run_dense(self):
+        w = self.w
+        n = api.loki_workspace_bytes(self.layout, w.S, 0, 0, -1)
+        ws = torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+        out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")
+        api.dense_decode_attn(self.layout, self.q, self.kfull, self.v, w.S, ws, out)
+        torch.cuda.synchronize()
+        return out.float().cpu().numpy().astype(np.float64)
+
+
+def check_index_set(gpu_idx: np.ndarray, ora_idx: np.ndarray, scores: np.ndarray, S: int, k: int,
+                    where: str) -> bool:
+    """Validity + equality up to near-threshold swaps.  Returns True if sets are identical."""
+    g = gpu_idx.astype(np.int64)
+    assert g.shape == (k,), where
+    assert g.min() >= 0 and g.max() < S, f"{where}: index out of range"
+    assert np.all(np.diff(g) > 0), f"{where}: indices not strictly ascending / duplicates"
+    gs, os_ = set(g.tolist()), set(ora_idx.tolist())
+    if gs == os_:
+        return True
+    diff = np.array(sorted(gs ^ os_))
+    t = np.sort(scores)[::-1][k - 1]
+    rms = float(np.sqrt(np.mean(scores ** 2)))
+    bound = 1e-3 * max(abs(t), 1e-3 * rms)
+    worst = np.max(np.abs(scores[diff] - t))
+    assert worst <= bound, (f"{where}: {len(diff)} positions differ and the farthest is "
+                            f"{worst:.3e} from the threshold (allowed {bound:.3e})")
+    return False
+
+
+def check_loki(case: DeviceCase, mode: int, units=None, out_gpu=None, idx_gpu=None):
+    """Runs (or takes) the GPU result and compares it with the oracle on `units`
+    (list of (b, kv_head); None = all).  Returns a small stats dict."""
+    w, x = case.w, case.inputs
+    if out_gpu is None:
+        out_gpu, idx_gpu = case.run_loki(mode)
+    eff_mode = 0 if w.G == 1 else mode
+    out_o, idx_o, sc_o = O.loki_decode_batch(x["q"], x["P"], x["khat"], x["v"], w.d, w.k, eff_mode,
+                                             units=units)
+    tol = OUT_TOL[w.dtype]
+    todo = units if units is not None else [(b, h) for b in range(w.B) for h in range(w.Hkv)]
+    swaps, max_err = 0, 0.0
+    for b, h in todo:
+        qheads = range(h * w.G, (h + 1) * w.G)
+        sel_heads = qheads if eff_mode == 0 else [h]
+        same = {}
+        for hs in sel_heads:
+            same[hs] = check_index_set(idx_gpu[b, hs], idx_o[b, hs], sc_o[b, hs], w.S, w.k,
+                                       f"{w.name} mode {mode} b={b} sel_head={hs}")
+        for hq in qheads:
+            hs = hq if eff_mode == 0 else h
+            ref = out_o[b, hq]
+            if not same[hs]:
+                swaps += 1
+                qhat = O.rotate_query(x["q"][b, hq], x["P"][h])
+                ref = O.attend_selected(qhat, x["khat"][b, h], x["v"][b, h],
+                                        idx_gpu[b, hs].astype(np.int64))
+            err = float(np.max(np.abs(out_gpu[b, hq] - ref)))
+            max_err = max(max_err, err)
+            assert err <= tol, f"{w.name} mode {mode} b={b} hq={hq}: |out - oracle| = {err:.3e} > {tol}"
+    return {"max_err": max_err, "heads_with_swaps": swaps}
+
+
+def check_dense(case: DeviceCase, units=None, out_gpu=None):
+    w, x = case.w, case.inputs
+    if out_gpu is None:
+        out_gpu = case.run_dense()
+    ref = O.dense_decode_batch(x["q"], x["khat"], x["v"], units=units)
+    tol = OUT_TOL[w.dtype]
+    todo = units if units is not None else [(b, h) for b in range(w.B) for h in range(w.Hkv)]
+    max_err = 0.0
+    for b, h in todo:
+        for hq in range(h * w.G, (h + 1) * w.G):
+            err = float(np.max(np.abs(out_gpu[b, hq] - ref[b, hq])))
+            max_err = max(max_err, err)
+            assert err <= tol, f"{w.name} dense b={b} hq={hq}: {err:.3e} > {tol}"
+    return {"max_err": max_err}

@@ -1,0 +1,241 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Sizes here are ones the oracle finishes in seconds; they span several tiles
+of every kernel and ragged tails.  Full benchmark sizes are in test_gpu_full_size.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loki_oracle as O
+from paper_2406_02542_amd import api, synth
+from tests.parity import DeviceCase, OUT_TOL, TORCH_DT, check_dense, check_loki, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(name, B, Hq, Hkv, S, dtype, d, k, **kw):
+    w = synth.Workload(name, B, Hq, Hkv, 128, S, dtype, d, k, **kw)
+    return w, synth.make_inputs(w)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ whole path --
+def test_tiny_config_fp32():
+    """Config 1: batch 1, 8 heads, S=1024, fp32, d=32, k=256."""
+    w = synth.paper_configs()["tiny"]
+    say(f"case {w}")
+    case = DeviceCase(w, synth.make_inputs(w))
+    st = check_loki(case, 0)
+    say(f"loki {st}")
+    assert st["max_err"] <= 1e-5
+    say(f"dense {check_dense(case)}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", [
+    # (B, Hq, Hkv, S, d, k)
+    (2, 4, 4, 1500, 32, 300),     # MHA, ragged S, several score/select tiles
+    (1, 8, 2, 3001, 16, 517),     # GQA G=4, odd sizes
+    (1, 8, 1, 2048, 64, 256),     # GQA G=8
+    (3, 2, 1, 700, 32, 699),      # G=2, k = S-1
+])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_loki_matches_oracle(dtype, shape, mode):
+    B, Hq, Hkv, S, d, k = shape
+    w, x = _case(f"p_{dtype}_{S}", B, Hq, Hkv, S, dtype, d, k, seed=1000 + S + d)
+    say(f"case {w} mode {mode}")
+    case = DeviceCase(w, x, S_cap=S + 37)  # capacity larger than the live rows
+    say(f"loki {check_loki(case, mode)}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_dense_matches_oracle(dtype):
+    for (B, Hq, Hkv, S) in [(2, 4, 4, 1500), (1, 8, 2, 3001), (1, 8, 1, 2048), (2, 2, 1, 77)]:
+        w, x = _case(f"dn_{dtype}_{S}", B, Hq, Hkv, S, dtype, 32, 1, seed=2000 + S)
+        say(f"case {w}")
+        say(f"dense {check_dense(DeviceCase(w, x, S_cap=S + 5))}")
+
+
+# ------------------------------------------------------------------- edge cases --
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("S,d,k", [
+    (1, 32, 1),         # a single cached token
+    (2, 32, 2),
+    (65, 32, 64),       # one row past a wave tile
+    (257, 8, 1),        # k = 1; one 16-byte chunk per slab row in bf16
+    (1000, 128, 100),   # d = D: the Exact-TopK case, empty residual slab
+    (1000, 96, 250),    # slab row is not a power-of-two number of chunks
+    (640, 32, 640),     # k = S: equals dense attention
+    (5000, 32, 4999),
+])
+def test_edge_shapes(dtype, S, d, k):
+    w, x = _case(f"e_{dtype}_{S}_{d}", 1, 4, 2, S, dtype, d, k, seed=3000 + S + d + k)
+    say(f"case {w}")
+    case = DeviceCase(w, x)
+    for mode in (0, 1):
+        say(f"mode {mode} {check_loki(case, mode)}")
+    if k == S:
+        # k = S: Loki equals dense attention of the same q over the unrotated keys
+        # K = Khat P^T (Lemma 4.1), whatever d is
+        out, _ = case.run_loki(0)
+        K = np.einsum("bhsj,hij->bhsi", x["khat"].astype(np.float64), x["P"].astype(np.float64))
+        dn = O.dense_decode_batch(x["q"], K, x["v"])
+        assert np.max(np.abs(out - dn)) <= OUT_TOL[dtype]
+
+
+def test_ties_go_to_lowest_position():
+    """All-zero cache: every score ties, the first k positions must be selected and the
+    output is the mean of the first k value rows.  Then planted duplicate rows."""
+    w, x = _case("ties", 1, 2, 2, 3000, "f32", 32, 1100, seed=4000)
+    x0 = dict(x)
+    x0["khat"] = np.zeros_like(x["khat"])
+    case = DeviceCase(w, x0)
+    out, idx = case.run_loki(0)
+    for h in range(2):
+        assert idx[0, h].tolist() == list(range(1100))
+        np.testing.assert_allclose(out[0, h], x["v"][0, h, :1100].astype(np.float64).mean(axis=0),
+                                   atol=1e-5)
+    # duplicates: rows 100.. are copies of rows 0..99 cyclically, so every score has 30 equals
+    xd = dict(x)
+    kd = x["khat"].copy()
+    kd[:, :, 100:, :] = np.tile(kd[:, :, :100, :], (1, 1, 29, 1))
+    xd["khat"] = kd
+    case = DeviceCase(w, xd)
+    out, idx = case.run_loki(0)
+    _, idx_o, _ = O.loki_decode_batch(xd["q"], xd["P"], kd, xd["v"], w.d, w.k, 0)
+    # equal rows give bit-identical GPU scores, so the tie rule decides: sets must be exact
+    # unless rows of *different* value fall within rounding of each other at the threshold
+    st = check_loki(case, 0, out_gpu=out, idx_gpu=idx)
+    say(f"duplicates {st}")
+    for h in range(2):
+        sel = set(idx[0, h].tolist())
+        for p in idx[0, h].tolist():
+            base = p % 100
+            lower = [base + 100 * j for j in range((p - base) // 100)]
+            # if a copy at position p is selected, all its earlier copies are selected too
+            assert all(lp in sel for lp in lower)
+
+
+def test_heavy_hitters_are_selected():
+    """The peaked-attention recipe of the long-context config at reduced size: the planted
+    positions carry > 90 % of the mass and must all be among the selected rows."""
+    w = synth.paper_configs()["long_gqa"].replace(B=1, Hq=8, Hkv=2, S=20000, k=1250)
+    x = synth.make_inputs(w)
+    case = DeviceCase(w, x)
+    for mode in (0, 1):
+        out, idx = case.run_loki(mode)
+        say(f"mode {mode} {check_loki(case, mode, out_gpu=out, idx_gpu=idx)}")
+        for h in range(2):
+            planted = set(synth.heavy_positions(w, h).tolist())
+            for hs in (range(4 * h, 4 * h + 4) if mode == 0 else [h]):
+                assert planted <= set(idx[0, hs].tolist())
+
+
+def test_deterministic():
+    w, x = _case("det", 2, 8, 2, 4096, "bf16", 32, 1024, seed=5000)
+    case = DeviceCase(w, x)
+    a, ia = case.run_loki(0)
+    b, ib = case.run_loki(0)
+    assert np.array_equal(a, b) and np.array_equal(ia, ib)
+    assert np.array_equal(case.run_dense(), case.run_dense())
+
+
+def test_out_idx_optional():
+    w, x = _case("noidx", 1, 4, 4, 900, "bf16", 32, 200, seed=5001)
+    case = DeviceCase(w, x)
+    a, _ = case.run_loki(0, want_idx=True)
+    b, none = case.run_loki(0, want_idx=False)
+    assert none is None and np.array_equal(a, b)
+
+
+# -------------------------------------------------------------------- rotate_keys --
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_rotate_keys_matches_oracle(dtype):
+    """Khat = K P rounded to storage.  bf16: within one unit in the last place everywhere and
+    exactly equal for >= 99.9 % of the elements (fp32 accumulation against the oracle's
+    float64 can only flip a rounding that sits within ~1e-6 relative of a tie).  fp32: within
+    fp32 accumulation error of the float64 product."""
+    w = synth.Workload("rot", 2, 4, 2, 128, 777, dtype, 32, 8, seed=6000)
+    P = synth.make_P(w)
+    K = synth.make_unrotated_keys(w, P)
+    say(f"case {w}")
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, w.d, 1000, TORCH_DT[dtype])
+    klo, khi, _ = api.alloc_cache(lay)
+    klo.fill_(5.0)
+    khi.fill_(5.0)
+    Pd = torch.from_numpy(P).cuda()
+    # prefill of 700 rows at position 3, then appends of 1 and 76 rows
+    pos = 3
+    for n_new, lo in ((700, 0), (1, 700), (76, 701)):
+        chunk = to_dev(K[:, :, lo:lo + n_new, :], dtype)
+        api.loki_rotate_keys(lay, chunk, Pd, klo, khi, pos + lo, n_new)
+    torch.cuda.synchronize()
+    got = torch.cat([klo, khi], dim=-1).float().cpu().numpy().astype(np.float64)
+    assert np.all(got[:, :, :pos] == 5.0) and np.all(got[:, :, pos + 777:] == 5.0)
+    ref64 = O.rotate_keys_batch(K, P)
+    ref = O.to_storage(ref64, dtype)
+    g = got[:, :, pos:pos + 777]
+    if dtype == "bf16":
+        exact = np.mean(g == ref)
+        # one unit in the last place of bf16 (8 significant bits) at the reference's magnitude,
+        # plus the fp32 accumulation error of the 128-term dot product, which dominates for
+        # elements that cancel to nearly zero: 1e-6 * sum_i |k_i| |P_ij|
+        ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+        mag = np.einsum("bhsi,hij->bhsj", np.abs(K.astype(np.float64)), np.abs(P.astype(np.float64)))
+        excess = np.abs(g - ref) - (ulp * 1.0000001 + 1e-6 * mag)
+        say(f"exact fraction {exact:.6f}; worst excess over (1 ulp + fp32 accumulation) {excess.max():.3e}")
+        assert excess.max() <= 0
+        assert exact >= 0.999
+    else:
+        # fp32 storage: the kernel's fp32 accumulation of 128 terms against the unrounded
+        # float64 product, relative to the row norm (sqrt(128) * 2^-24 ~ 7e-7)
+        err = np.abs(g - ref64) / np.linalg.norm(ref64, axis=-1, keepdims=True)
+        say(f"max relative-to-row-norm error {err.max():.3e}")
+        assert err.max() < 2e-6
+
+
+def test_rotate_then_decode_chain():
+    """K -> loki_rotate_keys -> loki_decode_attn on the GPU-rotated cache, compared with
+    the oracle run on that same cache content and, through Lemma 4.1 with d = D and k = S,
+    with dense attention on the unrotated keys."""
+    w = synth.Workload("chain", 1, 4, 2, 128, 1200, "bf16", 32, 300, seed=7000)
+    P = synth.make_P(w)
+    K = synth.make_unrotated_keys(w, P)
+    x = {"P": P, "q": synth.make_q(w, P), "v": synth.make_v(w)}
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, w.d, w.S, torch.bfloat16)
+    klo, khi, v = api.alloc_cache(lay)
+    Pd = torch.from_numpy(P).cuda()
+    api.loki_rotate_keys(lay, to_dev(K, "bf16"), Pd, klo, khi, 0, w.S)
+    torch.cuda.synchronize()
+    x["khat"] = torch.cat([klo, khi], dim=-1).float().cpu().numpy()
+    case = DeviceCase(w, x)
+    say(f"chain {check_loki(case, 0)}")
+    # Lemma 4.1: full-rank, full-k Loki on the rotated cache ~ dense attention on unrotated
+    # keys; the rotated cache was rounded to bf16, so allow that rounding in the logits.
+    wfull = w.replace(d=128, k=w.S)
+    lay2 = api.make_layout(w.B, w.Hq, w.Hkv, 128, 128, w.S, torch.bfloat16)
+    klo2, _, _ = api.alloc_cache(lay2)
+    api.loki_rotate_keys(lay2, to_dev(K, "bf16"), Pd, klo2, None, 0, w.S)
+    ws = api.alloc_workspace(lay2, w.S, 128, w.S, 0)
+    out = torch.empty((1, 4, 128), dtype=torch.bfloat16, device="cuda")
+    api.loki_decode_attn(lay2, case.q, Pd, klo2, None, case.v, w.S, 128, w.S, 0, ws, out)
+    torch.cuda.synchronize()
+    ref = O.dense_decode_batch(x["q"], K, x["v"])
+    assert np.max(np.abs(out.float().cpu().numpy() - ref)) < 3e-2
+    del wfull
+
+
+def test_errors_surface_as_exceptions():
+    w, x = _case("err", 1, 2, 2, 128, "bf16", 32, 16, seed=8000)
+    case = DeviceCase(w, x)
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    out = torch.empty((1, 2, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(api.LokiError) as e:
+        api.loki_decode_attn(case.layout, case.q, case.P, case.klo, case.khi, case.v, 128, 32, 16, 0,
+                             ws, out)
+    assert e.value.status == 4
+    with pytest.raises(api.LokiError):
+        api.loki_decode_attn(case.layout, case.q, case.P, case.klo, case.khi, case.v, 128, 32, 129, 0,
+                             ws, out)

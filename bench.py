@@ -42,7 +42,8 @@ def algorithmic_bytes(w, select_mode):
     score = units * w.S * w.d * e
     gather = sel_heads * w.k * 2 * w.D * e
     dense = units * w.S * 2 * w.D * e
-    return {"score": score, "gather_attend": gather, "step": score + gather, "dense_attend": dense}
+    return {"score": score, "gather_attend": gather, "step": score + gather,
+            "fused_decode": score + gather, "dense_attend": dense}
 
 
 def cpu_baseline(w, x, select_mode, budget_s=20.0):
@@ -57,16 +58,19 @@ def cpu_baseline(w, x, select_mode, budget_s=20.0):
     units = [(b, h) for b in range(w.B) for h in range(w.Hkv)]
     t0 = time.perf_counter()
     done = 0
-    for u in units:
-        O.loki_decode_batch(x["q"], x["P"], x["khat"], x["v"], w.d, w.k, select_mode, units=[u])
-        done += 1
-        if time.perf_counter() - t0 > budget_s:
+    while True:  # whole passes over the units until ~budget_s/2 has gone by, then stop
+        for u in units:
+            O.loki_decode_batch(x["q"], x["P"], x["khat"], x["v"], w.d, w.k, select_mode, units=[u])
+            done += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        if time.perf_counter() - t0 > budget_s / 2:
             break
     dt = time.perf_counter() - t0
     us_per_step = dt / done * len(units) * 1e6
     return {"value": us_per_step, "unit": "us/step", "cores": int(cores), "kind": "oracle",
-            "sample": f"{done} of {len(units)} (batch, KV head) units of {w.name}, "
-                      f"{dt:.1f} s, scaled to all units"}
+            "sample": f"{done} (batch, KV head) unit evaluations of {w.name} "
+                      f"({len(units)} units per step) in {dt:.1f} s, scaled to one step"}
 
 
 def main():
@@ -79,8 +83,13 @@ def main():
     ap.add_argument("--copies", type=int, default=3, help="KV-cache copies cycled through")
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto",
+                    help="kernel sequence: the library's choice, or pinned")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy 5 times (reference point for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path needs no collective; "
@@ -103,6 +112,7 @@ def main():
     if args.k is not None:
         w = w.replace(k=args.k)
     mode = args.select_mode
+    path_bits = {"auto": 0, "split": api.PATH_SPLIT, "fused": api.PATH_FUSED}[args.path]
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
 
     log(f"[bench] generating {w}")
@@ -129,7 +139,8 @@ def main():
 
     def loki_step(i):
         klo, khi, v, _ = caches[i % len(caches)]
-        api.loki_decode_attn(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, out, None, stream)
+        api.loki_decode_attn(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path_bits, ws, out, None,
+                             stream)
 
     def dense_step(i):
         _, _, v, kf = caches[i % len(caches)]
@@ -161,6 +172,14 @@ def main():
             api.Profile.detach()
             prof.close()
         return {n: float(np.mean(acc[n])) * 1e3 for n in order}  # microseconds
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     log("[bench] timing loki")
     t_loki = timed(loki_step, args.steps, args.warmup)
@@ -201,7 +220,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "S": w.S,
-                   "d": w.d, "k": w.k, "select_mode": mode, "cache_copies": args.copies},
+                   "d": w.d, "k": w.k, "select_mode": mode, "path": args.path, "cache_copies": args.copies},
         "tokens_heads_per_s": w.B * w.Hq / t_loki,
         "step_hbm_gbps": ab["step"] / t_loki / 1e9,
         "step_hbm_frac": ab["step"] / t_loki / 1e9 / HBM_PEAK_GBPS,

@@ -65,6 +65,13 @@ enum { LOKI_F32 = 0, LOKI_BF16 = 1 };
  * Both are identical when Hq == Hkv. */
 enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
 
+/* Optional bits OR-ed into select_mode that pin the kernel sequence (for tests and
+ * benchmarks; by default the library chooses).  SPLIT: separate score, select and attention
+ * kernels with the work of a unit spread over many blocks.  FUSED: one kernel, one block per
+ * unit; only available when Hq == Hkv, S <= 8192 and k <= 2048 (else LOKI_ERR_UNSUPPORTED).
+ * Both give the same selected sets; outputs agree to fp32 rounding. */
+enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_MASK = 0x300 };
+
 typedef struct {
   int32_t B;        /* sequences in the batch                         */
   int32_t Hq;       /* query heads                                    */

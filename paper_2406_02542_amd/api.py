@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libloki.so")
 
 LOKI_F32, LOKI_BF16 = 0, 1
 SELECT_PER_QUERY_HEAD, SELECT_PER_KV_GROUP = 0, 1
+PATH_SPLIT, PATH_FUSED, PATH_MASK = 0x100, 0x200, 0x300
 PROFILE_MAX_KERNELS = 8
 
 
@@ -175,7 +176,7 @@ def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
     dt = _torch_dtype(layout)
     rows = layout.B * layout.Hkv
     nq = layout.B * layout.Hq * layout.D
-    hsel = layout.Hq if select_mode == SELECT_PER_QUERY_HEAD else layout.Hkv
+    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
     _check(lib().loki_decode_attn(
         ctypes.byref(layout),
         _ptr(q, "q", dt, nq),

@@ -56,6 +56,7 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
     w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
     w.scores = reinterpret_cast<float*>(take(heads_sel * s.S * sizeof(float)));
     w.sel_idx = reinterpret_cast<int32_t*>(take(heads_sel * s.k * sizeof(int32_t)));
+    w.sel_score = reinterpret_cast<float*>(take(heads_sel * s.k * sizeof(float)));
   }
   w.partial = reinterpret_cast<float*>(
       take(nsplit > 1 ? heads_q * nsplit * (size_t)(kD + 2) * sizeof(float) : 0));
@@ -169,6 +170,7 @@ int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int sel
     *bytes = plan_workspace(s, -1, dense_splits(s), nullptr).total_bytes;
     return LOKI_OK;
   }
+  select_mode &= ~LOKI_PATH_MASK;
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
   if (d != s.d) return LOKI_ERR_UNSUPPORTED;
@@ -205,8 +207,11 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   if (rc != LOKI_OK) return rc;
   if (!q || !P || !klo || !v || !out || !workspace) return LOKI_ERR_INVALID_ARG;
   if (s.d < 128 && !khi) return LOKI_ERR_INVALID_ARG;
+  const int path = select_mode & LOKI_PATH_MASK;
+  select_mode &= ~LOKI_PATH_MASK;
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
+  if (path != 0 && path != LOKI_PATH_SPLIT && path != LOKI_PATH_FUSED) return LOKI_ERR_INVALID_ARG;
   if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
   if (k < 1 || k > S) return LOKI_ERR_INVALID_ARG;
   if (d != s.d) return LOKI_ERR_UNSUPPORTED;
@@ -226,16 +231,23 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   int32_t* idx = out_idx ? out_idx : w.sel_idx;
   StageTimer tm(st);
   hipError_t e;
+  if (path == LOKI_PATH_FUSED && !fused_eligible(s)) return LOKI_ERR_UNSUPPORTED;
+  if (path == LOKI_PATH_FUSED || (path == 0 && fused_preferred(s))) {
+    tm.begin("fused_decode");
+    e = launch_fused(s, q, P, klo, khi, v, out, out_idx, st);
+    tm.end();
+    return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+  }
   tm.begin("score");
   e = launch_score(s, select_mode, q, P, klo, w.scores, w.qhat, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("select");
-  e = launch_select(s, heads_sel, w.scores, idx, st);
+  e = launch_select(s, heads_sel, w.scores, idx, w.sel_score, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("gather_attend");
-  e = launch_gather(s, select_mode, nsplit, w.qhat, klo, khi, v, idx, w.partial, out, st);
+  e = launch_gather(s, select_mode, nsplit, w.qhat, klo, khi, v, idx, w.sel_score, w.partial, out, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   if (nsplit > 1) {

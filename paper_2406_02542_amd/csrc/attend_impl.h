@@ -1,0 +1,197 @@
+// Exact softmax attention over a list of cache rows with an online softmax in the log2
+// domain and scale 1/sqrt(D) (Algorithm 1 lines 7-9 of arXiv 2406.02542 for the selected set,
+// Section 2 Eq. 1 for every row).  Shared by the stand-alone attention kernels and the fused
+// decode kernel.
+//
+// A row of K (128 logical columns, possibly split between the low-rank slab and the residual
+// slab) and the matching row of V are each read by LPRV consecutive lanes with one 16-byte
+// load per lane; the K.q dot product is finished with DPP inside the lane group; every lane
+// keeps the running output for its EPC columns of V.
+//
+// REUSE_LO: the low-rank part of the exact logit, sum_{j<d} qhat_j Khat[s,j], is exactly the
+// approximate score the ranking stage already computed, so the lanes that would read the
+// low-rank slab read nothing and the saved score is added instead.
+#pragma once
+
+#include "common.h"
+
+namespace loki {
+
+constexpr int kRowsInFlight = 4;        // rows per lane group per loop trip
+constexpr int kPartialStride = kD + 2;  // o[128], m, l
+constexpr float kSoftmaxScaleLog2 = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
+
+template <typename T, int NH>
+struct AttendAcc {
+  float m[NH], l[NH], o[NH][T::EPC];
+  __device__ __forceinline__ void init() {
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      m[g] = kNegBig;
+      l[g] = 0.f;
+#pragma unroll
+      for (int e = 0; e < T::EPC; ++e) o[g][e] = 0.f;
+    }
+  }
+};
+
+struct RowAddr {
+  const char* k_base;   // this lane's 16-byte chunk of K row 0 of the unit
+  size_t k_row_bytes;
+  const char* v_base;   // this lane's 16-byte chunk of V row 0 of the unit
+  size_t v_row_bytes;
+  bool k_load;          // false: this lane's K chunk is covered by the reused score
+};
+
+// c = lane's chunk index inside a row (0 .. 128/EPC-1).  k_a holds the first d columns
+// (d = 128: the whole row), k_b the rest.
+template <typename T, bool REUSE_LO>
+__device__ __forceinline__ RowAddr make_row_addr(const void* k_a, const void* k_b, const void* v,
+                                                 size_t kv_unit, int S_cap, int d, int c) {
+  const int nlo = d / T::EPC;
+  const bool in_lo = c < nlo;
+  RowAddr ra;
+  ra.k_load = !(REUSE_LO && in_lo);
+  ra.k_row_bytes = in_lo ? (size_t)d * T::kBytes : (size_t)(kD - d) * T::kBytes;
+  const char* kb = in_lo ? static_cast<const char*>(k_a) + (size_t)c * 16
+                         : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
+  ra.k_base = kb + kv_unit * S_cap * ra.k_row_bytes;
+  ra.v_row_bytes = (size_t)kD * T::kBytes;
+  ra.v_base = static_cast<const char*>(v) + kv_unit * S_cap * ra.v_row_bytes + (size_t)c * 16;
+  return ra;
+}
+
+// Processes list entries r in [r0, r1): cache row = GATHER ? s_idx[r - r0] : r.  NGROUPS lane
+// groups of the block share the entries round-robin; `gid` is this lane's group.
+template <typename T, int NH, int NGROUPS, bool GATHER, bool REUSE_LO>
+__device__ __forceinline__ void attend_rows(AttendAcc<T, NH>& acc, const float (&qr)[NH][T::EPC],
+                                            const RowAddr& ra, const int32_t* s_idx,
+                                            const float* s_a, int gid, int r0, int r1) {
+  constexpr int EPC = T::EPC;
+  constexpr int LPRV = kD / EPC;
+  constexpr int R = kRowsInFlight;
+  static_assert(!REUSE_LO || NH == 1, "score reuse needs one query head per selection");
+  for (int t0 = r0; t0 < r1; t0 += NGROUPS * R) {
+    bool ok[R];
+    uint4 kraw[R], vraw[R];
+    float alo[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      const int r = t0 + j * NGROUPS + gid;
+      ok[j] = r < r1;
+      int row = 0;
+      alo[j] = 0.f;
+      if (ok[j]) {
+        row = GATHER ? s_idx[r - r0] : r;
+        if constexpr (REUSE_LO) alo[j] = s_a[r - r0];
+      }
+      kraw[j] = (ok[j] && ra.k_load) ? load16(ra.k_base + (size_t)row * ra.k_row_bytes)
+                                     : make_uint4(0, 0, 0, 0);
+      vraw[j] = ok[j] ? load16(ra.v_base + (size_t)row * ra.v_row_bytes) : make_uint4(0, 0, 0, 0);
+    }
+    float logit[NH][R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      float kf[EPC];
+      T::unpack(kraw[j], kf);
+#pragma unroll
+      for (int g = 0; g < NH; ++g) {
+        float p = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) p = fmaf(kf[e], qr[g][e], p);
+        p = group_allreduce_sum<LPRV>(p);
+        if constexpr (REUSE_LO) p += alo[j];
+        logit[g][j] = ok[j] ? p * kSoftmaxScaleLog2 : kNegBig;
+      }
+    }
+    float vf[R][EPC];
+#pragma unroll
+    for (int j = 0; j < R; ++j) T::unpack(vraw[j], vf[j]);
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      float mn = acc.m[g];
+#pragma unroll
+      for (int j = 0; j < R; ++j) mn = fmaxf(mn, logit[g][j]);
+      const float corr = fast_exp2(acc.m[g] - mn);
+      acc.m[g] = mn;
+      float pj[R], ps = 0.f;
+#pragma unroll
+      for (int j = 0; j < R; ++j) {
+        pj[j] = ok[j] ? fast_exp2(logit[g][j] - mn) : 0.f;
+        ps += pj[j];
+      }
+      acc.l[g] = fmaf(acc.l[g], corr, ps);
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        float a = acc.o[g][e] * corr;
+#pragma unroll
+        for (int j = 0; j < R; ++j) a = fmaf(pj[j], vf[j][e], a);
+        acc.o[g][e] = a;
+      }
+    }
+  }
+}
+
+template <int WAVES, int NH>
+struct MergeSmem {
+  float m[WAVES][NH], l[WAVES][NH];
+  float o[WAVES][NH][kD];
+};
+
+// Merges the lane groups of each wave in registers, then publishes one (m, l, o[128]) per
+// wave and head in LDS.  Ends with a barrier.
+template <typename T, int NH, int WAVES>
+__device__ __forceinline__ void attend_publish(AttendAcc<T, NH>& acc, MergeSmem<WAVES, NH>& sm) {
+  constexpr int EPC = T::EPC;
+  constexpr int LPRV = kD / EPC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane % LPRV, rg = lane / LPRV;
+#pragma unroll
+  for (int off = LPRV; off < 64; off <<= 1) {
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      const float m2 = __shfl_xor(acc.m[g], off);
+      const float l2 = __shfl_xor(acc.l[g], off);
+      const float mn = fmaxf(acc.m[g], m2);
+      const float a = fast_exp2(acc.m[g] - mn), b2 = fast_exp2(m2 - mn);
+      acc.l[g] = acc.l[g] * a + l2 * b2;
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) {
+        const float o2 = __shfl_xor(acc.o[g][e], off);
+        acc.o[g][e] = acc.o[g][e] * a + o2 * b2;
+      }
+      acc.m[g] = mn;
+    }
+  }
+  if (rg == 0) {
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+      if (c == 0) {
+        sm.m[wave][g] = acc.m[g];
+        sm.l[wave][g] = acc.l[g];
+      }
+#pragma unroll
+      for (int e = 0; e < EPC; ++e) sm.o[wave][g][c * EPC + e] = acc.o[g][e];
+    }
+  }
+  __syncthreads();
+}
+
+// Merged (max, sum, output) of head g, column col over the block's waves.
+template <int WAVES, int NH>
+__device__ __forceinline__ void attend_merged(const MergeSmem<WAVES, NH>& sm, int g, int col,
+                                              float& mn, float& ls, float& os) {
+  mn = sm.m[0][g];
+#pragma unroll
+  for (int w = 1; w < WAVES; ++w) mn = fmaxf(mn, sm.m[w][g]);
+  ls = 0.f;
+  os = 0.f;
+#pragma unroll
+  for (int w = 0; w < WAVES; ++w) {
+    const float f = fast_exp2(sm.m[w][g] - mn);
+    ls = fmaf(sm.l[w][g], f, ls);
+    os = fmaf(sm.o[w][g][col], f, os);
+  }
+}
+
+}  // namespace loki

@@ -1,0 +1,161 @@
+// The whole decode step of Loki (Algorithm 1 lines 3 and 5-9 of arXiv 2406.02542) for one
+// (batch, head) unit in ONE block, for shapes where a unit's scores fit in LDS and there are
+// enough units to fill the chip: rotate q, score the low-rank slab into LDS, select the top-k
+// in LDS, then attend over the selected rows — no score buffer, index list or partial result
+// ever leaves the CU, and there is no launch boundary between the stages.
+#include "attend_impl.h"
+#include "score_impl.h"
+#include "select_impl.h"
+
+namespace loki {
+
+constexpr int kFusedThreads = 512;
+constexpr int kFusedWaves = kFusedThreads / 64;
+
+template <typename T, int LPR, bool REUSE_LO>
+__global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
+    const typename T::store_t* __restrict__ klo, const typename T::store_t* __restrict__ khi,
+    const typename T::store_t* __restrict__ v, const typename T::store_t* __restrict__ q,
+    const float* __restrict__ P, typename T::store_t* __restrict__ out,
+    int32_t* __restrict__ out_idx, int Hkv, int S, int S_cap, int d, int k) {
+  using ST = typename T::store_t;
+  constexpr int EPC = T::EPC;
+  constexpr int LPRV = kD / EPC;
+  constexpr int RPW = 64 / LPRV;
+
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  float* s_score = reinterpret_cast<float*>(dyn_smem);           // [S rounded up to 64]
+  int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + ((S + 63) & ~63));  // [k]
+  float* s_a = reinterpret_cast<float*>(s_idx + k);              // [k]
+
+  __shared__ float s_q[1][kD];
+  __shared__ float s_part[1][kRotParts][kD];
+  __shared__ float s_qhat[1][kD];
+  __shared__ SelectSmem<kFusedThreads> s_sel;
+  __shared__ MergeSmem<kFusedWaves, 1> s_merge;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
+  const int h = unit % Hkv;
+
+  // ---- qhat = q P_h, all 128 columns ----------------------------------------------------
+  rotate_query_block<T, 1, kFusedThreads>(q + (size_t)unit * kD, P + (size_t)h * kD * kD, kD, s_q,
+                                          s_part, s_qhat);
+
+  // ---- approximate scores over the low-rank slab, into LDS ------------------------------
+  {
+    const int c = lane % LPR;
+    const int nch = d / EPC;
+    const bool cact = c < nch;
+    float qr[1][EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) qr[0][e] = cact ? s_qhat[0][c * EPC + e] : 0.f;
+    const size_t row_bytes = (size_t)d * T::kBytes;
+    const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
+                       (size_t)(cact ? c : 0) * 16;
+    score_rows<T, LPR, 1, kFusedWaves>(base, row_bytes, cact, qr, 0, S,
+                                       [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; });
+  }
+  __syncthreads();
+
+  // ---- top-k in LDS ------------------------------------------------------------------------
+  int32_t* gidx = out_idx ? out_idx + (size_t)unit * k : nullptr;
+  block_select_topk<kFusedThreads>(s_score, S, k, s_sel, [&](int rank, int pos) {
+    s_idx[rank] = pos;
+    s_a[rank] = s_score[pos];
+    if (gidx) gidx[rank] = pos;
+  });
+  __syncthreads();
+
+  // ---- exact attention over the selected rows -----------------------------------------------
+  const int c = lane % LPRV, rg = lane / LPRV;
+  float qr[1][EPC];
+#pragma unroll
+  for (int e = 0; e < EPC; ++e) qr[0][e] = s_qhat[0][c * EPC + e];
+  const RowAddr ra = make_row_addr<T, REUSE_LO>(klo, khi, v, (size_t)unit, S_cap, d, c);
+  AttendAcc<T, 1> acc;
+  acc.init();
+  attend_rows<T, 1, kFusedWaves * RPW, true, REUSE_LO>(acc, qr, ra, s_idx, s_a, wave * RPW + rg, 0,
+                                                       k);
+  attend_publish<T, 1, kFusedWaves>(acc, s_merge);
+  if (tid < kD) {
+    float mn, ls, os;
+    attend_merged<kFusedWaves, 1>(s_merge, 0, tid, mn, ls, os);
+    T::store1(out + (size_t)unit * kD + tid, os / ls);
+  }
+}
+
+size_t fused_dynamic_lds(const Shape& s) {
+  return (size_t)((s.S + 63) & ~63) * 4 + (size_t)s.k * 8;
+}
+
+bool fused_eligible(const Shape& s) {
+  return s.G == 1 && s.S <= kFusedMaxS && s.k <= kFusedMaxK;
+}
+
+bool fused_preferred(const Shape& s) {
+  if (!fused_eligible(s)) return false;
+  const int units = s.B * s.Hkv;
+  // enough blocks to occupy most CUs, or so little work per unit that launch count dominates
+  return units >= 192 || s.S <= 2048;
+}
+
+template <typename T, int LPR, bool REUSE_LO>
+static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, const void* klo,
+                                 const void* khi, const void* v, void* out, int32_t* out_idx,
+                                 hipStream_t st) {
+  using ST = typename T::store_t;
+  auto kern = fused_decode_kernel<T, LPR, REUSE_LO>;
+  const size_t lds = fused_dynamic_lds(s);
+  static bool attr_set = false;  // benign race: every caller sets the same value
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)(kFusedMaxS * 4 + kFusedMaxK * 8));
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(kFusedThreads), lds, st,
+                     static_cast<const ST*>(klo), static_cast<const ST*>(khi),
+                     static_cast<const ST*>(v), static_cast<const ST*>(q), P, static_cast<ST*>(out),
+                     out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k);
+  return hipGetLastError();
+}
+
+template <typename T, int LPR>
+static hipError_t launch_fused_l(const Shape& s, const void* q, const float* P, const void* klo,
+                                 const void* khi, const void* v, void* out, int32_t* out_idx,
+                                 hipStream_t st) {
+  if (s.d < kD) return launch_fused_r<T, LPR, true>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_r<T, LPR, false>(s, q, P, klo, khi, v, out, out_idx, st);
+}
+
+template <typename T>
+static hipError_t launch_fused_t(const Shape& s, const void* q, const float* P, const void* klo,
+                                 const void* khi, const void* v, void* out, int32_t* out_idx,
+                                 hipStream_t st) {
+  const int nch = s.d / T::EPC;
+  int lpr = 1;
+  while (lpr < nch) lpr <<= 1;
+  switch (lpr) {
+    case 1: return launch_fused_l<T, 1>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 2: return launch_fused_l<T, 2>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 4: return launch_fused_l<T, 4>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 8: return launch_fused_l<T, 8>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 16: return launch_fused_l<T, 16>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 32:
+      if constexpr (T::EPC == 4) return launch_fused_l<T, 32>(s, q, P, klo, khi, v, out, out_idx, st);
+      return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_fused(const Shape& s, const void* q, const float* P, const void* klo,
+                        const void* khi, const void* v, void* out, int32_t* out_idx,
+                        hipStream_t st) {
+  if (!fused_eligible(s)) return hipErrorInvalidValue;
+  return s.dtype == 0 ? launch_fused_t<F32>(s, q, P, klo, khi, v, out, out_idx, st)
+                      : launch_fused_t<BF16>(s, q, P, klo, khi, v, out, out_idx, st);
+}
+
+}  // namespace loki

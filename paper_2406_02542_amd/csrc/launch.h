@@ -22,6 +22,8 @@ struct Shape {
 constexpr int kNumCU = 256;              // MI355X
 constexpr int kScoreRowsPerStep = 256;   // rows one 256-thread block scores per step
 constexpr int kMaxGatherChunk = 2048;    // selected rows one attend block may own (LDS index list)
+constexpr int kFusedMaxS = 8192;         // fused single-kernel path: scores of a unit live in LDS
+constexpr int kFusedMaxK = 2048;
 
 int score_rows_per_block(const Shape& s);
 int gather_splits(const Shape& s, int select_mode);
@@ -31,6 +33,7 @@ struct Workspace {
   float* qhat;       // [B*Hq, 128]
   float* scores;     // [B*Hsel, S]
   int32_t* sel_idx;  // [B*Hsel, k]
+  float* sel_score;  // [B*Hsel, k] approximate scores of the selected rows
   float* partial;    // [B*Hq, nsplit, 130]
   size_t total_bytes;
 };
@@ -40,14 +43,20 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st);
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
-                         hipStream_t st);
+                         float* sel_score, hipStream_t st);
 hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
-                         float* partial, void* out, hipStream_t st);
+                         const float* sel_score, float* partial, void* out, hipStream_t st);
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
                         const void* v, float* partial, void* out, hipStream_t st);
 hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,
                           hipStream_t st);
+// Fused single-kernel decode step (one query head per KV head only).
+bool fused_eligible(const Shape& s);
+bool fused_preferred(const Shape& s);
+hipError_t launch_fused(const Shape& s, const void* q, const float* P, const void* klo,
+                        const void* khi, const void* v, void* out, int32_t* out_idx,
+                        hipStream_t st);
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
                          int pos, int n_new, hipStream_t st);
 

@@ -45,14 +45,15 @@ class DeviceCase:
         self.q = to_dev(inputs["q"], w.dtype)
         self.P = torch.from_numpy(inputs["P"]).to("cuda").contiguous()
 
-    def run_loki(self, mode: int, want_idx: bool = True):
+    def run_loki(self, mode: int, want_idx: bool = True, path: int = 0):
+        """path: 0 = library's choice, api.PATH_SPLIT or api.PATH_FUSED to pin it."""
         w = self.w
         ws = api.alloc_workspace(self.layout, w.S, w.d, w.k, mode)
         out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")
         hsel = w.Hq if (mode == 0 or w.G == 1) else w.Hkv
         idx = torch.full((w.B, hsel, w.k), -7, dtype=torch.int32, device="cuda") if want_idx else None
         api.loki_decode_attn(self.layout, self.q, self.P, self.klo, self.khi, self.v, w.S, w.d, w.k,
-                             mode, ws, out, idx)
+                             mode | path, ws, out, idx)
         torch.cuda.synchronize()
         return out.float().cpu().numpy().astype(np.float64), (idx.cpu().numpy() if want_idx else None)
 
@@ -86,12 +87,12 @@ def check_index_set(gpu_idx: np.ndarray, ora_idx: np.ndarray, scores: np.ndarray
     return False
 
 
-def check_loki(case: DeviceCase, mode: int, units=None, out_gpu=None, idx_gpu=None):
+def check_loki(case: DeviceCase, mode: int, units=None, out_gpu=None, idx_gpu=None, path: int = 0):
     """Runs (or takes) the GPU result and compares it with the oracle on `units`
     (list of (b, kv_head); None = all).  Returns a small stats dict."""
     w, x = case.w, case.inputs
     if out_gpu is None:
-        out_gpu, idx_gpu = case.run_loki(mode)
+        out_gpu, idx_gpu = case.run_loki(mode, path=path)
     eff_mode = 0 if w.G == 1 else mode
     out_o, idx_o, sc_o = O.loki_decode_batch(x["q"], x["P"], x["khat"], x["v"], w.d, w.k, eff_mode,
                                              units=units)

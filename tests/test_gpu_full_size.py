@@ -4,7 +4,7 @@ that hold at any size (index validity, ordering) are checked on every unit."""
 import numpy as np
 import pytest
 
-from paper_2406_02542_amd import synth
+from paper_2406_02542_amd import api, synth
 from tests.parity import DeviceCase, check_dense, check_loki
 
 pytestmark = pytest.mark.gpu
@@ -48,6 +48,12 @@ def test_full_size_config(name, modes, n_units):
         _all_index_sets_valid(idx, w.S)
         assert np.all(np.isfinite(out))
         say(f"{name} mode {mode}: {check_loki(case, mode, units=units, out_gpu=out, idx_gpu=idx)}")
+        if w.G == 1:
+            # the library's choice above is the one-kernel path; pin the split path too
+            out2, idx2 = case.run_loki(mode, path=api.PATH_SPLIT)
+            assert np.array_equal(idx, idx2)
+            say(f"{name} mode {mode} split path: "
+                f"{check_loki(case, mode, units=units, out_gpu=out2, idx_gpu=idx2)}")
     out = case.run_dense()
     assert np.all(np.isfinite(out))
     say(f"{name} dense: {check_dense(case, units=units[:4], out_gpu=out)}")

@@ -27,9 +27,10 @@ def test_tiny_config_fp32():
     w = synth.paper_configs()["tiny"]
     say(f"case {w}")
     case = DeviceCase(w, synth.make_inputs(w))
-    st = check_loki(case, 0)
-    say(f"loki {st}")
-    assert st["max_err"] <= 1e-5
+    for path in (0, api.PATH_SPLIT, api.PATH_FUSED):
+        st = check_loki(case, 0, path=path)
+        say(f"loki path {path:#x} {st}")
+        assert st["max_err"] <= 1e-5
     say(f"dense {check_dense(case)}")
 
 
@@ -48,6 +49,9 @@ def test_loki_matches_oracle(dtype, shape, mode):
     say(f"case {w} mode {mode}")
     case = DeviceCase(w, x, S_cap=S + 37)  # capacity larger than the live rows
     say(f"loki {check_loki(case, mode)}")
+    say(f"loki split {check_loki(case, mode, path=api.PATH_SPLIT)}")
+    if Hq == Hkv:
+        say(f"loki fused {check_loki(case, mode, path=api.PATH_FUSED)}")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -85,6 +89,36 @@ def test_edge_shapes(dtype, S, d, k):
         assert np.max(np.abs(out - dn)) <= OUT_TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("S,d,k", [
+    (1, 32, 1), (2, 32, 2), (65, 32, 64), (257, 8, 1), (1000, 128, 100), (1000, 96, 250),
+    (640, 32, 640), (5000, 32, 2048), (8192, 16, 2048), (8191, 64, 1),
+])
+def test_edge_shapes_single_kernel_and_split_paths(dtype, S, d, k):
+    """Hq == Hkv: the same shapes through the one-kernel path and through the split path;
+    the selected sets must be identical and the outputs agree to fp32 rounding."""
+    w, x = _case(f"f_{dtype}_{S}_{d}", 2, 3, 3, S, dtype, d, k, seed=3500 + S + d + k)
+    say(f"case {w}")
+    case = DeviceCase(w, x)
+    of, jf = case.run_loki(0, path=api.PATH_FUSED)
+    os_, js = case.run_loki(0, path=api.PATH_SPLIT)
+    say(f"fused {check_loki(case, 0, out_gpu=of, idx_gpu=jf)}")
+    say(f"split {check_loki(case, 0, out_gpu=os_, idx_gpu=js)}")
+    assert np.array_equal(jf, js)
+    assert np.max(np.abs(of - os_)) <= (1e-6 if dtype == "f32" else 8e-3)
+
+
+def test_single_kernel_path_limits():
+    """Pinning the one-kernel path outside its limits is refused, not silently rerouted."""
+    for (Hq, Hkv, S, k) in [(4, 2, 512, 64), (2, 2, 8193, 64), (2, 2, 8192, 2049)]:
+        w, x = _case("lim", 1, Hq, Hkv, S, "bf16", 32, k, seed=3600)
+        case = DeviceCase(w, x)
+        with pytest.raises(api.LokiError) as e:
+            case.run_loki(0, path=api.PATH_FUSED)
+        assert e.value.status == 2
+        check_loki(case, 0)  # the default route still works
+
+
 def test_ties_go_to_lowest_position():
     """All-zero cache: every score ties, the first k positions must be selected and the
     output is the mean of the first k value rows.  Then planted duplicate rows."""
@@ -92,19 +126,21 @@ def test_ties_go_to_lowest_position():
     x0 = dict(x)
     x0["khat"] = np.zeros_like(x["khat"])
     case = DeviceCase(w, x0)
-    out, idx = case.run_loki(0)
-    for h in range(2):
-        assert idx[0, h].tolist() == list(range(1100))
-        np.testing.assert_allclose(out[0, h], x["v"][0, h, :1100].astype(np.float64).mean(axis=0),
-                                   atol=1e-5)
+    for path in (api.PATH_SPLIT, api.PATH_FUSED):
+        out, idx = case.run_loki(0, path=path)
+        for h in range(2):
+            assert idx[0, h].tolist() == list(range(1100))
+            np.testing.assert_allclose(out[0, h],
+                                       x["v"][0, h, :1100].astype(np.float64).mean(axis=0), atol=1e-5)
     # duplicates: rows 100.. are copies of rows 0..99 cyclically, so every score has 30 equals
     xd = dict(x)
     kd = x["khat"].copy()
     kd[:, :, 100:, :] = np.tile(kd[:, :, :100, :], (1, 1, 29, 1))
     xd["khat"] = kd
     case = DeviceCase(w, xd)
-    out, idx = case.run_loki(0)
-    _, idx_o, _ = O.loki_decode_batch(xd["q"], xd["P"], kd, xd["v"], w.d, w.k, 0)
+    out, idx = case.run_loki(0, path=api.PATH_SPLIT)
+    outf, idxf = case.run_loki(0, path=api.PATH_FUSED)
+    assert np.array_equal(idx, idxf)
     # equal rows give bit-identical GPU scores, so the tie rule decides: sets must be exact
     # unless rows of *different* value fall within rounding of each other at the threshold
     st = check_loki(case, 0, out_gpu=out, idx_gpu=idx)

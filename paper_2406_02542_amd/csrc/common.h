@@ -11,6 +11,22 @@ namespace loki {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no row seen yet" sentinel for running maxima (finite on purpose)
 
+// Debug builds (-DLOKI_PHASE_TIMING) stamp the 100 MHz wall clock at phase boundaries of the
+// fused kernel's blocks so that its time line can be read back; a no-op otherwise.
+#ifdef LOKI_PHASE_TIMING
+constexpr int kPhaseSlots = 16;
+static __device__ unsigned long long g_phase_ts[8192 * kPhaseSlots];  // one copy per source file
+#define LOKI_STAMP(i)                                           \
+  do {                                                          \
+    if (threadIdx.x == 0 && blockIdx.x < 8192)                  \
+      loki::g_phase_ts[blockIdx.x * loki::kPhaseSlots + (i)] = wall_clock64(); \
+  } while (0)
+#else
+#define LOKI_STAMP(i) \
+  do {                \
+  } while (0)
+#endif
+
 // ---- storage types: one 16-byte chunk holds EPC elements ---------------------------------
 struct F32 {
   using store_t = float;

@@ -11,6 +11,13 @@ namespace loki {
 
 constexpr int kFusedThreads = 512;
 constexpr int kFusedWaves = kFusedThreads / 64;
+constexpr int kFusedKPT = kFusedMaxS / kFusedThreads;  // keys a thread may hold in the select stage
+
+// positions per thread in the select stage: ceil(S / threads) rounded up to a multiple of 4
+__host__ __device__ inline int fused_keys_per_thread(int S) {
+  const int c = (S + kFusedThreads - 1) / kFusedThreads;
+  return (c + 3) & ~3;
+}
 
 template <typename T, int LPR, bool REUSE_LO>
 __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
@@ -24,24 +31,28 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
   constexpr int RPW = 64 / LPRV;
 
   extern __shared__ __align__(16) unsigned char dyn_smem[];
-  float* s_score = reinterpret_cast<float*>(dyn_smem);           // [S rounded up to 64]
-  int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + ((S + 63) & ~63));  // [k]
+  const int per_thread = fused_keys_per_thread(S);               // multiple of 4, <= kFusedKPT
+  float* s_score = reinterpret_cast<float*>(dyn_smem);           // [kFusedThreads * per_thread]
+  int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + kFusedThreads * per_thread);  // [k]
   float* s_a = reinterpret_cast<float*>(s_idx + k);              // [k]
 
   __shared__ float s_q[1][kD];
   __shared__ float s_part[1][kRotParts][kD];
   __shared__ float s_qhat[1][kD];
-  __shared__ SelectSmem<kFusedThreads> s_sel;
+  __shared__ ResidentSelectSmem<kFusedThreads> s_sel;
   __shared__ MergeSmem<kFusedWaves, 1> s_merge;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
   const int h = unit % Hkv;
 
+  LOKI_STAMP(0);
+  resident_select_clear<kFusedThreads>(s_sel);  // covered by the barriers of the next stages
   // ---- qhat = q P_h, all 128 columns ----------------------------------------------------
   rotate_query_block<T, 1, kFusedThreads>(q + (size_t)unit * kD, P + (size_t)h * kD * kD, kD, s_q,
                                           s_part, s_qhat);
 
+  LOKI_STAMP(1);
   // ---- approximate scores over the low-rank slab, into LDS ------------------------------
   {
     const int c = lane % LPR;
@@ -57,15 +68,18 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
                                        [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; });
   }
   __syncthreads();
+  LOKI_STAMP(2);
 
   // ---- top-k in LDS ------------------------------------------------------------------------
   int32_t* gidx = out_idx ? out_idx + (size_t)unit * k : nullptr;
-  block_select_topk<kFusedThreads>(s_score, S, k, s_sel, [&](int rank, int pos) {
+  block_select_topk_resident<kFusedThreads, kFusedKPT>(s_score, S, k, per_thread, s_sel,
+                                                       [&](int rank, int pos) {
     s_idx[rank] = pos;
     s_a[rank] = s_score[pos];
     if (gidx) gidx[rank] = pos;
   });
   __syncthreads();
+  LOKI_STAMP(6);
 
   // ---- exact attention over the selected rows -----------------------------------------------
   const int c = lane % LPRV, rg = lane / LPRV;
@@ -77,16 +91,24 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
   acc.init();
   attend_rows<T, 1, kFusedWaves * RPW, true, REUSE_LO>(acc, qr, ra, s_idx, s_a, wave * RPW + rg, 0,
                                                        k);
+  LOKI_STAMP(7);
   attend_publish<T, 1, kFusedWaves>(acc, s_merge);
   if (tid < kD) {
     float mn, ls, os;
     attend_merged<kFusedWaves, 1>(s_merge, 0, tid, mn, ls, os);
     T::store1(out + (size_t)unit * kD + tid, os / ls);
   }
+  LOKI_STAMP(8);
 }
 
+#ifdef LOKI_PHASE_TIMING
+extern "C" int loki_debug_read_phase_ts(unsigned long long* host_dst, size_t count) {
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(loki::g_phase_ts), count * sizeof(unsigned long long));
+}
+#endif
+
 size_t fused_dynamic_lds(const Shape& s) {
-  return (size_t)((s.S + 63) & ~63) * 4 + (size_t)s.k * 8;
+  return (size_t)kFusedThreads * fused_keys_per_thread(s.S) * 4 + (size_t)s.k * 8;
 }
 
 bool fused_eligible(const Shape& s) {

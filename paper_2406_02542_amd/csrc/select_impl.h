@@ -12,22 +12,32 @@
 
 namespace loki {
 
+constexpr int kSelMaxCand = 1024;  // candidates of the threshold bin ranked directly (<= 2048 / 2)
+
 template <int THREADS>
 struct SelectSmem {
   static constexpr int kWaves = THREADS / 64;
-  uint32_t hist[2048];
+  uint32_t hist[2048];  // digit histogram; its first kSelMaxCand words later hold the candidates
   uint32_t wave[kWaves];
   uint32_t out[2];
+  uint32_t ncand;
   uint32_t cnt[2][kWaves][2];
 };
 
+template <int CTRL, int ROW_MASK, bool BOUND_CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, BOUND_CTRL);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave, all in DPP: a shift-and-add scan inside
+// each row of 16 lanes, then the row totals are carried into the following rows.
 __device__ __forceinline__ uint32_t wave_inclusive_scan_u32(uint32_t x) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(x, o);
-    if (lane >= o) x += y;
-  }
+  x += dpp_u32<0x111, 0xf, true>(x);   // row_shr:1, zero shifted in
+  x += dpp_u32<0x112, 0xf, true>(x);   // row_shr:2
+  x += dpp_u32<0x114, 0xf, true>(x);   // row_shr:4
+  x += dpp_u32<0x118, 0xf, true>(x);   // row_shr:8
+  x += dpp_u32<0x142, 0xa, false>(x);  // row_bcast:15 into rows 1 and 3
+  x += dpp_u32<0x143, 0xc, false>(x);  // row_bcast:31 into rows 2 and 3
   return x;
 }
 
@@ -135,6 +145,191 @@ __device__ __forceinline__ void block_select_topk(const float* a, int S, int k,
     base_gt += tgt;
     base_eq += teq;
   }
+}
+
+// Same selection for a score array that lives in LDS and is small enough for every thread to
+// keep its keys in registers: thread t owns the C consecutive positions starting at t*C,
+// C = per_thread <= KPT, C a multiple of 4; `a` must have THREADS*C readable floats (values
+// at positions >= S are ignored).  Two histogram passes (11 + 11 bits) run on the register
+// keys, the second one only over the keys of the first pass's threshold bin; the handful of
+// keys that still share all 22 leading bits with the threshold are ranked against each other
+// directly (a third, 10-bit pass replaces the ranking if there are more than kSelMaxRank of
+// them, e.g. many equal scores).  The compaction is one block-wide exclusive scan of
+// per-thread counts.  emit(rank, pos) as in block_select_topk.
+//
+// resident_select_clear() zeroes both histograms; the caller runs it any time before the
+// call (with a barrier in between), e.g. ahead of the scoring loop whose closing barrier
+// then covers it.
+constexpr int kSelMaxRank = 64;
+
+template <int THREADS>
+struct ResidentSelectSmem {
+  static constexpr int kWaves = THREADS / 64;
+  uint32_t hist[2][2048];
+  uint32_t wave[2][kWaves];
+  uint32_t out[2][2];
+  uint32_t ncand;
+  uint32_t cand[kSelMaxRank];
+};
+
+template <int THREADS>
+__device__ __forceinline__ void resident_select_clear(ResidentSelectSmem<THREADS>& sm) {
+  for (int i = threadIdx.x; i < 2 * 2048; i += THREADS) (&sm.hist[0][0])[i] = 0u;
+  if (threadIdx.x == 0) sm.ncand = 0u;
+}
+
+// As find_threshold_bin, on histogram `which` (2048 bins).  One barrier inside, one at the end.
+template <int THREADS>
+__device__ __forceinline__ void resident_find_bin(ResidentSelectSmem<THREADS>& sm, int which,
+                                                  uint32_t rem) {
+  constexpr int kWaves = THREADS / 64;
+  constexpr int BPT = 2048 / THREADS;
+  static_assert(BPT >= 1, "at most 2048 threads");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int top = 2047 - BPT * tid;
+  uint32_t cbin[BPT];
+  uint32_t c = 0;
+#pragma unroll
+  for (int i = 0; i < BPT; ++i) {
+    cbin[i] = sm.hist[which][top - i];
+    c += cbin[i];
+  }
+  uint32_t incl = wave_inclusive_scan_u32(c);
+  if (lane == 63) sm.wave[which][wave] = incl;
+  __syncthreads();
+  uint32_t off = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t t = sm.wave[which][w];
+    off += (w < wave) ? t : 0u;
+  }
+  incl += off;
+  uint32_t excl = incl - c;
+  if (excl < rem && rem <= incl) {
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) {
+      if (excl < rem && rem <= excl + cbin[i]) {
+        sm.out[which][0] = (uint32_t)(top - i);
+        sm.out[which][1] = rem - excl;
+      }
+      excl += cbin[i];
+    }
+  }
+  __syncthreads();
+}
+
+template <int THREADS, int KPT, typename Emit>
+__device__ __forceinline__ void block_select_topk_resident(const float* a, int S, int k,
+                                                           int per_thread,
+                                                           ResidentSelectSmem<THREADS>& sm,
+                                                           Emit emit) {
+  constexpr int kWaves = THREADS / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = per_thread;
+  const int p0 = tid * C;
+
+  uint32_t key[KPT];
+#pragma unroll
+  for (int i = 0; i < KPT; i += 4) {
+    if (i < C) {
+      const float4 f = *reinterpret_cast<const float4*>(a + p0 + i);
+      key[i + 0] = float_to_key(f.x);
+      key[i + 1] = float_to_key(f.y);
+      key[i + 2] = float_to_key(f.z);
+      key[i + 3] = float_to_key(f.w);
+    } else {
+      key[i + 0] = key[i + 1] = key[i + 2] = key[i + 3] = 0u;
+    }
+  }
+  // valid(i): position p0 + i is a live row
+#define LOKI_SEL_VALID(i) ((i) < C && p0 + (i) < S)
+
+  // pass 1: bits 31..21 of every key
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if (LOKI_SEL_VALID(i)) atomicAdd(&sm.hist[0][key[i] >> 21], 1u);
+  __syncthreads();
+  resident_find_bin<THREADS>(sm, 0, (uint32_t)k);
+  const uint32_t bin1 = sm.out[0][0];
+  LOKI_STAMP(3);
+
+  // pass 2: bits 20..10 of the keys inside the threshold bin
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if (LOKI_SEL_VALID(i) && (key[i] >> 21) == bin1) atomicAdd(&sm.hist[1][(key[i] >> 10) & 2047u], 1u);
+  __syncthreads();
+  resident_find_bin<THREADS>(sm, 1, sm.out[0][1]);
+  const uint32_t top22 = (bin1 << 11) | sm.out[1][0];
+  uint32_t rem = sm.out[1][1];
+
+  // the keys that share all 22 leading bits with the threshold
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if (LOKI_SEL_VALID(i) && (key[i] >> 10) == top22) {
+      const uint32_t slot = atomicAdd(&sm.ncand, 1u);
+      if (slot < (uint32_t)kSelMaxRank) sm.cand[slot] = key[i];
+    }
+  __syncthreads();
+  const uint32_t ncand = sm.ncand;
+  uint32_t T, need_eq;
+  if (ncand <= (uint32_t)kSelMaxRank) {
+    // T is the candidate with (#greater < rem <= #greater + #equal) among the candidates
+    if (tid < (int)ncand) {
+      const uint32_t ki = sm.cand[tid];
+      uint32_t gt = 0, eq = 0;
+      for (uint32_t j = 0; j < ncand; ++j) {
+        const uint32_t kj = sm.cand[j];
+        gt += kj > ki;
+        eq += kj == ki;
+      }
+      if (gt < rem && rem <= gt + eq) {
+        sm.out[0][0] = ki;
+        sm.out[0][1] = rem - gt;
+      }
+    }
+    __syncthreads();
+    T = sm.out[0][0];
+    need_eq = sm.out[0][1];
+  } else {
+    // many keys agree on 22 bits (e.g. equal scores): resolve bits 9..0 with a third pass,
+    // reusing histogram 0 (everyone is past its last read: two barriers ago)
+    for (int i = tid; i < 2048; i += THREADS) sm.hist[0][i] = 0u;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < KPT; ++i)
+      if (LOKI_SEL_VALID(i) && (key[i] >> 10) == top22) atomicAdd(&sm.hist[0][1024u + (key[i] & 1023u)], 1u);
+    __syncthreads();
+    resident_find_bin<THREADS>(sm, 0, rem);   // bins 1024..2047 hold the 10-bit digit
+    T = (top22 << 10) | (sm.out[0][0] - 1024u);
+    need_eq = sm.out[0][1];
+  }
+  LOKI_STAMP(4);
+
+  // compaction: per-thread counts, one block-wide exclusive scan (greater in the low half-word,
+  // equal in the high half-word: both totals are <= S <= 65535)
+  uint32_t mine = 0;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if (LOKI_SEL_VALID(i)) mine += (key[i] > T ? 1u : 0u) + (key[i] == T ? 0x10000u : 0u);
+  const uint32_t incl = wave_inclusive_scan_u32(mine);
+  if (lane == 63) sm.wave[0][wave] = incl;   // last read of wave[0] was before >= 2 barriers
+  __syncthreads();
+  uint32_t before = incl - mine;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t t = sm.wave[0][w];
+    before += (w < wave) ? t : 0u;
+  }
+  uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
+#pragma unroll
+  for (int i = 0; i < KPT; ++i)
+    if (LOKI_SEL_VALID(i)) {
+      const bool gt = key[i] > T, eq = key[i] == T;
+      if (gt || (eq && eq_before < need_eq)) emit((int)(gt_before + min(eq_before, need_eq)), p0 + i);
+      gt_before += gt;
+      eq_before += eq;
+    }
+#undef LOKI_SEL_VALID
 }
 
 }  // namespace loki

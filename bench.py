@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="llama2_7b")
     ap.add_argument("--select-mode", type=int, default=0)
-    ap.add_argument("--copies", type=int, default=3, help="KV-cache copies cycled through")
+    ap.add_argument("--copies", type=int, default=4, help="KV-cache copies cycled through")
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto",
@@ -147,8 +147,15 @@ def main():
         api.dense_decode_attn(lay, q, kf, v, w.S, wsd, out, stream)
 
     def timed(step_fn, steps, warmup):
-        for i in range(warmup):
+        # untimed: at least `warmup` steps and at least ~50 ms of work, so that clocks have
+        # settled before the timed region starts
+        t_w = time.perf_counter()
+        i = 0
+        while i < warmup or time.perf_counter() - t_w < 0.05:
             step_fn(i)
+            i += 1
+            if i % 50 == 0:
+                torch.cuda.synchronize()
         torch.cuda.synchronize()
         t = time.perf_counter()
         for i in range(steps):

@@ -17,7 +17,10 @@
 
 namespace loki {
 
-constexpr int kRowsInFlight = 4;        // rows per lane group per loop trip
+#ifndef LOKI_ROWS_IN_FLIGHT
+#define LOKI_ROWS_IN_FLIGHT 4
+#endif
+constexpr int kRowsInFlight = LOKI_ROWS_IN_FLIGHT;  // rows per lane group per loop trip
 constexpr int kPartialStride = kD + 2;  // o[128], m, l
 constexpr float kSoftmaxScaleLog2 = kLog2e * 0.08838834764831845f;  // log2(e) / sqrt(128)
 

@@ -46,7 +46,19 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
   const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
   const int h = unit % Hkv;
 
+#ifdef LOKI_STAGGER_TICKS
+  if (blockIdx.x >= gridDim.x / 2) {
+    const unsigned long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < LOKI_STAGGER_TICKS) __builtin_amdgcn_s_sleep(8);
+  }
+#endif
   LOKI_STAMP(0);
+#ifdef LOKI_PHASE_TIMING
+  if (threadIdx.x == 0 && blockIdx.x < 8192) {
+    g_phase_ts[blockIdx.x * kPhaseSlots + 9] = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID
+    g_phase_ts[blockIdx.x * kPhaseSlots + 10] = __builtin_amdgcn_s_getreg((31 << 11) | 20);  // XCC_ID
+  }
+#endif
   resident_select_clear<kFusedThreads>(s_sel);  // covered by the barriers of the next stages
   // ---- qhat = q P_h, all 128 columns ----------------------------------------------------
   rotate_query_block<T, 1, kFusedThreads>(q + (size_t)unit * kD, P + (size_t)h * kD * kD, kD, s_q,

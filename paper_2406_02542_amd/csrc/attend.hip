@@ -96,20 +96,41 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
 }
 
 // Merges the nsplit partial results of each query head: out = sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).
+// Loads are issued in independent batches of 8 splits so that the merge costs a few memory
+// round trips, not one per split.
 template <typename T>
 __global__ __launch_bounds__(kD) void combine_kernel(const float* __restrict__ partial,
                                                      typename T::store_t* __restrict__ out,
                                                      int nsplit) {
+  constexpr int B8 = 8;
   const size_t head = blockIdx.x;
   const int col = threadIdx.x;
   const float* pr = partial + head * nsplit * kPartialStride;
   float mn = kNegBig;
-  for (int i = 0; i < nsplit; ++i) mn = fmaxf(mn, pr[i * kPartialStride + kD]);
+  for (int i0 = 0; i0 < nsplit; i0 += B8) {
+    float mi[B8];
+#pragma unroll
+    for (int u = 0; u < B8; ++u) mi[u] = (i0 + u < nsplit) ? pr[(i0 + u) * kPartialStride + kD] : kNegBig;
+#pragma unroll
+    for (int u = 0; u < B8; ++u) mn = fmaxf(mn, mi[u]);
+  }
   float ls = 0.f, os = 0.f;
-  for (int i = 0; i < nsplit; ++i) {
-    const float f = fast_exp2(pr[i * kPartialStride + kD] - mn);
-    ls = fmaf(pr[i * kPartialStride + kD + 1], f, ls);
-    os = fmaf(pr[i * kPartialStride + col], f, os);
+  for (int i0 = 0; i0 < nsplit; i0 += B8) {
+    float mi[B8], li[B8], oi[B8];
+#pragma unroll
+    for (int u = 0; u < B8; ++u) {
+      const bool ok = i0 + u < nsplit;
+      const float* p = pr + (ok ? (i0 + u) : 0) * kPartialStride;
+      mi[u] = ok ? p[kD] : kNegBig;
+      li[u] = ok ? p[kD + 1] : 0.f;
+      oi[u] = ok ? p[col] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < B8; ++u) {
+      const float f = fast_exp2(mi[u] - mn);
+      ls = fmaf(li[u], f, ls);
+      os = fmaf(oi[u], f, os);
+    }
   }
   T::store1(out + head * kD + col, os / ls);
 }

@@ -105,4 +105,10 @@ __device__ inline uint32_t float_to_key(float a) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+
+// Inverse of float_to_key (up to the sign of zero).
+__device__ inline float key_to_float(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k ^ 0x80000000u) : ~k);
+}
+
 }  // namespace loki

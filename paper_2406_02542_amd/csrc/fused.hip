@@ -85,9 +85,9 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
   // ---- top-k in LDS ------------------------------------------------------------------------
   int32_t* gidx = out_idx ? out_idx + (size_t)unit * k : nullptr;
   block_select_topk_resident<kFusedThreads, kFusedKPT>(s_score, S, k, per_thread, s_sel,
-                                                       [&](int rank, int pos) {
+                                                       [&](int rank, int pos, float score) {
     s_idx[rank] = pos;
-    s_a[rank] = s_score[pos];
+    s_a[rank] = score;
     if (gidx) gidx[rank] = pos;
   });
   __syncthreads();

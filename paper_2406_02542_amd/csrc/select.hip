@@ -1,31 +1,258 @@
-// Per-head top-k selection (Algorithm 1 line 6 of arXiv 2406.02542) as a stand-alone kernel:
-// one 1024-thread block per selecting head reads that head's approximate scores and writes
-// the k selected positions (ascending) together with their scores, which the attention
-// stage reuses as the low-rank part of the exact logits.
+// Per-head top-k selection (Algorithm 1 line 6 of arXiv 2406.02542) as stand-alone kernels:
+// one block per selecting head reads that head's approximate scores and writes the k selected
+// positions (ascending) together with their scores, which the attention stage reuses as the
+// low-rank part of the exact logits.
+//
+//   S <= 16384: select_resident_kernel — every thread keeps its keys in registers
+//               (select_impl.h), one read of the scores.
+//   larger S:   select_stream_kernel — the scores are streamed four times by one block
+//               (histogram of the leading 11 bits; collect the keys of the threshold bin into
+//               LDS and resolve the exact threshold among them; count; ordered write), each
+//               wave owning a contiguous range so that the ordered write needs no barrier.
 #include "select_impl.h"
 
 namespace loki {
 
-constexpr int kSelThreads = 1024;
+constexpr int kSelKPT = 16;
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ scores,
-                                                             int32_t* __restrict__ sel_idx,
-                                                             float* __restrict__ sel_score, int S,
-                                                             int k) {
-  __shared__ SelectSmem<kSelThreads> sm;
+// Second launch bound: 8 waves per SIMD, i.e. at most 64 VGPRs, so that two 1024-thread blocks
+// (or four 512-thread blocks) share a CU and overlap each other's barrier and LDS latencies.
+template <int THREADS>
+__global__ __launch_bounds__(THREADS, 8) void select_resident_kernel(const float* __restrict__ scores,
+                                                                  int32_t* __restrict__ sel_idx,
+                                                                  float* __restrict__ sel_score,
+                                                                  int S, int k, int per_thread) {
+  __shared__ ResidentSelectSmem<THREADS> sm;
   const float* a = scores + (size_t)blockIdx.x * S;
   int32_t* out = sel_idx + (size_t)blockIdx.x * k;
   float* outs = sel_score + (size_t)blockIdx.x * k;
-  block_select_topk<kSelThreads>(a, S, k, sm, [&](int rank, int pos) {
-    out[rank] = pos;
-    outs[rank] = a[pos];
-  });
+  LOKI_STAMP(0);
+  resident_select_clear<THREADS>(sm);
+  __syncthreads();
+  block_select_topk_resident<THREADS, kSelKPT>(a, S, k, per_thread, sm,
+                                               [&](int rank, int pos, float score) {
+                                                 out[rank] = pos;
+                                                 outs[rank] = score;
+                                               });
 }
+
+constexpr int kStreamThreads = 1024;
+constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kStreamMaxCand = kStreamThreads * kSelKPT;  // 16384 keys = 64 KiB of LDS
+constexpr int kStreamTile = 256;                          // positions a wave covers per load
+constexpr int kStreamUnroll = 4;                          // loads a lane keeps in flight
+
+union StreamScratch {
+  uint32_t cand[kStreamMaxCand];
+  SelectSmem<kStreamThreads> generic;  // only used when the threshold bin overflows `cand`
+};
+
+template <bool VEC4>
+__global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
+    const float* __restrict__ scores, int32_t* __restrict__ sel_idx, float* __restrict__ sel_score,
+    int S, int k) {
+  __shared__ ResidentSelectSmem<kStreamThreads> sm;
+  __shared__ StreamScratch scratch;
+  __shared__ uint32_t s_wcnt[kStreamWaves][2];
+  __shared__ uint32_t s_ncand;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float* a = scores + (size_t)blockIdx.x * S;
+  int32_t* out = sel_idx + (size_t)blockIdx.x * k;
+  float* outs = sel_score + (size_t)blockIdx.x * k;
+
+  // wave w owns positions [w0, w1), a whole number of tiles
+  const int per_wave =
+      ((S + kStreamWaves * kStreamTile - 1) / (kStreamWaves * kStreamTile)) * kStreamTile;
+  const int w0 = min(S, wave * per_wave), w1 = min(S, w0 + per_wave);
+
+  auto load4 = [&](int pos, float (&f)[4], bool (&ok)[4]) {
+    if (VEC4) {  // S % 4 == 0: the head's base and pos are 16-byte aligned, pos + 3 < S
+      const bool in = pos < w1;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (in) v = *reinterpret_cast<const float4*>(a + pos);
+      f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+      ok[0] = ok[1] = ok[2] = ok[3] = in;
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        ok[j] = pos + j < w1;
+        f[j] = ok[j] ? a[pos + j] : 0.f;
+      }
+    }
+  };
+
+  LOKI_STAMP(0);
+  resident_select_clear<kStreamThreads>(sm);
+  if (tid == 0) s_ncand = 0u;
+  __syncthreads();
+
+  // pass 1: histogram of key bits 31..21
+  for (int tile = w0; tile < w1; tile += kStreamTile * kStreamUnroll) {
+    float f[kStreamUnroll][4];
+    bool ok[kStreamUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) load4(tile + u * kStreamTile + lane * 4, f[u], ok[u]);
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (ok[u][j]) atomicAdd(&sm.hist[0][float_to_key(f[u][j]) >> 21], 1u);
+  }
+  __syncthreads();
+  resident_find_bin<kStreamThreads>(sm, 0, (uint32_t)k);
+  const uint32_t bin1 = sm.out[0][0];
+  const uint32_t rem1 = sm.out[0][1];
+  LOKI_STAMP(1);
+
+  // pass 2: collect the keys of the threshold bin
+  for (int tile = w0; tile < w1; tile += kStreamTile * kStreamUnroll) {
+    float f[kStreamUnroll][4];
+    bool ok[kStreamUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) load4(tile + u * kStreamTile + lane * 4, f[u], ok[u]);
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = float_to_key(f[u][j]);
+        if (ok[u][j] && (key >> 21) == bin1) {
+          const uint32_t slot = atomicAdd(&s_ncand, 1u);
+          if (slot < (uint32_t)kStreamMaxCand) scratch.cand[slot] = key;
+        }
+      }
+  }
+  __syncthreads();
+  LOKI_STAMP(2);
+  const uint32_t ncand = s_ncand;
+  if (ncand > (uint32_t)kStreamMaxCand) {
+    // the threshold bin does not fit (e.g. a long run of equal scores): plain digit passes
+    __syncthreads();
+    block_select_topk<kStreamThreads>(a, S, k, scratch.generic, [&](int rank, int pos) {
+      out[rank] = pos;
+      outs[rank] = a[pos];
+    });
+    return;
+  }
+
+  // exact threshold among the candidates: they agree on the leading 11 bits, so rank them on
+  // the remaining 21, moved to the top of the word
+  uint32_t T, need_eq;
+  {
+    for (int i = tid; i < 2048; i += kStreamThreads) sm.hist[0][i] = 0u;
+    int C = ((int)ncand + kStreamThreads - 1) / kStreamThreads;
+    C = (C + 3) & ~3;
+    uint32_t ck[kSelKPT];
+    uint32_t valid_mask = 0;
+#pragma unroll
+    for (int i = 0; i < kSelKPT; ++i) {
+      const uint32_t p = (uint32_t)(tid * C + i);
+      const bool v = i < C && p < ncand;
+      ck[i] = v ? (scratch.cand[p] << 11) : 0u;
+      valid_mask |= (v ? 1u : 0u) << i;
+    }
+    __syncthreads();
+    uint32_t Tp;
+    resident_threshold<kStreamThreads, kSelKPT>(ck, valid_mask, rem1, sm, Tp, need_eq);
+    T = (bin1 << 21) | (Tp >> 11);
+  }
+  LOKI_STAMP(3);
+
+  // pass 3: how many selected rows precede each wave's range
+  uint32_t cg = 0, ce = 0;
+  for (int tile = w0; tile < w1; tile += kStreamTile * kStreamUnroll) {
+    float f[kStreamUnroll][4];
+    bool ok[kStreamUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) load4(tile + u * kStreamTile + lane * 4, f[u], ok[u]);
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = float_to_key(f[u][j]);
+        cg += (ok[u][j] && key > T) ? 1u : 0u;
+        ce += (ok[u][j] && key == T) ? 1u : 0u;
+      }
+  }
+  cg = wave_inclusive_scan_u32(cg);
+  ce = wave_inclusive_scan_u32(ce);
+  if (lane == 63) {
+    s_wcnt[wave][0] = cg;
+    s_wcnt[wave][1] = ce;
+  }
+  __syncthreads();
+  uint32_t run_g = 0, run_e = 0;
+#pragma unroll
+  for (int w = 0; w < kStreamWaves; ++w) {
+    const uint32_t tg = s_wcnt[w][0], te = s_wcnt[w][1];
+    run_g += (w < wave) ? tg : 0u;
+    run_e += (w < wave) ? te : 0u;
+  }
+  LOKI_STAMP(5);
+
+  // pass 4: ordered write; inside a tile, lane l holds positions tile + 4l .. 4l+3
+  for (int tile0 = w0; tile0 < w1; tile0 += kStreamTile * kStreamUnroll) {
+    float f[kStreamUnroll][4];
+    bool ok[kStreamUnroll][4];
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) load4(tile0 + u * kStreamTile + lane * 4, f[u], ok[u]);
+#pragma unroll
+    for (int u = 0; u < kStreamUnroll; ++u) {
+      const int pos = tile0 + u * kStreamTile + lane * 4;
+      bool gt[4], eq[4];
+      uint32_t mine = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t key = float_to_key(f[u][j]);
+        gt[j] = ok[u][j] && key > T;
+        eq[j] = ok[u][j] && key == T;
+        mine += (gt[j] ? 1u : 0u) + (eq[j] ? 0x10000u : 0u);
+      }
+      const uint32_t incl = wave_inclusive_scan_u32(mine);  // per tile at most 256 of each kind
+      const uint32_t excl = incl - mine;
+      uint32_t g_before = run_g + (excl & 0xffffu), e_before = run_e + (excl >> 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        if (gt[j] || (eq[j] && e_before < need_eq)) {
+          const uint32_t rank = g_before + min(e_before, need_eq);
+          out[rank] = pos + j;
+          outs[rank] = f[u][j];
+        }
+        g_before += gt[j] ? 1u : 0u;
+        e_before += eq[j] ? 1u : 0u;
+      }
+      const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+      run_g += tot & 0xffffu;
+      run_e += tot >> 16;
+    }
+  }
+  LOKI_STAMP(6);
+}
+
+#ifdef LOKI_PHASE_TIMING
+extern "C" int loki_debug_read_select_ts(unsigned long long* host_dst, size_t count) {
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(loki::g_phase_ts),
+                                  count * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
                          float* sel_score, hipStream_t st) {
-  hipLaunchKernelGGL(select_kernel, dim3(n_sel_heads), dim3(kSelThreads), 0, st, scores, sel_idx,
-                     sel_score, s.S, s.k);
+  if (s.S <= 512 * kSelKPT) {
+    const int per_thread = (((s.S + 511) / 512) + 3) & ~3;
+    hipLaunchKernelGGL(select_resident_kernel<512>, dim3(n_sel_heads), dim3(512), 0, st, scores,
+                       sel_idx, sel_score, s.S, s.k, per_thread);
+  } else if (s.S <= 1024 * kSelKPT) {
+    const int per_thread = (((s.S + 1023) / 1024) + 3) & ~3;
+    hipLaunchKernelGGL(select_resident_kernel<1024>, dim3(n_sel_heads), dim3(1024), 0, st, scores,
+                       sel_idx, sel_score, s.S, s.k, per_thread);
+  } else if (s.S % 4 == 0) {
+    hipLaunchKernelGGL(select_stream_kernel<true>, dim3(n_sel_heads), dim3(kStreamThreads), 0, st,
+                       scores, sel_idx, sel_score, s.S, s.k);
+  } else {
+    hipLaunchKernelGGL(select_stream_kernel<false>, dim3(n_sel_heads), dim3(kStreamThreads), 0, st,
+                       scores, sel_idx, sel_score, s.S, s.k);
+  }
   return hipGetLastError();
 }
 

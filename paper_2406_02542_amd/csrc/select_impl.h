@@ -147,15 +147,15 @@ __device__ __forceinline__ void block_select_topk(const float* a, int S, int k,
   }
 }
 
-// Same selection for a score array that lives in LDS and is small enough for every thread to
-// keep its keys in registers: thread t owns the C consecutive positions starting at t*C,
-// C = per_thread <= KPT, C a multiple of 4; `a` must have THREADS*C readable floats (values
-// at positions >= S are ignored).  Two histogram passes (11 + 11 bits) run on the register
+// Same selection for a score array (LDS or global) small enough for every thread to keep its
+// keys in registers: C = per_thread <= KPT keys each, C a multiple of 4, THREADS*C >= S
+// (nothing at or past S is read).  Two histogram passes (11 + 11 bits) run on the register
 // keys, the second one only over the keys of the first pass's threshold bin; the handful of
 // keys that still share all 22 leading bits with the threshold are ranked against each other
 // directly (a third, 10-bit pass replaces the ranking if there are more than kSelMaxRank of
 // them, e.g. many equal scores).  The compaction is one block-wide exclusive scan of
-// per-thread counts.  emit(rank, pos) as in block_select_topk.
+// per-thread counts.  emit(rank, pos, score) is called exactly k times,
+// rank in [0, k) ascending with pos.
 //
 // resident_select_clear() zeroes both histograms; the caller runs it any time before the
 // call (with a barrier in between), e.g. ahead of the scoring loop whose closing barrier
@@ -218,40 +218,24 @@ __device__ __forceinline__ void resident_find_bin(ResidentSelectSmem<THREADS>& s
   __syncthreads();
 }
 
-template <int THREADS, int KPT, typename Emit>
-__device__ __forceinline__ void block_select_topk_resident(const float* a, int S, int k,
-                                                           int per_thread,
-                                                           ResidentSelectSmem<THREADS>& sm,
-                                                           Emit emit) {
-  constexpr int kWaves = THREADS / 64;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int C = per_thread;
-  const int p0 = tid * C;
-
-  uint32_t key[KPT];
-#pragma unroll
-  for (int i = 0; i < KPT; i += 4) {
-    if (i < C) {
-      const float4 f = *reinterpret_cast<const float4*>(a + p0 + i);
-      key[i + 0] = float_to_key(f.x);
-      key[i + 1] = float_to_key(f.y);
-      key[i + 2] = float_to_key(f.z);
-      key[i + 3] = float_to_key(f.w);
-    } else {
-      key[i + 0] = key[i + 1] = key[i + 2] = key[i + 3] = 0u;
-    }
-  }
-  // valid(i): position p0 + i is a live row
-#define LOKI_SEL_VALID(i) ((i) < C && p0 + (i) < S)
-
+// Exact threshold of the rem-th largest of the block's register-resident keys: returns the
+// key T and how many keys equal to T are needed (need_eq >= 1).  valid_mask bit i says whether
+// key[i] takes part.  Both histograms and sm.ncand must be clear on entry (see
+// resident_select_clear) and every thread must be past any earlier use of sm.
+template <int THREADS, int KPT>
+__device__ __forceinline__ void resident_threshold(const uint32_t (&key)[KPT], uint32_t valid_mask,
+                                                   uint32_t rem_in, ResidentSelectSmem<THREADS>& sm,
+                                                   uint32_t& T, uint32_t& need_eq) {
+  const int tid = threadIdx.x;
+#define LOKI_SEL_VALID(i) ((valid_mask >> (i)) & 1u)
   // pass 1: bits 31..21 of every key
 #pragma unroll
   for (int i = 0; i < KPT; ++i)
     if (LOKI_SEL_VALID(i)) atomicAdd(&sm.hist[0][key[i] >> 21], 1u);
   __syncthreads();
-  resident_find_bin<THREADS>(sm, 0, (uint32_t)k);
+  resident_find_bin<THREADS>(sm, 0, rem_in);
   const uint32_t bin1 = sm.out[0][0];
-  LOKI_STAMP(3);
+  LOKI_STAMP(13);
 
   // pass 2: bits 20..10 of the keys inside the threshold bin
 #pragma unroll
@@ -260,7 +244,8 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
   __syncthreads();
   resident_find_bin<THREADS>(sm, 1, sm.out[0][1]);
   const uint32_t top22 = (bin1 << 11) | sm.out[1][0];
-  uint32_t rem = sm.out[1][1];
+  const uint32_t rem = sm.out[1][1];
+  LOKI_STAMP(14);
 
   // the keys that share all 22 leading bits with the threshold
 #pragma unroll
@@ -271,7 +256,6 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
     }
   __syncthreads();
   const uint32_t ncand = sm.ncand;
-  uint32_t T, need_eq;
   if (ncand <= (uint32_t)kSelMaxRank) {
     // T is the candidate with (#greater < rem <= #greater + #equal) among the candidates
     if (tid < (int)ncand) {
@@ -303,33 +287,102 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
     T = (top22 << 10) | (sm.out[0][0] - 1024u);
     need_eq = sm.out[0][1];
   }
+#undef LOKI_SEL_VALID
+}
+
+// The block's positions are laid out wave by wave: wave w owns the 64*C consecutive positions
+// from w*64*C in tiles of 256, and inside a tile lane l holds the 4 positions from 4l — one
+// coalesced 16-byte load per lane and tile, and a position order (wave, tile, lane, element)
+// that the compaction can follow with per-tile DPP scans and a single barrier.
+template <int THREADS, int KPT, typename Emit>
+__device__ __forceinline__ void block_select_topk_resident(const float* a, int S, int k,
+                                                           int per_thread,
+                                                           ResidentSelectSmem<THREADS>& sm,
+                                                           Emit emit) {
+  constexpr int kWaves = THREADS / 64;
+  constexpr int kTiles = KPT / 4;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = per_thread;
+  const int wbase = wave * 64 * C + lane * 4;  // position of key[0]; key[4j + e] sits at +256j + e
+  const bool aligned = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
+
+  uint32_t key[KPT];
+  uint32_t valid_mask = 0;
+#pragma unroll
+  for (int j = 0; j < kTiles; ++j) {
+    const int i = 4 * j;
+    const int p = wbase + 256 * j;
+    key[i + 0] = key[i + 1] = key[i + 2] = key[i + 3] = 0u;
+    if (i < C) {
+      if (aligned && p + 3 < S) {
+        const float4 f = *reinterpret_cast<const float4*>(a + p);
+        key[i + 0] = float_to_key(f.x);
+        key[i + 1] = float_to_key(f.y);
+        key[i + 2] = float_to_key(f.z);
+        key[i + 3] = float_to_key(f.w);
+        valid_mask |= 0xfu << i;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (p + e < S) {
+            key[i + e] = float_to_key(a[p + e]);
+            valid_mask |= 1u << (i + e);
+          }
+      }
+    }
+  }
+
+  LOKI_STAMP(11);
+  uint32_t T, need_eq;
+  resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, sm, T, need_eq);
   LOKI_STAMP(4);
 
-  // compaction: per-thread counts, one block-wide exclusive scan (greater in the low half-word,
-  // equal in the high half-word: both totals are <= S <= 65535)
-  uint32_t mine = 0;
+  // compaction: per tile a DPP exclusive scan over the lanes (greater in the low half-word,
+  // equal in the high half-word: a wave holds at most 64*KPT <= 65535 keys), then one
+  // barrier to learn how many selected rows the earlier waves hold.  For the block-wide sums
+  // the two counts travel separately (S may exceed 65535).
+  uint32_t excl[kTiles];
+  uint32_t wave_g = 0, wave_e = 0;
 #pragma unroll
-  for (int i = 0; i < KPT; ++i)
-    if (LOKI_SEL_VALID(i)) mine += (key[i] > T ? 1u : 0u) + (key[i] == T ? 0x10000u : 0u);
-  const uint32_t incl = wave_inclusive_scan_u32(mine);
-  if (lane == 63) sm.wave[0][wave] = incl;   // last read of wave[0] was before >= 2 barriers
+  for (int j = 0; j < kTiles; ++j) {
+    uint32_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((valid_mask >> (4 * j + e)) & 1u)
+        mine += (key[4 * j + e] > T ? 1u : 0u) + (key[4 * j + e] == T ? 0x10000u : 0u);
+    const uint32_t incl = wave_inclusive_scan_u32(mine);
+    const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    excl[j] = ((wave_g + ((incl - mine) & 0xffffu)) & 0xffffu) | ((wave_e + ((incl - mine) >> 16)) << 16);
+    wave_g += tot & 0xffffu;
+    wave_e += tot >> 16;
+  }
+  if (lane == 0) {
+    sm.wave[0][wave] = wave_g;   // last reads of wave[0] / wave[1] are >= 2 barriers back
+    sm.wave[1][wave] = wave_e;
+  }
   __syncthreads();
-  uint32_t before = incl - mine;
+  uint32_t before_g = 0, before_e = 0;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
-    const uint32_t t = sm.wave[0][w];
-    before += (w < wave) ? t : 0u;
+    const uint32_t tg = sm.wave[0][w], te = sm.wave[1][w];
+    before_g += (w < wave) ? tg : 0u;
+    before_e += (w < wave) ? te : 0u;
   }
-  uint32_t gt_before = before & 0xffffu, eq_before = before >> 16;
 #pragma unroll
-  for (int i = 0; i < KPT; ++i)
-    if (LOKI_SEL_VALID(i)) {
-      const bool gt = key[i] > T, eq = key[i] == T;
-      if (gt || (eq && eq_before < need_eq)) emit((int)(gt_before + min(eq_before, need_eq)), p0 + i);
-      gt_before += gt;
-      eq_before += eq;
-    }
-#undef LOKI_SEL_VALID
+  for (int j = 0; j < kTiles; ++j) {
+    uint32_t g_before = before_g + (excl[j] & 0xffffu), e_before = before_e + (excl[j] >> 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((valid_mask >> (4 * j + e)) & 1u) {
+        const uint32_t kk = key[4 * j + e];
+        const bool gt = kk > T, eq = kk == T;
+        if (gt || (eq && e_before < need_eq))
+          emit((int)(g_before + min(e_before, need_eq)), wbase + 256 * j + e, key_to_float(kk));
+        g_before += gt;
+        e_before += eq;
+      }
+  }
+  LOKI_STAMP(12);
 }
 
 }  // namespace loki

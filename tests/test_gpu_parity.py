@@ -119,6 +119,39 @@ def test_single_kernel_path_limits():
         check_loki(case, 0)  # the default route still works
 
 
+@pytest.mark.parametrize("S,k,G", [
+    (8193, 700, 1),      # just past the one-kernel limit: 1024-thread register-resident select
+    (16384, 2048, 2),
+    (16385, 1000, 1),    # first size of the streaming select, S % 4 != 0
+    (20000, 1250, 4),
+    (50001, 3000, 1),
+    (70000, 35000, 2),   # half of everything selected
+])
+def test_long_sequences(S, k, G):
+    w, x = _case(f"long_{S}", 1, 2 * G, 2, S, "bf16", 16, k, seed=3700 + S)
+    say(f"case {w}")
+    case = DeviceCase(w, x)
+    for mode in ((0, 1) if G > 1 else (0,)):
+        say(f"mode {mode} {check_loki(case, mode)}")
+
+
+def test_long_sequence_with_massive_ties():
+    """S = 40000 with an all-zero cache and with only 7 distinct key rows: the threshold bin
+    overflows every candidate buffer, the plain digit passes must take over."""
+    w, x = _case("long_ties", 1, 2, 2, 40000, "f32", 32, 17001, seed=3800)
+    x0 = dict(x)
+    x0["khat"] = np.zeros_like(x["khat"])
+    out, idx = DeviceCase(w, x0).run_loki(0)
+    for h in range(2):
+        assert idx[0, h].tolist() == list(range(17001))
+    x7 = dict(x)
+    x7["khat"] = np.tile(x["khat"][:, :, :7, :], (1, 1, 40000 // 7 + 1, 1))[:, :, :40000, :].copy()
+    case = DeviceCase(w, x7)
+    st = check_loki(case, 0)
+    say(f"7 distinct rows: {st}")
+    assert st["heads_with_swaps"] == 0
+
+
 def test_ties_go_to_lowest_position():
     """All-zero cache: every score ties, the first k positions must be selected and the
     output is the mean of the first k value rows.  Then planted duplicate rows."""

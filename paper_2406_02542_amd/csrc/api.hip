@@ -238,6 +238,10 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
     tm.end();
     return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
   }
+  tm.begin("rotate_query");
+  e = launch_qrot(s, q, P, w.qhat, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("score");
   e = launch_score(s, select_mode, q, P, klo, w.scores, w.qhat, st);
   tm.end();

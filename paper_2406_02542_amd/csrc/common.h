@@ -96,6 +96,16 @@ __device__ inline float group_allreduce_sum(float x) {
   return x;
 }
 
+// Maximum over each aligned group of LANES consecutive lanes (LANES <= 16), to every lane.
+template <int LANES>
+__device__ inline float group_allreduce_max(float x) {
+  if constexpr (LANES >= 2) x = fmaxf(x, dpp_mov<kDppQuadXor1>(x));
+  if constexpr (LANES >= 4) x = fmaxf(x, dpp_mov<kDppQuadXor2>(x));
+  if constexpr (LANES >= 8) x = fmaxf(x, dpp_mov<kDppRowHalfMirror>(x));
+  if constexpr (LANES >= 16) x = fmaxf(x, dpp_mov<kDppRowMirror>(x));
+  return x;
+}
+
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Order-preserving map float -> uint32 (larger float <=> larger key); -0 is folded onto +0.

@@ -40,6 +40,7 @@ struct Workspace {
 // Lays the workspace out from `base` (may be null to only size it).
 Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base);
 
+hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, hipStream_t st);
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st);
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,

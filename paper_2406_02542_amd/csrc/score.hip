@@ -1,33 +1,70 @@
-// Query rotation fused with low-rank scoring (Algorithm 1 lines 3 and 5 of arXiv 2406.02542)
-// as a stand-alone kernel: one block scores a run of rows of one (batch, KV head) unit for
-// all G query heads of the group, so the slab is streamed once per unit.
+// Query rotation and low-rank scoring (Algorithm 1 lines 3 and 5 of arXiv 2406.02542) as
+// stand-alone kernels for the split path, where the rows of a unit are spread over many
+// blocks: qrot_kernel rotates every query once (qhat = q P_h, fp32, kept in the workspace for
+// the attention stage too), and the score kernels stream the low-rank slab, one block scoring
+// a run of rows of one (batch, KV head) unit for all G query heads of the group, so the slab
+// is read once per unit.  (Where one block owns a whole unit the rotation is done inside that
+// block instead: see fused.hip.)  A score block needs no LDS and no barrier: its slice of qhat
+// goes straight to registers while the first slab loads are already in flight.
 #include "score_impl.h"
 
 namespace loki {
 
+// Block (unit, quarter) computes 32 columns of qhat for the unit's G query heads: thread
+// (column j, part p) accumulates the 16 terms of part p, then the 8 parts are added in order —
+// the same association as rotate_query_block, so every path sees bit-identical qhat.
+constexpr int kQrotCols = 32;
+
+template <typename T, int G>
+__global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __restrict__ q,
+                                                   const float* __restrict__ P,
+                                                   float* __restrict__ qhat_out, int Hkv) {
+  __shared__ __align__(16) float s_q[G][kD];
+  __shared__ float s_part[G][kRotParts][kQrotCols];
+  const int tid = threadIdx.x;
+  const int unit = blockIdx.x;
+  const int h = unit % Hkv;
+  const size_t head0 = (size_t)unit * G;
+  const int jl = tid % kQrotCols, part = tid / kQrotCols;  // 8 parts of 16 terms
+  const int j = blockIdx.y * kQrotCols + jl;
+  const float* Ph = P + (size_t)h * kD * kD + j;
+
+  float pv[kRotPartLen];
+#pragma unroll
+  for (int ii = 0; ii < kRotPartLen; ++ii) pv[ii] = Ph[(size_t)(part * kRotPartLen + ii) * kD];
+  for (int i = tid; i < G * kD; i += 256) s_q[i / kD][i % kD] = T::load1(q + head0 * kD + i);
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float acc = 0.f;
+#pragma unroll
+    for (int i4 = 0; i4 < kRotPartLen; i4 += 4) {
+      const float4 qq = *reinterpret_cast<const float4*>(&s_q[g][part * kRotPartLen + i4]);
+      acc = fmaf(qq.x, pv[i4 + 0], acc);
+      acc = fmaf(qq.y, pv[i4 + 1], acc);
+      acc = fmaf(qq.z, pv[i4 + 2], acc);
+      acc = fmaf(qq.w, pv[i4 + 3], acc);
+    }
+    s_part[g][part][jl] = acc;
+  }
+  __syncthreads();
+  for (int i = tid; i < G * kQrotCols; i += 256) {
+    const int g = i / kQrotCols, jj = i % kQrotCols;
+    float sum = 0.f;
+#pragma unroll
+    for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[g][pp][jj];
+    qhat_out[(head0 + g) * kD + blockIdx.y * kQrotCols + jj] = sum;
+  }
+}
+
 template <typename T, int LPR, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_kernel(
-    const typename T::store_t* __restrict__ klo, const typename T::store_t* __restrict__ q,
-    const float* __restrict__ P, float* __restrict__ scores, float* __restrict__ qhat_out,
-    int Hkv, int S, int S_cap, int d, int rows_per_block) {
+    const typename T::store_t* __restrict__ klo, const float* __restrict__ qhat,
+    float* __restrict__ scores, int Hkv, int S, int S_cap, int d, int rows_per_block) {
   constexpr int EPC = T::EPC;
-
-  __shared__ float s_q[G][kD];
-  __shared__ float s_part[G][kRotParts][kD];
-  __shared__ float s_qhat[G][kD];
-
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
-  const int b = unit / Hkv, h = unit % Hkv;
-  const int head0 = (b * Hkv + h) * G;  // first query head of the group, flattened over batch
-
-  // Block 0 of a unit rotates all D columns and publishes qhat for the attention stage.
-  const int ncols = (blockIdx.x == 0) ? kD : d;
-  rotate_query_block<T, G, 256>(q + (size_t)head0 * kD, P + (size_t)h * kD * kD, ncols, s_q, s_part,
-                           s_qhat);
-  if (blockIdx.x == 0) {
-    for (int i = tid; i < G * kD; i += 256) qhat_out[(size_t)head0 * kD + i] = s_qhat[i / kD][i % kD];
-  }
+  const int head0 = unit * G;  // first query head of the group, flattened over batch
 
   const int lane = tid & 63;
   const int c = lane % LPR;
@@ -37,7 +74,8 @@ __global__ __launch_bounds__(256) void score_kernel(
 #pragma unroll
   for (int g = 0; g < G; ++g)
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) qr[g][e] = cact ? s_qhat[g][c * EPC + e] : 0.f;
+    for (int e = 0; e < EPC; ++e)
+      qr[g][e] = cact ? qhat[(size_t)(head0 + g) * kD + c * EPC + e] : 0.f;
 
   const size_t row_bytes = (size_t)d * T::kBytes;
   const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
@@ -59,6 +97,183 @@ __global__ __launch_bounds__(256) void score_kernel(
                            });
 }
 
+// ---- matrix-core variant for grouped queries on a bf16 cache ----------------------------------
+// With G > 1 query heads per KV head the scoring step is a small dense contraction per row tile,
+// scores[s, g] = sum_j Klo[s, j] qhat[g, j], and the per-byte vector work of the kernel above
+// grows with G until it, not HBM, sets the pace.  Here a wave's 1 KiB load is used directly as
+// the A operand of v_mfma_f32_16x16x32_bf16 (lane l supplies row l%16, columns 8*(l/16)..+7 —
+// exactly one 16-byte chunk of a slab row) and qhat^T, padded to 16 heads, is the B operand.
+// qhat is fp32: it enters as three bf16 terms (value, remainder, remainder of the remainder =
+// 24 significant bits), so the products are exact and a score differs from the fp32 vector
+// kernel only by accumulation order; the bf16 keys are exact.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (&term)[3]) {
+  uint32_t w[3][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t part[3][2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      float rest = active ? x[2 * i + e] : 0.f;
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        const uint16_t hb = BF16::round(rest);
+        rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
+        part[t][e] = hb;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) w[t][i] = part[t][0] | (part[t][1] << 16);
+  }
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+    term[t] = __builtin_bit_cast(bf16x8_t, make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]));
+}
+
+// NCH = 16-byte chunks per slab row (d = 8 * NCH).
+template <int NCH, int G, bool GROUP_MAX>
+__global__ __launch_bounds__(256) void score_mfma_kernel(
+    const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
+    int Hkv, int S, int S_cap, int rows_per_block) {
+  constexpr int d = 8 * NCH;
+  constexpr int RB = NCH <= 4 ? 4 / NCH : 1;   // 16-row blocks one load instruction covers
+  constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
+  constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
+  constexpr int RPS = 16 * RB;                 // rows per wave step
+  constexpr int UN = 8 / NL;                   // steps per loop trip: 8 loads in flight per lane
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int unit = blockIdx.y;
+  const int head0 = unit * G;
+
+  const int kgrp = lane >> 4, r16 = lane & 15;
+  const bool head_ok = r16 < G;
+
+  // B operands: qhat of head r16, the 8 columns this lane's k-group stands for
+  bf16x8_t bq[NB][3];
+#pragma unroll
+  for (int n = 0; n < NB; ++n) {
+    const int kbase = NCH <= 4 ? 8 * (kgrp % NCH) : 32 * n + 8 * kgrp;
+    const bool active = head_ok && (NCH <= 4 ? (kgrp / NCH == n) : true);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = qhat[(size_t)(head0 + (head_ok ? r16 : 0)) * kD + kbase + e];
+    split_bf16x8(x, active, bq[n]);
+  }
+
+  // where this lane's chunk of load j sits inside a step
+  const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
+  const size_t row_bytes = (size_t)d * 2;
+  const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
+                     (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+  const int row0 = blockIdx.x * rows_per_block;
+  const int row_end = min(S, row0 + rows_per_block);
+  const bool vec_ok = (S & 3) == 0;
+
+  for (int t0 = row0 + wave * RPS; t0 < row_end; t0 += 4 * RPS * UN) {
+    uint4 raw[UN][NL];
+#pragma unroll
+    for (int u = 0; u < UN; ++u)
+#pragma unroll
+      for (int j = 0; j < NL; ++j) {
+        const int trow = t0 + u * 4 * RPS;
+        raw[u][j] = (trow + row_in_step < row_end)
+                        ? load16(base + (size_t)trow * row_bytes + (size_t)j * 64)
+                        : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int trow = t0 + u * 4 * RPS;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (NCH <= 4) {
+          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][0]);
+#pragma unroll
+          for (int t = 2; t >= 0; --t)  // smallest terms first
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[rb][t], acc, 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int j = 0; j < NL; ++j) {
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][j]);
+#pragma unroll
+            for (int t = 2; t >= 0; --t)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
+          }
+        }
+        // acc[i] = score of head r16 at row trow + 16*rb + 4*kgrp + i
+        const int rowbase = trow + 16 * rb + 4 * kgrp;
+        float v[4] = {acc[0], acc[1], acc[2], acc[3]};
+        bool writer = head_ok;
+        float* dst;
+        if constexpr (GROUP_MAX) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<16>(head_ok ? v[i] : -3.0e38f);
+          writer = r16 == 0;
+          dst = scores + (size_t)unit * S + rowbase;
+        } else {
+          dst = scores + (size_t)(head0 + (head_ok ? r16 : 0)) * S + rowbase;
+        }
+        if (writer && rowbase < row_end) {
+          if (vec_ok && rowbase + 3 < row_end) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (rowbase + i < row_end) dst[i] = v[i];
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int NCH, int G>
+static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const void* q, const float* P,
+                                      const void* klo, float* scores, float* qhat, hipStream_t st) {
+  const int rpb = score_rows_per_block(s);
+  dim3 grid((s.S + rpb - 1) / rpb, s.B * s.Hkv);
+  if (select_mode == 1) {
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, true>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb);
+  } else {
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false>), grid, dim3(256), 0, st,
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb);
+  }
+  return hipGetLastError();
+}
+
+template <int NCH>
+static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const void* q, const float* P,
+                                      const void* klo, float* scores, float* qhat, hipStream_t st) {
+  switch (s.G) {
+    case 2: return launch_score_mfma_g<NCH, 2>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 4: return launch_score_mfma_g<NCH, 4>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 8: return launch_score_mfma_g<NCH, 8>(s, select_mode, q, P, klo, scores, qhat, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// bf16 cache, 2..8 query heads per KV head and a power-of-two number of chunks per slab row
+static bool score_mfma_applies(const Shape& s) {
+  const int nch = s.d / 8;
+  return s.dtype == 1 && s.G >= 2 && s.G <= 8 && s.d % 8 == 0 && (nch & (nch - 1)) == 0;
+}
+
+static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* q, const float* P,
+                                    const void* klo, float* scores, float* qhat, hipStream_t st) {
+  switch (s.d / 8) {
+    case 1: return launch_score_mfma_n<1>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 2: return launch_score_mfma_n<2>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 4: return launch_score_mfma_n<4>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 8: return launch_score_mfma_n<8>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 16: return launch_score_mfma_n<16>(s, select_mode, q, P, klo, scores, qhat, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 template <typename T, int LPR, int G>
 static hipError_t launch_score_g(const Shape& s, int select_mode, const void* q, const float* P,
                                  const void* klo, float* scores, float* qhat, hipStream_t st) {
@@ -68,12 +283,10 @@ static hipError_t launch_score_g(const Shape& s, int select_mode, const void* q,
   const bool gm = (select_mode == 1) && (G > 1);
   if (gm) {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, (G > 1)>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), static_cast<const ST*>(q), P, scores, qhat,
-                       s.Hkv, s.S, s.S_cap, s.d, rpb);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb);
   } else {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), static_cast<const ST*>(q), P, scores, qhat,
-                       s.Hkv, s.S, s.S_cap, s.d, rpb);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb);
   }
   return hipGetLastError();
 }
@@ -109,8 +322,28 @@ static hipError_t launch_score_t(const Shape& s, int select_mode, const void* q,
   }
 }
 
+template <typename T>
+static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, float* qhat,
+                                hipStream_t st) {
+  using ST = typename T::store_t;
+  const dim3 grid(s.B * s.Hkv, kD / kQrotCols), block(256);
+  switch (s.G) {
+    case 1: hipLaunchKernelGGL((qrot_kernel<T, 1>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
+    case 2: hipLaunchKernelGGL((qrot_kernel<T, 2>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
+    case 4: hipLaunchKernelGGL((qrot_kernel<T, 4>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
+    case 8: hipLaunchKernelGGL((qrot_kernel<T, 8>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, hipStream_t st) {
+  return s.dtype == 0 ? launch_qrot_t<F32>(s, q, P, qhat, st) : launch_qrot_t<BF16>(s, q, P, qhat, st);
+}
+
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st) {
+  if (score_mfma_applies(s)) return launch_score_mfma(s, select_mode, q, P, klo, scores, qhat, st);
   return s.dtype == 0 ? launch_score_t<F32>(s, select_mode, q, P, klo, scores, qhat, st)
                       : launch_score_t<BF16>(s, select_mode, q, P, klo, scores, qhat, st);
 }

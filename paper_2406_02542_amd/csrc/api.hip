@@ -57,6 +57,9 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
     w.scores = reinterpret_cast<float*>(take(heads_sel * s.S * sizeof(float)));
     w.sel_idx = reinterpret_cast<int32_t*>(take(heads_sel * s.k * sizeof(int32_t)));
     w.sel_score = reinterpret_cast<float*>(take(heads_sel * s.k * sizeof(float)));
+    const size_t scratch_words = select_scratch_words(s.S, (int)heads_sel);
+    w.sel_scratch = scratch_words ? reinterpret_cast<uint32_t*>(take(scratch_words * 4)) : nullptr;
+    if (scratch_words && !p) w.sel_scratch = nullptr;
   }
   w.partial = reinterpret_cast<float*>(
       take(nsplit > 1 ? heads_q * nsplit * (size_t)(kD + 2) * sizeof(float) : 0));
@@ -247,7 +250,7 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("select");
-  e = launch_select(s, heads_sel, w.scores, idx, w.sel_score, st);
+  e = launch_select(s, heads_sel, w.scores, idx, w.sel_score, w.sel_scratch, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("gather_attend");

@@ -34,6 +34,7 @@ struct Workspace {
   float* scores;     // [B*Hsel, S]
   int32_t* sel_idx;  // [B*Hsel, k]
   float* sel_score;  // [B*Hsel, k] approximate scores of the selected rows
+  uint32_t* sel_scratch;  // long sequences only: chunk histograms, candidates, bookkeeping
   float* partial;    // [B*Hq, nsplit, 130]
   size_t total_bytes;
 };
@@ -43,8 +44,9 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
 hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, hipStream_t st);
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st);
+size_t select_scratch_words(int S, int n_sel_heads);
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
-                         float* sel_score, hipStream_t st);
+                         float* sel_score, uint32_t* scratch, hipStream_t st);
 hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
                          const float* sel_score, float* partial, void* out, hipStream_t st);

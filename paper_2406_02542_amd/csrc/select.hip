@@ -5,7 +5,8 @@
 //
 //   S <= 16384: select_resident_kernel — every thread keeps its keys in registers
 //               (select_impl.h), one read of the scores.
-//   larger S:   select_stream_kernel — the scores are streamed four times by one block
+//   larger S:   several blocks per head (mb_*_kernel below); beyond 64 chunks of 16384,
+//               select_stream_kernel — the scores are streamed four times by one block
 //               (histogram of the leading 11 bits; collect the keys of the threshold bin into
 //               LDS and resolve the exact threshold among them; count; ordered write), each
 //               wave owning a contiguous range so that the ordered write needs no barrier.
@@ -40,7 +41,6 @@ constexpr int kStreamThreads = 1024;
 constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kStreamMaxCand = kStreamThreads * kSelKPT;  // 16384 keys = 64 KiB of LDS
 constexpr int kStreamTile = 256;                          // positions a wave covers per load
-constexpr int kStreamUnroll = 4;                          // loads a lane keeps in flight
 
 union StreamScratch {
   uint32_t cand[kStreamMaxCand];
@@ -51,6 +51,10 @@ template <bool VEC4>
 __global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
     const float* __restrict__ scores, int32_t* __restrict__ sel_idx, float* __restrict__ sel_score,
     int S, int k) {
+  // loads a lane keeps in flight: a block streams alone on its CU, so the bytes in flight set
+  // its bandwidth (16 x 16 B x 1024 threads = 256 KiB); the unaligned variant uses four
+  // scalar loads per step and would spill at that depth
+  constexpr int kStreamUnroll = VEC4 ? 16 : 4;
   __shared__ ResidentSelectSmem<kStreamThreads> sm;
   __shared__ StreamScratch scratch;
   __shared__ uint32_t s_wcnt[kStreamWaves][2];
@@ -229,6 +233,222 @@ __global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
   LOKI_STAMP(6);
 }
 
+// ---- long sequences: several blocks per head ---------------------------------------------------
+// One CU cannot stream a long score row fast enough (its outstanding-miss budget caps it at a
+// few tens of GB/s), so for S > 16384 a head's scores are cut into chunks of 16384 positions
+// and the selection runs as five small kernels:
+//   hist     (chunk, head)  11-bit digit histogram of the chunk -> global
+//   bin      (head)         sum the chunk histograms, find the threshold bin
+//   collect  (chunk, head)  keys of the threshold bin -> per-chunk candidate lists; count of
+//                           keys in higher bins
+//   resolve  (head)         exact threshold T among the candidates, rank offset of every chunk
+//   write    (chunk, head)  ordered emission with those offsets
+// If a chunk's candidate list overflows (long runs of equal scores), `resolve` runs the plain
+// digit-pass selection for that head by itself and `write` skips it.
+constexpr int kMbThreads = 1024;
+constexpr int kMbChunk = kMbThreads * kSelKPT;  // 16384 positions per block
+
+__host__ __device__ inline int mb_cand_cap(int nc) { return (kMbChunk / nc) & ~(kSelKPT - 1); }
+// per-head words of bookkeeping: cand_cnt[nc], gt_hi[nc], base[nc][2], bin1, rem1, T, need_eq, skip
+__host__ __device__ inline int mb_meta_stride(int nc) { return 4 * nc + 8; }
+
+__global__ __launch_bounds__(kMbThreads, 8) void mb_hist_kernel(const float* __restrict__ scores,
+                                                                uint32_t* __restrict__ hist_part,
+                                                                int S, int nc) {
+  __shared__ uint32_t s_hist[2048];
+  const int tid = threadIdx.x, chunk = blockIdx.x, head = blockIdx.y;
+  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
+  uint32_t key[kSelKPT], valid_mask;
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
+  s_hist[tid] = 0u;
+  s_hist[tid + kMbThreads] = 0u;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelKPT; ++i)
+    if ((valid_mask >> i) & 1u) atomicAdd(&s_hist[key[i] >> 21], 1u);
+  __syncthreads();
+  uint32_t* dst = hist_part + ((size_t)head * nc + chunk) * 2048;
+  dst[tid] = s_hist[tid];
+  dst[tid + kMbThreads] = s_hist[tid + kMbThreads];
+}
+
+__global__ __launch_bounds__(kMbThreads) void mb_bin_kernel(const uint32_t* __restrict__ hist_part,
+                                                            uint32_t* __restrict__ meta, int k,
+                                                            int nc) {
+  __shared__ ResidentSelectSmem<kMbThreads> sm;
+  const int tid = threadIdx.x, head = blockIdx.x;
+  const uint32_t* src = hist_part + (size_t)head * nc * 2048;
+  uint32_t h0 = 0, h1 = 0;
+  for (int c = 0; c < nc; ++c) {
+    h0 += src[(size_t)c * 2048 + tid];
+    h1 += src[(size_t)c * 2048 + tid + kMbThreads];
+  }
+  sm.hist[0][tid] = h0;
+  sm.hist[0][tid + kMbThreads] = h1;
+  __syncthreads();
+  resident_find_bin<kMbThreads>(sm, 0, (uint32_t)k);
+  if (tid == 0) {
+    uint32_t* m = meta + (size_t)head * mb_meta_stride(nc) + 4 * nc;
+    m[0] = sm.out[0][0];  // bin1
+    m[1] = sm.out[0][1];  // rows still needed from inside bin1
+    m[4] = 0u;            // skip flag
+  }
+}
+
+__global__ __launch_bounds__(kMbThreads, 8) void mb_collect_kernel(const float* __restrict__ scores,
+                                                                   uint32_t* __restrict__ meta,
+                                                                   uint32_t* __restrict__ cand,
+                                                                   int S, int nc) {
+  __shared__ uint32_t s_ncand, s_gt;
+  const int tid = threadIdx.x, lane = tid & 63, chunk = blockIdx.x, head = blockIdx.y;
+  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
+  uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
+  const uint32_t bin1 = m[4 * nc];
+  const int cap = mb_cand_cap(nc);
+  uint32_t* my_cand = cand + (size_t)head * kMbChunk + (size_t)chunk * cap;
+  uint32_t key[kSelKPT], valid_mask;
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
+  if (tid == 0) {
+    s_ncand = 0u;
+    s_gt = 0u;
+  }
+  __syncthreads();
+  uint32_t gt = 0;
+#pragma unroll
+  for (int i = 0; i < kSelKPT; ++i)
+    if ((valid_mask >> i) & 1u) {
+      const uint32_t b = key[i] >> 21;
+      gt += b > bin1;
+      if (b == bin1) {
+        const uint32_t slot = atomicAdd(&s_ncand, 1u);
+        if (slot < (uint32_t)cap) my_cand[slot] = key[i];
+      }
+    }
+  gt = wave_inclusive_scan_u32(gt);
+  if (lane == 63) atomicAdd(&s_gt, gt);
+  __syncthreads();
+  if (tid == 0) {
+    m[chunk] = s_ncand;      // may exceed cap: resolve then takes the slow road
+    m[nc + chunk] = s_gt;
+  }
+}
+
+__global__ __launch_bounds__(kMbThreads) void mb_resolve_kernel(
+    const float* __restrict__ scores, uint32_t* __restrict__ meta, const uint32_t* __restrict__ cand,
+    int32_t* __restrict__ sel_idx, float* __restrict__ sel_score, int S, int k, int nc) {
+  __shared__ ResidentSelectSmem<kMbThreads> sm;
+  __shared__ SelectSmem<kMbThreads> generic;
+  __shared__ uint32_t s_cg[64], s_ce[64];
+  __shared__ uint32_t s_over;
+  const int tid = threadIdx.x, head = blockIdx.x;
+  uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
+  const int cap = mb_cand_cap(nc);
+  if (tid == 0) s_over = 0u;
+  resident_select_clear<kMbThreads>(sm);
+  if (tid < 64) {
+    s_cg[tid] = 0u;
+    s_ce[tid] = 0u;
+  }
+  __syncthreads();
+  if (tid < nc && m[tid] > (uint32_t)cap) s_over = 1u;
+  __syncthreads();
+  if (s_over) {
+    if (tid == 0) m[4 * nc + 4] = 1u;
+    const float* a = scores + (size_t)head * S;
+    int32_t* out = sel_idx + (size_t)head * k;
+    float* outs = sel_score + (size_t)head * k;
+    block_select_topk<kMbThreads>(a, S, k, generic, [&](int rank, int pos) {
+      out[rank] = pos;
+      outs[rank] = a[pos];
+    });
+    return;
+  }
+  // thread t holds candidate slots [16 t, 16 t + 16), all inside one chunk's list
+  const int slot0 = tid * kSelKPT;
+  const int ct = slot0 / cap;
+  const int ls = slot0 - ct * cap;
+  const uint32_t cnt = ct < nc ? m[ct] : 0u;
+  const uint32_t* src = cand + (size_t)head * kMbChunk + slot0;
+  uint32_t ck[kSelKPT], valid_mask = 0;
+#pragma unroll
+  for (int i = 0; i < kSelKPT; ++i) {
+    const bool v = (uint32_t)(ls + i) < cnt;
+    ck[i] = v ? (src[i] << 11) : 0u;   // candidates agree on the top 11 bits: rank on the low 21
+    valid_mask |= (v ? 1u : 0u) << i;
+  }
+  uint32_t Tp, need_eq;
+  resident_threshold<kMbThreads, kSelKPT>(ck, valid_mask, m[4 * nc + 1], sm, Tp, need_eq);
+  // rows of every chunk that precede it in the output: keys above T and keys equal to T
+  uint32_t cg = 0, ce = 0;
+#pragma unroll
+  for (int i = 0; i < kSelKPT; ++i)
+    if ((valid_mask >> i) & 1u) {
+      cg += ck[i] > Tp;
+      ce += ck[i] == Tp;
+    }
+  if (cg) atomicAdd(&s_cg[ct], cg);
+  if (ce) atomicAdd(&s_ce[ct], ce);
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t g = 0, e = 0;
+    for (int c = 0; c < nc; ++c) {
+      m[2 * nc + 2 * c] = g;
+      m[2 * nc + 2 * c + 1] = e;
+      g += m[nc + c] + s_cg[c];
+      e += s_ce[c];
+    }
+    m[4 * nc + 2] = (m[4 * nc] << 21) | (Tp >> 11);
+    m[4 * nc + 3] = need_eq;
+  }
+}
+
+__global__ __launch_bounds__(kMbThreads, 8) void mb_write_kernel(const float* __restrict__ scores,
+                                                                 const uint32_t* __restrict__ meta,
+                                                                 int32_t* __restrict__ sel_idx,
+                                                                 float* __restrict__ sel_score,
+                                                                 int S, int k, int nc) {
+  __shared__ uint32_t s_wave[2][kMbThreads / 64];
+  const int chunk = blockIdx.x, head = blockIdx.y;
+  const uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
+  if (m[4 * nc + 4]) return;  // the head was finished by mb_resolve_kernel
+  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
+  uint32_t key[kSelKPT], valid_mask;
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
+  int32_t* out = sel_idx + (size_t)head * k;
+  float* outs = sel_score + (size_t)head * k;
+  resident_compact<kMbThreads, kSelKPT>(key, valid_mask, kSelKPT, m[4 * nc + 2], m[4 * nc + 3],
+                                        m[2 * nc + 2 * chunk], m[2 * nc + 2 * chunk + 1], s_wave[0],
+                                        s_wave[1], [&](int rank, int pos, float score) {
+                                          out[rank] = c0 + pos;
+                                          outs[rank] = score;
+                                        });
+}
+
+int select_chunks(int S) { return S > kMbChunk ? (S + kMbChunk - 1) / kMbChunk : 0; }
+size_t select_scratch_words(int S, int n_sel_heads) {
+  const int nc = select_chunks(S);
+  if (nc == 0 || nc > 64) return 0;
+  return (size_t)n_sel_heads * ((size_t)nc * 2048 + kMbChunk + mb_meta_stride(nc));
+}
+
+static hipError_t launch_select_multiblock(const Shape& s, int heads, const float* scores,
+                                           int32_t* sel_idx, float* sel_score, uint32_t* scratch,
+                                           hipStream_t st) {
+  const int nc = select_chunks(s.S);
+  uint32_t* hist_part = scratch;
+  uint32_t* cand = hist_part + (size_t)heads * nc * 2048;
+  uint32_t* meta = cand + (size_t)heads * kMbChunk;
+  const dim3 wide(nc, heads), narrow(heads), block(kMbThreads);
+  hipLaunchKernelGGL(mb_hist_kernel, wide, block, 0, st, scores, hist_part, s.S, nc);
+  hipLaunchKernelGGL(mb_bin_kernel, narrow, block, 0, st, hist_part, meta, s.k, nc);
+  hipLaunchKernelGGL(mb_collect_kernel, wide, block, 0, st, scores, meta, cand, s.S, nc);
+  hipLaunchKernelGGL(mb_resolve_kernel, narrow, block, 0, st, scores, meta, cand, sel_idx,
+                     sel_score, s.S, s.k, nc);
+  hipLaunchKernelGGL(mb_write_kernel, wide, block, 0, st, scores, meta, sel_idx, sel_score, s.S,
+                     s.k, nc);
+  return hipGetLastError();
+}
+
 #ifdef LOKI_PHASE_TIMING
 extern "C" int loki_debug_read_select_ts(unsigned long long* host_dst, size_t count) {
   return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(loki::g_phase_ts),
@@ -237,7 +457,9 @@ extern "C" int loki_debug_read_select_ts(unsigned long long* host_dst, size_t co
 #endif
 
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
-                         float* sel_score, hipStream_t st) {
+                         float* sel_score, uint32_t* scratch, hipStream_t st) {
+  if (scratch != nullptr && select_scratch_words(s.S, n_sel_heads) != 0)
+    return launch_select_multiblock(s, n_sel_heads, scores, sel_idx, sel_score, scratch, st);
   if (s.S <= 512 * kSelKPT) {
     const int per_thread = (((s.S + 511) / 512) + 3) & ~3;
     hipLaunchKernelGGL(select_resident_kernel<512>, dim3(n_sel_heads), dim3(512), 0, st, scores,

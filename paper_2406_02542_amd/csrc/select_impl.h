@@ -294,27 +294,27 @@ __device__ __forceinline__ void resident_threshold(const uint32_t (&key)[KPT], u
 // from w*64*C in tiles of 256, and inside a tile lane l holds the 4 positions from 4l — one
 // coalesced 16-byte load per lane and tile, and a position order (wave, tile, lane, element)
 // that the compaction can follow with per-tile DPP scans and a single barrier.
-template <int THREADS, int KPT, typename Emit>
-__device__ __forceinline__ void block_select_topk_resident(const float* a, int S, int k,
-                                                           int per_thread,
-                                                           ResidentSelectSmem<THREADS>& sm,
-                                                           Emit emit) {
-  constexpr int kWaves = THREADS / 64;
-  constexpr int kTiles = KPT / 4;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int C = per_thread;
-  const int wbase = wave * 64 * C + lane * 4;  // position of key[0]; key[4j + e] sits at +256j + e
-  const bool aligned = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
+//
+// resident_load_keys: reads a[0..n) in that layout; key[4j + e] is position
+// resident_pos0(C) + 256 j + e.
+__device__ __forceinline__ int resident_pos0(int C) {
+  return (int)(threadIdx.x >> 6) * 64 * C + (int)(threadIdx.x & 63) * 4;
+}
 
-  uint32_t key[KPT];
-  uint32_t valid_mask = 0;
+template <int KPT>
+__device__ __forceinline__ void resident_load_keys(const float* a, int n, int C, uint32_t (&key)[KPT],
+                                                   uint32_t& valid_mask) {
+  constexpr int kTiles = KPT / 4;
+  const int wbase = resident_pos0(C);
+  const bool aligned = (reinterpret_cast<uintptr_t>(a) & 15u) == 0;
+  valid_mask = 0;
 #pragma unroll
   for (int j = 0; j < kTiles; ++j) {
     const int i = 4 * j;
     const int p = wbase + 256 * j;
     key[i + 0] = key[i + 1] = key[i + 2] = key[i + 3] = 0u;
     if (i < C) {
-      if (aligned && p + 3 < S) {
+      if (aligned && p + 3 < n) {
         const float4 f = *reinterpret_cast<const float4*>(a + p);
         key[i + 0] = float_to_key(f.x);
         key[i + 1] = float_to_key(f.y);
@@ -324,23 +324,32 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
       } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-          if (p + e < S) {
+          if (p + e < n) {
             key[i + e] = float_to_key(a[p + e]);
             valid_mask |= 1u << (i + e);
           }
       }
     }
   }
+}
 
-  LOKI_STAMP(11);
-  uint32_t T, need_eq;
-  resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, sm, T, need_eq);
-  LOKI_STAMP(4);
-
-  // compaction: per tile a DPP exclusive scan over the lanes (greater in the low half-word,
-  // equal in the high half-word: a wave holds at most 64*KPT <= 65535 keys), then one
-  // barrier to learn how many selected rows the earlier waves hold.  For the block-wide sums
-  // the two counts travel separately (S may exceed 65535).
+// Ordered emission of the keys > T and of the first need_eq keys == T (counted from
+// eq_base equal keys already seen at lower positions); ranks start at gt_base +
+// min(eq_base, need_eq).  Per tile a DPP exclusive scan over the lanes (greater in the low
+// half-word, equal in the high half-word: a wave holds at most 64*KPT <= 65535 keys), then one
+// barrier to learn how many selected rows the earlier waves hold.  wave_g / wave_e are two
+// LDS arrays of THREADS/64 words that nobody else touches until the next barrier.
+// emit(rank, local position, score).
+template <int THREADS, int KPT, typename Emit>
+__device__ __forceinline__ void resident_compact(const uint32_t (&key)[KPT], uint32_t valid_mask,
+                                                 int C, uint32_t T, uint32_t need_eq,
+                                                 uint32_t gt_base, uint32_t eq_base,
+                                                 uint32_t* wave_g_tot, uint32_t* wave_e_tot,
+                                                 Emit emit) {
+  constexpr int kWaves = THREADS / 64;
+  constexpr int kTiles = KPT / 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wbase = resident_pos0(C);
   uint32_t excl[kTiles];
   uint32_t wave_g = 0, wave_e = 0;
 #pragma unroll
@@ -352,19 +361,19 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
         mine += (key[4 * j + e] > T ? 1u : 0u) + (key[4 * j + e] == T ? 0x10000u : 0u);
     const uint32_t incl = wave_inclusive_scan_u32(mine);
     const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-    excl[j] = ((wave_g + ((incl - mine) & 0xffffu)) & 0xffffu) | ((wave_e + ((incl - mine) >> 16)) << 16);
+    excl[j] = (wave_g + ((incl - mine) & 0xffffu)) | ((wave_e + ((incl - mine) >> 16)) << 16);
     wave_g += tot & 0xffffu;
     wave_e += tot >> 16;
   }
   if (lane == 0) {
-    sm.wave[0][wave] = wave_g;   // last reads of wave[0] / wave[1] are >= 2 barriers back
-    sm.wave[1][wave] = wave_e;
+    wave_g_tot[wave] = wave_g;
+    wave_e_tot[wave] = wave_e;
   }
   __syncthreads();
-  uint32_t before_g = 0, before_e = 0;
+  uint32_t before_g = gt_base, before_e = eq_base;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) {
-    const uint32_t tg = sm.wave[0][w], te = sm.wave[1][w];
+    const uint32_t tg = wave_g_tot[w], te = wave_e_tot[w];
     before_g += (w < wave) ? tg : 0u;
     before_e += (w < wave) ? te : 0u;
   }
@@ -382,6 +391,25 @@ __device__ __forceinline__ void block_select_topk_resident(const float* a, int S
         e_before += eq;
       }
   }
+}
+
+// Whole selection for S <= THREADS*C: emit(rank, pos, score) is called exactly k times, rank
+// in [0, k) ascending with pos.
+template <int THREADS, int KPT, typename Emit>
+__device__ __forceinline__ void block_select_topk_resident(const float* a, int S, int k,
+                                                           int per_thread,
+                                                           ResidentSelectSmem<THREADS>& sm,
+                                                           Emit emit) {
+  uint32_t key[KPT];
+  uint32_t valid_mask;
+  resident_load_keys<KPT>(a, S, per_thread, key, valid_mask);
+  LOKI_STAMP(11);
+  uint32_t T, need_eq;
+  resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, sm, T, need_eq);
+  LOKI_STAMP(4);
+  // sm.wave[0] / sm.wave[1] were last read two or more barriers ago
+  resident_compact<THREADS, KPT>(key, valid_mask, per_thread, T, need_eq, 0u, 0u, sm.wave[0],
+                                 sm.wave[1], emit);
   LOKI_STAMP(12);
 }
 

@@ -93,6 +93,7 @@ def main():
                     help="kernel sequence: the library's choice, or pinned")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-rotate", action="store_true", help="skip the loki_rotate_keys timing")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference point for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -205,6 +206,32 @@ def main():
         k_dense = per_kernel(dense_step, args.steps)
         log(f"[bench] dense {t_dense * 1e6:.1f} us/step")
 
+    # key rotation + append (Algorithm 1 lines 3-4): whole-prompt prefill and one-token append
+    rot = None
+    if not args.no_rotate:
+        log("[bench] timing loki_rotate_keys")
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(w.seed)
+        k_pre = torch.randn((w.B, w.Hkv, w.S, w.D), device="cuda", generator=gen).to(tdt)
+        k_one = k_pre[:, :, :1, :].contiguous()
+        rklo, rkhi, _ = api.alloc_cache(lay)
+
+        def rot_prefill(i):
+            api.loki_rotate_keys(lay, k_pre, P, rklo, rkhi, 0, w.S, stream)
+
+        def rot_append(i):
+            api.loki_rotate_keys(lay, k_one, P, rklo, rkhi, w.S - 1, 1, stream)
+
+        t_pre = timed(rot_prefill, max(10, args.steps // 10), 3)
+        t_app = timed(rot_append, args.steps, args.warmup)
+        pre_bytes = 2 * w.B * w.Hkv * w.S * w.D * w.elem_bytes  # read K, write Khat
+        rot = {"prefill_us": t_pre * 1e6, "prefill_rows": w.B * w.Hkv * w.S,
+               "prefill_hbm_gbps": pre_bytes / t_pre / 1e9,
+               "prefill_hbm_frac": pre_bytes / t_pre / 1e9 / HBM_PEAK_GBPS,
+               "append_one_token_us": t_app * 1e6}
+        log(f"[bench] rotate prefill {t_pre * 1e6:.1f} us, append {t_app * 1e6:.1f} us")
+        del k_pre, k_one, rklo, rkhi
+
     ab = algorithmic_bytes(w, mode)
     dominant = max((n for n in k_loki if n in ab), key=lambda n: k_loki[n])
     achieved = ab[dominant] / (k_loki[dominant] * 1e-6) / 1e9
@@ -237,6 +264,7 @@ def main():
         "dense_hbm_gbps": ab["dense_attend"] / t_dense / 1e9 if t_dense else None,
         "dense_kernels_us": k_dense,
         "speedup_vs_dense": (t_dense / t_loki) if t_dense else None,
+        "rotate_keys": rot,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -59,12 +59,16 @@ struct BF16 {
   __device__ static inline float load1(const store_t* p) {
     return __uint_as_float(static_cast<uint32_t>(*p) << 16);
   }
-  // fp32 -> bf16, round to nearest, ties to even; NaN stays NaN
+  // fp32 -> bf16, round to nearest, ties to even; NaN stays NaN (v_cvt_pk_bf16_f32)
   __device__ static inline uint16_t round(float x) {
-    uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x40u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(x));
+  }
+  // two conversions in one instruction: `lo` lands in bits 15..0, `hi` in bits 31..16
+  __device__ static inline uint32_t round2(float lo, float hi) {
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
   }
   __device__ static inline void store1(store_t* p, float x) { *p = round(x); }
 };

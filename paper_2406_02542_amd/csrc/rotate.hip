@@ -4,6 +4,8 @@
 //
 // All rows that share a KV head share P_h, whatever their batch index, so a block works on a
 // run of (batch, row) items of ONE head with P_h resident in LDS.
+#include <type_traits>
+
 #include "common.h"
 #include "launch.h"
 
@@ -78,106 +80,172 @@ __global__ __launch_bounds__(kRotThreads) void rotate_kernel(
 // ---- matrix-core variant for bf16 caches --------------------------------------------------------
 // Khat = K P_h over a run of rows is a genuine [n, 128] x [128, 128] contraction.  A wave's
 // 16-byte-per-lane load of a 16-row tile of K is directly the A operand of
-// v_mfma_f32_16x16x32_bf16 (lane l: row l%16, columns 8*(l/16)..+7 of a 32-column step); the B
-// operand is P_h, which is fp32 and enters as three bf16 terms (24 significant bits) so every
-// product is exact and only the fp32 accumulation order differs from the vector kernel.  Each
-// of the block's four waves owns 32 output columns and keeps its share of P_h in registers
-// (4 steps x 2 column blocks x 3 terms); all four read the same K tiles.
+// v_mfma_f32_16x16x32_bf16 (lane l: row l%16, columns 8*(l/16)..+7 of a 32-column step).  The B
+// operand is P_h, which is fp32: it is split once per block into three bf16 terms (24
+// significant bits, so every product is exact and only the fp32 accumulation order differs
+// from the vector kernel) and parked in LDS already in operand layout, 96 KiB.  Every wave
+// owns whole 16-row tiles (each key row is read from HBM once), prefetches its next tile while
+// the 96 matrix instructions of the current one run, and packs pairs of neighbouring columns
+// so that results leave as 4-byte stores.
 typedef __bf16 rot_bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float rot_f32x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kRotMfmaTiles = 2;  // 16-row tiles per loop trip (8 loads in flight per lane)
+constexpr int kRotMfmaThreads = 512;
+constexpr int kRotMfmaWaves = kRotMfmaThreads / 64;
+constexpr int kRotMfmaItems = 2048;  // rows per block: 16 tiles per wave
+constexpr int kRotMfmaTPW = 2;        // tiles a wave multiplies per operand fetch
 
-__global__ __launch_bounds__(kRotThreads) void rotate_mfma_kernel(
+__global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
     const uint16_t* __restrict__ k_new, const float* __restrict__ P, uint16_t* __restrict__ klo,
     uint16_t* __restrict__ khi, int Hkv, int S_cap, int d, int pos, int n_new, int n_items,
     int items_per_block) {
-  __shared__ float s_P[kD * kD];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  __shared__ uint4 s_B[3][4][8][64];  // [term][32-column step of K][16-column block of Khat][lane]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: row bases stay scalar
   const int kgrp = lane >> 4, r16 = lane & 15;
   const int h = blockIdx.y;
   const float* Ph = P + (size_t)h * kD * kD;
-  for (int i = tid * 4; i < kD * kD; i += kRotThreads * 4)
-    *reinterpret_cast<float4*>(s_P + i) = *reinterpret_cast<const float4*>(Ph + i);
-  __syncthreads();
 
-  // this wave's columns: 32*wave + 16*nbi + r16
-  rot_bf16x8_t bp[4][2][3];
+  // element P[i][col] belongs to operand (step i/32, block col/16), lane ((i%32)/8)*16 + col%16,
+  // slot i%8
+  constexpr int kPrep = kD * kD / kRotMfmaThreads;  // 32 elements per thread, all loads in flight
+  float pv[kPrep];
 #pragma unroll
-  for (int step = 0; step < 4; ++step)
+  for (int n = 0; n < kPrep; ++n) pv[n] = Ph[tid + n * kRotMfmaThreads];
 #pragma unroll
-    for (int nbi = 0; nbi < 2; ++nbi) {
-      uint32_t w[3][4];
+  for (int n = 0; n < kPrep; ++n) {
+    const int idx = tid + n * kRotMfmaThreads;
+    const int i = idx / kD, col = idx % kD;
+    float rest = pv[n];
+    uint16_t* base = reinterpret_cast<uint16_t*>(&s_B[0][i / 32][col / 16][((i % 32) / 8) * 16 + col % 16]) + (i % 8);
 #pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        uint32_t part[3][2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          float rest = s_P[(32 * step + 8 * kgrp + 2 * e2 + e) * kD + 32 * wave + 16 * nbi + r16];
-#pragma unroll
-          for (int t = 0; t < 3; ++t) {
-            const uint16_t hb = BF16::round(rest);
-            rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
-            part[t][e] = hb;
-          }
-        }
-#pragma unroll
-        for (int t = 0; t < 3; ++t) w[t][e2] = part[t][0] | (part[t][1] << 16);
-      }
-#pragma unroll
-      for (int t = 0; t < 3; ++t)
-        bp[step][nbi][t] =
-            __builtin_bit_cast(rot_bf16x8_t, make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]));
+    for (int t = 0; t < 3; ++t) {
+      const uint16_t hb = BF16::round(rest);
+      rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
+      base[(size_t)t * (sizeof(s_B[0]) / 2)] = hb;
     }
+  }
+  __syncthreads();
 
   const int item0 = blockIdx.x * items_per_block;
   const int item1 = min(n_items, item0 + items_per_block);
-  for (int t0 = item0; t0 < item1; t0 += 16 * kRotMfmaTiles) {
-    uint4 raw[kRotMfmaTiles][4];
-#pragma unroll
-    for (int u = 0; u < kRotMfmaTiles; ++u) {
-      const int it = t0 + 16 * u + r16;
-      const bool valid = it < item1;
-      const int b = valid ? it / n_new : 0, r = valid ? it % n_new : 0;
-      const char* src = reinterpret_cast<const char*>(k_new) +
-                        ((size_t)(b * Hkv + h) * n_new + r) * (kD * 2) + (size_t)kgrp * 16;
-#pragma unroll
-      for (int step = 0; step < 4; ++step)
-        raw[u][step] = valid ? load16(src + step * 64) : make_uint4(0, 0, 0, 0);
+
+  // Loads never branch: rows past the block's end re-read its last row (item1 > item0 always)
+  // and are simply not stored.  Straight-line loads and stores let the compiler count
+  // outstanding memory operations exactly, which keeps the prefetch of the next trip in flight
+  // during the matrix work instead of being waited for together with the stores.
+  // item -> (batch, row): one scalar division per tile base, then a short carry per lane
+  auto split_item = [&](int base, int off, int& b, int& r) {
+    b = base / n_new;
+    r = base % n_new + off;  // off < 64
+    while (r >= n_new) {
+      r -= n_new;
+      ++b;
     }
+  };
+  auto load_tile = [&](int t0, uint4 (&raw)[4]) {
+    const int itb = min(t0, item1 - 1);
+    int b, r;
+    split_item(itb, min(t0 + r16, item1 - 1) - itb, b, r);
+    const char* src = reinterpret_cast<const char*>(k_new) +
+                      ((size_t)(b * Hkv + h) * n_new + r) * (kD * 2) + (size_t)kgrp * 16;
 #pragma unroll
-    for (int u = 0; u < kRotMfmaTiles; ++u) {
-      // rows this lane will store: items t0 + 16u + 4*kgrp + i
-      size_t dst_row[4];
-      bool ok[4];
+    for (int step = 0; step < 4; ++step) raw[step] = load16(src + step * 64);
+  };
+
+  constexpr int TPW = kRotMfmaTPW;
+  constexpr int kStride = 16 * TPW * kRotMfmaWaves;  // rows the block covers per trip
+
+  // One trip: TPW tiles starting at row t0; FULL = every row of them exists.
+  auto trip = [&](int t0, const uint4 (&raw)[TPW][4], auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    // rows this lane stores per tile: items +4*kgrp + {0,1} (even column) or {2,3} (odd column)
+    const int i0 = (r16 & 1) * 2;
+    size_t row[TPW][2];
+    bool ok[TPW][2];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int it = t0 + 16 * u + 4 * kgrp + i;
-        ok[i] = it < item1;
-        const int b = ok[i] ? it / n_new : 0, r = ok[i] ? it % n_new : 0;
-        dst_row[i] = (size_t)(b * Hkv + h) * S_cap + pos + r;
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+      for (int ii = 0; ii < 2; ++ii) {
+        const int it = t0 + 16 * u + 4 * kgrp + i0 + ii;
+        ok[u][ii] = FULL || it < item1;
+        const int itb = min(t0, item1 - 1);
+        int b, r;
+        split_item(itb, min(it, item1 - 1) - itb, b, r);
+        row[u][ii] = (size_t)(b * Hkv + h) * S_cap + pos + r;
       }
+    // The operands in LDS never change, but they must be re-read for every trip: hoisted out of
+    // the loop, all 96 of them would live in registers and spill.  An offset the compiler
+    // cannot see through (always 0) keeps the reads inside the trip.
+    uint32_t opaque = 0;
+    __asm__ volatile("" : "+v"(opaque));
+    const uint4* bop = &s_B[0][0][0][0] + opaque;
 #pragma unroll
-      for (int nbi = 0; nbi < 2; ++nbi) {
-        rot_f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < 8; nb += 2) {
+      rot_f32x4_t acc[TPW][2];
 #pragma unroll
-        for (int t = 2; t >= 0; --t)  // smallest terms first
+      for (int u = 0; u < TPW; ++u)
 #pragma unroll
-          for (int step = 0; step < 4; ++step)
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-                __builtin_bit_cast(rot_bf16x8_t, raw[u][step]), bp[step][nbi][t], acc, 0, 0, 0);
-        const int col = 32 * wave + 16 * nbi + r16;
+        for (int half = 0; half < 2; ++half) acc[u][half] = rot_f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (ok[i]) {
-            if (col < d)
-              klo[dst_row[i] * d + col] = BF16::round(acc[i]);
-            else
-              khi[dst_row[i] * (kD - d) + (col - d)] = BF16::round(acc[i]);
+      for (int t = 2; t >= 0; --t)  // smallest terms first
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+          const rot_bf16x8_t b0 =
+              __builtin_bit_cast(rot_bf16x8_t, bop[((t * 4 + step) * 8 + nb) * 64 + lane]);
+          const rot_bf16x8_t b1 =
+              __builtin_bit_cast(rot_bf16x8_t, bop[((t * 4 + step) * 8 + nb + 1) * 64 + lane]);
+#pragma unroll
+          for (int u = 0; u < TPW; ++u) {
+            const rot_bf16x8_t a = __builtin_bit_cast(rot_bf16x8_t, raw[u][step]);
+            acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b0, acc[u][0], 0, 0, 0);
+            acc[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b1, acc[u][1], 0, 0, 0);
           }
-      }
+        }
+#pragma unroll
+      for (int u = 0; u < TPW; ++u)
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int colb = 16 * (nb + half) + (r16 & ~1);  // even column of the pair
+          // neighbour lane (r16 ^ 1) holds the other column of the pair for the same rows
+          float other[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) other[i] = dpp_mov<kDppQuadXor1>(acc[u][half][i]);
+#pragma unroll
+          for (int ii = 0; ii < 2; ++ii) {
+            const int i = i0 + ii;
+            const float mine = (r16 & 1) ? acc[u][half][2 + ii] : acc[u][half][ii];
+            const float lo_col = (r16 & 1) ? other[i] : mine;
+            const float hi_col = (r16 & 1) ? mine : other[i];
+            const uint32_t packed = BF16::round2(lo_col, hi_col);
+            uint32_t* p32 =
+                (colb < d) ? reinterpret_cast<uint32_t*>(klo + row[u][ii] * d + colb)
+                           : reinterpret_cast<uint32_t*>(khi + row[u][ii] * (kD - d) + (colb - d));
+            if (FULL) {
+              *p32 = packed;
+            } else if (ok[u][ii]) {
+              *p32 = packed;
+            }
+          }
+        }
     }
+  };
+
+  uint4 nxt[TPW][4];
+#pragma unroll
+  for (int u = 0; u < TPW; ++u) load_tile(item0 + 16 * (TPW * wave + u), nxt[u]);
+  int t0 = item0 + 16 * TPW * wave;
+  for (; t0 + 16 * TPW <= item1; t0 += kStride) {  // trips whose rows all exist
+    uint4 raw[TPW][4];
+#pragma unroll
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+      for (int step = 0; step < 4; ++step) raw[u][step] = nxt[u][step];
+#pragma unroll
+    for (int u = 0; u < TPW; ++u) load_tile(t0 + kStride + 16 * u, nxt[u]);
+    trip(t0, raw, std::true_type{});
   }
+  if (t0 < item1) trip(t0, nxt, std::false_type{});  // ragged last trip of this wave
 }
 
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
@@ -190,10 +258,10 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
   dim3 grid((n_items + ipb - 1) / ipb, s.Hkv);
   const size_t lds = 0;  // LDS is declared statically in the kernels
   if (s.dtype == 1) {
-    int ipb_m = 1024;
+    int ipb_m = kRotMfmaItems;
     if (n_items < ipb_m) ipb_m = ((n_items + 15) / 16) * 16;
     dim3 grid_m((n_items + ipb_m - 1) / ipb_m, s.Hkv);
-    hipLaunchKernelGGL(rotate_mfma_kernel, grid_m, dim3(kRotThreads), 0, st,
+    hipLaunchKernelGGL(rotate_mfma_kernel, grid_m, dim3(kRotMfmaThreads), 0, st,
                        static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
                        static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb_m);
     return hipGetLastError();

@@ -19,8 +19,12 @@ __host__ __device__ inline int fused_keys_per_thread(int S) {
   return (c + 3) & ~3;
 }
 
-template <typename T, int LPR, bool REUSE_LO>
-__global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
+// Two blocks share a CU (4 waves per SIMD): the register budget is 128 VGPRs and the compiler
+// is told not to trade load-level parallelism for a higher occupancy that cannot happen.
+// KPT = keys a thread holds in the select stage (8 for S <= 4096, else 16).
+template <typename T, int LPR, bool REUSE_LO, int KPT>
+__global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void
+fused_decode_kernel(
     const typename T::store_t* __restrict__ klo, const typename T::store_t* __restrict__ khi,
     const typename T::store_t* __restrict__ v, const typename T::store_t* __restrict__ q,
     const float* __restrict__ P, typename T::store_t* __restrict__ out,
@@ -60,31 +64,44 @@ __global__ __launch_bounds__(kFusedThreads) void fused_decode_kernel(
   }
 #endif
   resident_select_clear<kFusedThreads>(s_sel);  // covered by the barriers of the next stages
+
+  // this lane's place in the low-rank slab
+  const int cs = lane % LPR;
+  const bool cact = cs < d / EPC;
+  const size_t slab_row_bytes = (size_t)d * T::kBytes;
+  const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * slab_row_bytes +
+                     (size_t)(cact ? cs : 0) * 16;
+  constexpr bool kPipelined = LPR <= 8;
+  // q first (so that nothing younger has to land before it can be used), then the first slab
+  // loads, which do not need qhat: they are in flight during the rotation
+  const float q_mine = tid < kD ? T::load1(q + (size_t)unit * kD + tid) : 0.f;
+  ScoreTrip<kPipelined ? LPR : 8> first_trip;
+  if constexpr (kPipelined)
+    score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
+
   // ---- qhat = q P_h, all 128 columns ----------------------------------------------------
-  rotate_query_block<T, 1, kFusedThreads>(q + (size_t)unit * kD, P + (size_t)h * kD * kD, kD, s_q,
-                                          s_part, s_qhat);
+  if (tid < kD) s_q[0][tid] = q_mine;
+  __syncthreads();
+  rotate_query_from_lds<1, kFusedThreads>(P + (size_t)h * kD * kD, kD, s_q, s_part, s_qhat);
 
   LOKI_STAMP(1);
   // ---- approximate scores over the low-rank slab, into LDS ------------------------------
   {
-    const int c = lane % LPR;
-    const int nch = d / EPC;
-    const bool cact = c < nch;
     float qr[1][EPC];
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) qr[0][e] = cact ? s_qhat[0][c * EPC + e] : 0.f;
-    const size_t row_bytes = (size_t)d * T::kBytes;
-    const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
-                       (size_t)(cact ? c : 0) * 16;
-    score_rows<T, LPR, 1, kFusedWaves>(base, row_bytes, cact, qr, 0, S,
-                                       [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; });
+    for (int e = 0; e < EPC; ++e) qr[0][e] = cact ? s_qhat[0][cs * EPC + e] : 0.f;
+    auto to_lds = [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; };
+    if constexpr (kPipelined)
+      score_rows_pipelined<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, qr, 0, S, first_trip, to_lds);
+    else
+      score_rows<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, cact, qr, 0, S, to_lds);
   }
   __syncthreads();
   LOKI_STAMP(2);
 
   // ---- top-k in LDS ------------------------------------------------------------------------
   int32_t* gidx = out_idx ? out_idx + (size_t)unit * k : nullptr;
-  block_select_topk_resident<kFusedThreads, kFusedKPT>(s_score, S, k, per_thread, s_sel,
+  block_select_topk_resident<kFusedThreads, KPT>(s_score, S, k, per_thread, s_sel,
                                                        [&](int rank, int pos, float score) {
     s_idx[rank] = pos;
     s_a[rank] = score;
@@ -134,12 +151,12 @@ bool fused_preferred(const Shape& s) {
   return units >= 192 || s.S <= 2048;
 }
 
-template <typename T, int LPR, bool REUSE_LO>
-static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, const void* klo,
+template <typename T, int LPR, bool REUSE_LO, int KPT>
+static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, const void* klo,
                                  const void* khi, const void* v, void* out, int32_t* out_idx,
                                  hipStream_t st) {
   using ST = typename T::store_t;
-  auto kern = fused_decode_kernel<T, LPR, REUSE_LO>;
+  auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT>;
   const size_t lds = fused_dynamic_lds(s);
   static bool attr_set = false;  // benign race: every caller sets the same value
   if (!attr_set) {
@@ -154,6 +171,15 @@ static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, 
                      static_cast<const ST*>(v), static_cast<const ST*>(q), P, static_cast<ST*>(out),
                      out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k);
   return hipGetLastError();
+}
+
+template <typename T, int LPR, bool REUSE_LO>
+static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, const void* klo,
+                                 const void* khi, const void* v, void* out, int32_t* out_idx,
+                                 hipStream_t st) {
+  if (fused_keys_per_thread(s.S) <= 8)
+    return launch_fused_k<T, LPR, REUSE_LO, 8>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_k<T, LPR, REUSE_LO, kFusedKPT>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <typename T, int LPR>

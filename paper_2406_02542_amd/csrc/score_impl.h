@@ -13,7 +13,15 @@ namespace loki {
 constexpr int kRotParts = 8;                 // q P is summed as 8 partial sums of 16 terms each,
 constexpr int kRotPartLen = kD / kRotParts;  // in a fixed order, whichever block computes it
 
-// qhat[g][j] for j < ncols into s_qhat; THREADS threads.  Ends with a barrier.
+// qhat[g][j] for j < ncols into s_qhat, from q already stored in s_q (a barrier between that
+// store and this call is the caller's); THREADS threads.  Ends with a barrier.
+template <int G, int THREADS>
+__device__ inline void rotate_query_from_lds(const float* __restrict__ Ph, int ncols,
+                                             float (&s_q)[G][kD],
+                                             float (&s_part)[G][kRotParts][kD],
+                                             float (&s_qhat)[G][kD]);
+
+// As above, reading q from global memory first.
 template <typename T, int G, int THREADS>
 __device__ inline void rotate_query_block(const typename T::store_t* __restrict__ q_heads,
                                           const float* __restrict__ Ph, int ncols,
@@ -22,6 +30,15 @@ __device__ inline void rotate_query_block(const typename T::store_t* __restrict_
   const int tid = threadIdx.x;
   for (int i = tid; i < G * kD; i += THREADS) s_q[i / kD][i % kD] = T::load1(q_heads + i);
   __syncthreads();
+  rotate_query_from_lds<G, THREADS>(Ph, ncols, s_q, s_part, s_qhat);
+}
+
+template <int G, int THREADS>
+__device__ inline void rotate_query_from_lds(const float* __restrict__ Ph, int ncols,
+                                             float (&s_q)[G][kD],
+                                             float (&s_part)[G][kRotParts][kD],
+                                             float (&s_qhat)[G][kD]) {
+  const int tid = threadIdx.x;
   int ncol_pad = 1;
   while (ncol_pad < ncols) ncol_pad <<= 1;  // <= 128
   const int j = tid % ncol_pad;
@@ -29,15 +46,17 @@ __device__ inline void rotate_query_block(const typename T::store_t* __restrict_
   const int ngroups = THREADS / ncol_pad;
   if (j < ncols) {
     for (int p = pg; p < kRotParts; p += ngroups) {
+      float pv[kRotPartLen];  // the 16 loads of a part are independent: all in flight at once
+#pragma unroll
+      for (int ii = 0; ii < kRotPartLen; ++ii) pv[ii] = Ph[(p * kRotPartLen + ii) * kD + j];
       float acc[G];
 #pragma unroll
       for (int g = 0; g < G; ++g) acc[g] = 0.f;
 #pragma unroll
       for (int ii = 0; ii < kRotPartLen; ++ii) {
         const int i = p * kRotPartLen + ii;
-        const float pv = Ph[i * kD + j];
 #pragma unroll
-        for (int g = 0; g < G; ++g) acc[g] = fmaf(s_q[g][i], pv, acc[g]);
+        for (int g = 0; g < G; ++g) acc[g] = fmaf(s_q[g][i], pv[ii], acc[g]);
       }
 #pragma unroll
       for (int g = 0; g < G; ++g) s_part[g][p][j] = acc[g];
@@ -99,6 +118,72 @@ __device__ __forceinline__ void score_rows(const char* base, size_t row_bytes, b
         }
     }
     // lane now owns the score of row tile + c*RPI + rsub of each of its TPI tiles
+#pragma unroll
+    for (int tt = 0; tt < TPI; ++tt) {
+      const int row = tile0 + tt * WAVES * 64 + c * RPI + rsub;
+      if (row < row_end) emit(row, keep[tt]);
+    }
+  }
+}
+
+// ---- software-pipelined form (LPR <= 8) -----------------------------------------------------
+// The loads of a trip are issued one trip ahead, and the first trip can be issued by the
+// caller before it has qhat at all (e.g. ahead of the query rotation).  Loads never branch:
+// rows past row_end re-read row row_end-1 and are simply not emitted, lanes past the slab
+// row's last chunk read chunk 0 and multiply it by zero.
+template <int LPR>
+struct ScoreTrip {
+  static_assert(LPR <= 8, "pipelined scoring keeps one load per chunk lane group");
+  static constexpr int TPI = 8 / LPR;  // 64-row tiles per trip: 8 loads in flight per lane
+  uint4 raw[TPI][LPR];
+};
+
+template <int LPR, int WAVES>
+__device__ __forceinline__ void score_load_trip(const char* base, size_t row_bytes, int tile0,
+                                                int row_end, ScoreTrip<LPR>& t) {
+  constexpr int RPI = 64 / LPR;
+  const int rsub = (threadIdx.x & 63) / LPR;
+#pragma unroll
+  for (int tt = 0; tt < ScoreTrip<LPR>::TPI; ++tt)
+#pragma unroll
+    for (int u = 0; u < LPR; ++u) {
+      const int row = min(tile0 + tt * WAVES * 64 + u * RPI + rsub, row_end - 1);
+      t.raw[tt][u] = load16(base + (size_t)row * row_bytes);
+    }
+}
+
+// `first` holds the trip of tile0 = row0 + wave*64, already in flight.
+template <typename T, int LPR, int G, int WAVES, typename Emit>
+__device__ __forceinline__ void score_rows_pipelined(const char* base, size_t row_bytes,
+                                                     const float (&qr)[G][T::EPC], int row0,
+                                                     int row_end, ScoreTrip<LPR>& first, Emit emit) {
+  constexpr int EPC = T::EPC;
+  constexpr int RPI = 64 / LPR;
+  constexpr int TPI = ScoreTrip<LPR>::TPI;
+  constexpr int kStride = WAVES * 64 * TPI;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c = lane % LPR, rsub = lane / LPR;
+
+  ScoreTrip<LPR> nxt = first;
+  for (int tile0 = row0 + wave * 64; tile0 < row_end; tile0 += kStride) {
+    ScoreTrip<LPR> cur = nxt;
+    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + kStride, row_end, nxt);
+    float keep[TPI][G];
+#pragma unroll
+    for (int tt = 0; tt < TPI; ++tt)
+#pragma unroll
+      for (int u = 0; u < LPR; ++u) {
+        float f[EPC];
+        T::unpack(cur.raw[tt][u], f);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float p = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPC; ++e) p = fmaf(f[e], qr[g][e], p);
+          p = group_allreduce_sum<LPR>(p);
+          if (c == u) keep[tt][g] = p;
+        }
+      }
 #pragma unroll
     for (int tt = 0; tt < TPI; ++tt) {
       const int row = tile0 + tt * WAVES * 64 + c * RPI + rsub;

@@ -182,6 +182,8 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
                          const float* sel_score, float* partial, void* out, hipStream_t st) {
   const int NH = (select_mode == 1) ? s.G : 1;
+  if (attend_mfma_applies(s, NH))
+    return launch_gather_mfma(s, nsplit, qhat, klo, khi, v, sel_idx, partial, out, st);
   const int blocks_y = s.B * s.Hq / NH;
   const int rpb = div_up(s.k, nsplit);
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
@@ -194,6 +196,7 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
                         const void* v, float* partial, void* out, hipStream_t st) {
+  if (attend_mfma_applies(s, s.G)) return launch_dense_mfma(s, nsplit, q, k_full, v, partial, out, st);
   const int blocks_y = s.B * s.Hkv;
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)

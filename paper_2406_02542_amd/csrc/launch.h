@@ -52,6 +52,13 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
                          const float* sel_score, float* partial, void* out, hipStream_t st);
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
                         const void* v, float* partial, void* out, hipStream_t st);
+// Matrix-core attention for 8 query heads per block on bf16 caches (attend_mfma.hip).
+bool attend_mfma_applies(const Shape& s, int heads_per_block);
+hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const void* k_full,
+                             const void* v, float* partial, void* out, hipStream_t st);
+hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
+                              const void* khi, const void* v, const int32_t* sel_idx, float* partial,
+                              void* out, hipStream_t st);
 hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,
                           hipStream_t st);
 // Fused single-kernel decode step (one query head per KV head only).

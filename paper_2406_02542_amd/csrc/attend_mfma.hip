@@ -270,7 +270,7 @@ static hipError_t launch_attend_mfma_nh(int NH, int blocks_y, int nsplit, int rp
 }
 
 bool attend_mfma_applies(const Shape& s, int heads_per_block) {
-  return s.dtype == 1 && heads_per_block == 8;
+  return s.dtype == 1 && (heads_per_block == 8 || heads_per_block == 4);
 }
 
 hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const void* k_full,

@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy
 # calibration; measured values and commands are in profiles/llama2_7b_fused_decode.md.
 MEASURED_TRAFFIC_BYTES = {
-    "llama2_7b:fused_decode": 193784.0 * 2048 + 128.0 * 1024,
+    "llama2_7b:fused_decode": 194406.5 * 2048 + 128.0 * 1024,
 }
 
 
@@ -233,13 +233,36 @@ def main():
         del k_pre, k_one, rklo, rkhi
 
     ab = algorithmic_bytes(w, mode)
+
+    # the read ceiling of this device: a trivial kernel streaming as many bytes as one decode
+    # step moves (algorithmic bytes), over buffers cycled like the cache copies
+    step_bytes = int(ab["step"]) // 16 * 16
+    sbufs = [torch.empty(step_bytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+             for _ in range(max(3, args.copies))]
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(10):
+        api.loki_stream_read(sbufs[i % len(sbufs)], step_bytes, stream)
+    n_sr = max(20, args.steps // 4)
+    ev0.record(stream)
+    for i in range(n_sr):
+        api.loki_stream_read(sbufs[i % len(sbufs)], step_bytes, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    sr_us = ev0.elapsed_time(ev1) * 1e3 / n_sr
+    del sbufs
+    stream_read = {"bytes": step_bytes, "us": sr_us, "GB/s": step_bytes / sr_us / 1e3,
+                   "frac_of_peak": step_bytes / sr_us / 1e3 / HBM_PEAK_GBPS}
+    log(f"[bench] plain read of {step_bytes} bytes: {sr_us:.1f} us")
+
     dominant = max((n for n in k_loki if n in ab), key=lambda n: k_loki[n])
     achieved = ab[dominant] / (k_loki[dominant] * 1e-6) / 1e9
     default_shape = (w == cfgs[args.workload])
     traffic = MEASURED_TRAFFIC_BYTES.get(f"{w.name}:{dominant}") if default_shape else None
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "algorithmic_bytes": ab[dominant], "kernel_us": k_loki[dominant]}
+                "algorithmic_bytes": ab[dominant], "kernel_us": k_loki[dominant],
+                "stream_read": stream_read,
+                "frac_of_stream_read": achieved / stream_read["GB/s"]}
 
     result = {
         "metric": "loki_decode_attn_us_per_step",

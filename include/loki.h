@@ -164,6 +164,14 @@ int loki_profile_destroy(loki_profile* p);
 int loki_profile_attach(loki_profile* p);
 int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** names);
 
+/*
+ * Measurement aid, not part of the method: enqueues one trivial kernel that reads
+ * `bytes` bytes (a multiple of 16, 16-byte aligned device pointer) with coalesced
+ * 16-byte loads and discards them.  Its duration over as many bytes as a decode step
+ * moves is the read ceiling a benchmark can set beside the published HBM peak.
+ */
+int loki_stream_read(const void* buf, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
     L.loki_profile_destroy.argtypes = [vp]
     L.loki_profile_attach.restype = i32
     L.loki_profile_attach.argtypes = [vp]
+    L.loki_stream_read.restype = i32
+    L.loki_stream_read.argtypes = [vp, sz, vp]
     L.loki_profile_read.restype = i32
     L.loki_profile_read.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float),
                                     ctypes.POINTER(ctypes.c_char_p)]
@@ -207,6 +209,14 @@ def dense_decode_attn(layout: Layout, q: torch.Tensor, k_full: torch.Tensor, v: 
         workspace.numel() if workspace is not None else 0,
         _ptr(out, "out", dt, nq),
         _stream_ptr(stream)), "dense_decode_attn")
+
+
+def loki_stream_read(buf: torch.Tensor, nbytes: int, stream=None) -> None:
+    """Enqueues the library's trivial read kernel over the first ``nbytes`` bytes of ``buf``."""
+    if not buf.is_cuda or not buf.is_contiguous() or nbytes > buf.numel() * buf.element_size():
+        raise ValueError("buf must be a contiguous device tensor of at least nbytes bytes")
+    _check(lib().loki_stream_read(ctypes.c_void_p(buf.data_ptr()), nbytes, _stream_ptr(stream)),
+           "loki_stream_read")
 
 
 class Profile:

@@ -132,6 +132,30 @@ static inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_
 
 using namespace loki;
 
+// Measurement aid: streams `n16` 16-byte words through the load path and discards them.  The
+// time of this kernel over as many bytes as a decode step moves is the practical ceiling of
+// a read-bound kernel on the device it runs on.
+namespace loki {
+__device__ unsigned g_stream_read_sink;
+__global__ __launch_bounds__(512) void stream_read_kernel(const uint4* __restrict__ p, size_t n16) {
+  unsigned acc = 0;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = p[i + u * stride];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+  }
+  for (; i < n16; i += stride) {
+    const uint4 v = p[i];
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x9e3779b9u) g_stream_read_sink = acc;  // keeps the loads alive
+}
+}  // namespace loki
+
 extern "C" {
 
 int loki_version(void) { return 100; }
@@ -343,6 +367,14 @@ int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** n
     if (names) names[i] = p->names[i];
   }
   return LOKI_OK;
+}
+
+int loki_stream_read(const void* buf, size_t bytes, void* stream) {
+  if (!buf || bytes == 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(buf) & 15))
+    return LOKI_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(loki::stream_read_kernel, dim3(loki::kNumCU), dim3(512), 0,
+                     static_cast<hipStream_t>(stream), static_cast<const uint4*>(buf), bytes / 16);
+  return hipGetLastError() == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
 }
 
 }  // extern "C"

@@ -40,9 +40,10 @@ fused_decode_kernel(
   int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + kFusedThreads * per_thread);  // [k]
   float* s_a = reinterpret_cast<float*>(s_idx + k);              // [k]
 
-  __shared__ float s_q[1][kD];
-  __shared__ float s_part[1][kRotParts][kD];
+  __shared__ __align__(16) float s_q[kD];
+  __shared__ __align__(8) float s_part[kRotParts][kD];
   __shared__ float s_qhat[1][kD];
+  static_assert(kFusedWaves == kRotParts, "one wave per part of the rotation");
   __shared__ ResidentSelectSmem<kFusedThreads> s_sel;
   __shared__ MergeSmem<kFusedWaves, 1> s_merge;
 
@@ -50,12 +51,6 @@ fused_decode_kernel(
   const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
   const int h = unit % Hkv;
 
-#ifdef LOKI_STAGGER_TICKS
-  if (blockIdx.x >= gridDim.x / 2) {
-    const unsigned long long t0 = wall_clock64();
-    while (wall_clock64() - t0 < LOKI_STAGGER_TICKS) __builtin_amdgcn_s_sleep(8);
-  }
-#endif
   LOKI_STAMP(0);
 #ifdef LOKI_PHASE_TIMING
   if (threadIdx.x == 0 && blockIdx.x < 8192) {
@@ -72,17 +67,50 @@ fused_decode_kernel(
   const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * slab_row_bytes +
                      (size_t)(cact ? cs : 0) * 16;
   constexpr bool kPipelined = LPR <= 8;
-  // q first (so that nothing younger has to land before it can be used), then the first slab
-  // loads, which do not need qhat: they are in flight during the rotation
-  const float q_mine = tid < kD ? T::load1(q + (size_t)unit * kD + tid) : 0.f;
+  // Issue order = the order the results are needed in (loads return in order): q, then this
+  // thread's 16 x 2 entries of P_h, then the first slab loads, which do not need qhat and stay
+  // in flight during the rotation.
+  const float q_mine = T::load1(q + (size_t)unit * kD + (tid & (kD - 1)));  // no branch: no early wait
+  // qhat = q P_h with the association every path uses (8 parts of 16 terms, parts added in
+  // order): wave w owns part w, lane l columns 2l and 2l+1; a load instruction of the wave
+  // covers one 512-byte row of P_h.
+  float2 pv[kRotPartLen];
+  {
+    const float* Ph = P + (size_t)h * kD * kD + (size_t)(wave * kRotPartLen) * kD + 2 * lane;
+#pragma unroll
+    for (int ii = 0; ii < kRotPartLen; ++ii)
+      pv[ii] = *reinterpret_cast<const float2*>(Ph + (size_t)ii * kD);
+  }
   ScoreTrip<kPipelined ? LPR : 8> first_trip;
   if constexpr (kPipelined)
     score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
 
-  // ---- qhat = q P_h, all 128 columns ----------------------------------------------------
-  if (tid < kD) s_q[0][tid] = q_mine;
+  s_q[tid & (kD - 1)] = q_mine;  // four threads store the same value: no branch to sink the load into
   __syncthreads();
-  rotate_query_from_lds<1, kFusedThreads>(P + (size_t)h * kD * kD, kD, s_q, s_part, s_qhat);
+  {
+    float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+    for (int i4 = 0; i4 < kRotPartLen; i4 += 4) {
+      const float4 qq = *reinterpret_cast<const float4*>(&s_q[wave * kRotPartLen + i4]);
+      a0 = fmaf(qq.x, pv[i4 + 0].x, a0);
+      a1 = fmaf(qq.x, pv[i4 + 0].y, a1);
+      a0 = fmaf(qq.y, pv[i4 + 1].x, a0);
+      a1 = fmaf(qq.y, pv[i4 + 1].y, a1);
+      a0 = fmaf(qq.z, pv[i4 + 2].x, a0);
+      a1 = fmaf(qq.z, pv[i4 + 2].y, a1);
+      a0 = fmaf(qq.w, pv[i4 + 3].x, a0);
+      a1 = fmaf(qq.w, pv[i4 + 3].y, a1);
+    }
+    *reinterpret_cast<float2*>(&s_part[wave][2 * lane]) = make_float2(a0, a1);
+  }
+  __syncthreads();
+  if (tid < kD) {
+    float sum = 0.f;
+#pragma unroll
+    for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[pp][tid];
+    s_qhat[0][tid] = sum;
+  }
+  __syncthreads();
 
   LOKI_STAMP(1);
   // ---- approximate scores over the low-rank slab, into LDS ------------------------------

@@ -12,7 +12,7 @@ namespace loki {
 
 // Block (unit, quarter) computes 32 columns of qhat for the unit's G query heads: thread
 // (column j, part p) accumulates the 16 terms of part p, then the 8 parts are added in order —
-// the same association as rotate_query_block, so every path sees bit-identical qhat.
+// the same association as the fused decode kernel, so every path sees bit-identical qhat.
 constexpr int kQrotCols = 32;
 
 template <typename T, int G>

@@ -11,67 +11,7 @@
 namespace loki {
 
 constexpr int kRotParts = 8;                 // q P is summed as 8 partial sums of 16 terms each,
-constexpr int kRotPartLen = kD / kRotParts;  // in a fixed order, whichever block computes it
-
-// qhat[g][j] for j < ncols into s_qhat, from q already stored in s_q (a barrier between that
-// store and this call is the caller's); THREADS threads.  Ends with a barrier.
-template <int G, int THREADS>
-__device__ inline void rotate_query_from_lds(const float* __restrict__ Ph, int ncols,
-                                             float (&s_q)[G][kD],
-                                             float (&s_part)[G][kRotParts][kD],
-                                             float (&s_qhat)[G][kD]);
-
-// As above, reading q from global memory first.
-template <typename T, int G, int THREADS>
-__device__ inline void rotate_query_block(const typename T::store_t* __restrict__ q_heads,
-                                          const float* __restrict__ Ph, int ncols,
-                                          float (&s_q)[G][kD], float (&s_part)[G][kRotParts][kD],
-                                          float (&s_qhat)[G][kD]) {
-  const int tid = threadIdx.x;
-  for (int i = tid; i < G * kD; i += THREADS) s_q[i / kD][i % kD] = T::load1(q_heads + i);
-  __syncthreads();
-  rotate_query_from_lds<G, THREADS>(Ph, ncols, s_q, s_part, s_qhat);
-}
-
-template <int G, int THREADS>
-__device__ inline void rotate_query_from_lds(const float* __restrict__ Ph, int ncols,
-                                             float (&s_q)[G][kD],
-                                             float (&s_part)[G][kRotParts][kD],
-                                             float (&s_qhat)[G][kD]) {
-  const int tid = threadIdx.x;
-  int ncol_pad = 1;
-  while (ncol_pad < ncols) ncol_pad <<= 1;  // <= 128
-  const int j = tid % ncol_pad;
-  const int pg = tid / ncol_pad;
-  const int ngroups = THREADS / ncol_pad;
-  if (j < ncols) {
-    for (int p = pg; p < kRotParts; p += ngroups) {
-      float pv[kRotPartLen];  // the 16 loads of a part are independent: all in flight at once
-#pragma unroll
-      for (int ii = 0; ii < kRotPartLen; ++ii) pv[ii] = Ph[(p * kRotPartLen + ii) * kD + j];
-      float acc[G];
-#pragma unroll
-      for (int g = 0; g < G; ++g) acc[g] = 0.f;
-#pragma unroll
-      for (int ii = 0; ii < kRotPartLen; ++ii) {
-        const int i = p * kRotPartLen + ii;
-#pragma unroll
-        for (int g = 0; g < G; ++g) acc[g] = fmaf(s_q[g][i], pv[ii], acc[g]);
-      }
-#pragma unroll
-      for (int g = 0; g < G; ++g) s_part[g][p][j] = acc[g];
-    }
-  }
-  __syncthreads();
-  for (int i = tid; i < G * ncols; i += THREADS) {
-    const int g = i / ncols, jj = i % ncols;
-    float s = 0.f;
-#pragma unroll
-    for (int p = 0; p < kRotParts; ++p) s += s_part[g][p][jj];
-    s_qhat[g][jj] = s;
-  }
-  __syncthreads();
-}
+constexpr int kRotPartLen = kD / kRotParts;  // in a fixed order, whichever kernel computes it
 
 // Scores rows [row0, row_end) of one unit's low-rank slab with the block's WAVES waves.
 // qr is this lane's slice of qhat (zero for lanes past the slab row's last chunk); `base`
@@ -152,43 +92,54 @@ __device__ __forceinline__ void score_load_trip(const char* base, size_t row_byt
     }
 }
 
-// `first` holds the trip of tile0 = row0 + wave*64, already in flight.
+// Scores one trip already (or about to be) in registers.
+template <typename T, int LPR, int G, int WAVES, typename Emit>
+__device__ __forceinline__ void score_trip(const ScoreTrip<LPR>& cur, const float (&qr)[G][T::EPC],
+                                           int tile0, int row_end, Emit& emit) {
+  constexpr int EPC = T::EPC;
+  constexpr int RPI = 64 / LPR;
+  constexpr int TPI = ScoreTrip<LPR>::TPI;
+  const int lane = threadIdx.x & 63;
+  const int c = lane % LPR, rsub = lane / LPR;
+  float keep[TPI][G];
+#pragma unroll
+  for (int tt = 0; tt < TPI; ++tt)
+#pragma unroll
+    for (int u = 0; u < LPR; ++u) {
+      float f[EPC];
+      T::unpack(cur.raw[tt][u], f);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float p = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) p = fmaf(f[e], qr[g][e], p);
+        p = group_allreduce_sum<LPR>(p);
+        if (c == u) keep[tt][g] = p;
+      }
+    }
+#pragma unroll
+  for (int tt = 0; tt < TPI; ++tt) {
+    const int row = tile0 + tt * WAVES * 64 + c * RPI + rsub;
+    if (row < row_end) emit(row, keep[tt]);
+  }
+}
+
+// `first` holds the trip of tile0 = row0 + wave*64, already in flight.  Two register buffers
+// take turns (the loop body handles two trips), so a trip's loads stay in flight while the
+// previous trip is scored and no buffer is ever copied; the loads past the last trip are
+// clamped re-reads of the last row.
 template <typename T, int LPR, int G, int WAVES, typename Emit>
 __device__ __forceinline__ void score_rows_pipelined(const char* base, size_t row_bytes,
                                                      const float (&qr)[G][T::EPC], int row0,
                                                      int row_end, ScoreTrip<LPR>& first, Emit emit) {
-  constexpr int EPC = T::EPC;
-  constexpr int RPI = 64 / LPR;
-  constexpr int TPI = ScoreTrip<LPR>::TPI;
-  constexpr int kStride = WAVES * 64 * TPI;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = lane % LPR, rsub = lane / LPR;
-
-  ScoreTrip<LPR> nxt = first;
-  for (int tile0 = row0 + wave * 64; tile0 < row_end; tile0 += kStride) {
-    ScoreTrip<LPR> cur = nxt;
-    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + kStride, row_end, nxt);
-    float keep[TPI][G];
-#pragma unroll
-    for (int tt = 0; tt < TPI; ++tt)
-#pragma unroll
-      for (int u = 0; u < LPR; ++u) {
-        float f[EPC];
-        T::unpack(cur.raw[tt][u], f);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float p = 0.f;
-#pragma unroll
-          for (int e = 0; e < EPC; ++e) p = fmaf(f[e], qr[g][e], p);
-          p = group_allreduce_sum<LPR>(p);
-          if (c == u) keep[tt][g] = p;
-        }
-      }
-#pragma unroll
-    for (int tt = 0; tt < TPI; ++tt) {
-      const int row = tile0 + tt * WAVES * 64 + c * RPI + rsub;
-      if (row < row_end) emit(row, keep[tt]);
-    }
+  constexpr int kStride = WAVES * 64 * ScoreTrip<LPR>::TPI;
+  const int wave = threadIdx.x >> 6;
+  ScoreTrip<LPR> other;
+  for (int tile0 = row0 + wave * 64; tile0 < row_end; tile0 += 2 * kStride) {
+    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + kStride, row_end, other);
+    score_trip<T, LPR, G, WAVES>(first, qr, tile0, row_end, emit);
+    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 2 * kStride, row_end, first);
+    score_trip<T, LPR, G, WAVES>(other, qr, tile0 + kStride, row_end, emit);
   }
 }
 

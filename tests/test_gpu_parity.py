@@ -308,3 +308,12 @@ def test_errors_surface_as_exceptions():
     with pytest.raises(api.LokiError):
         api.loki_decode_attn(case.layout, case.q, case.P, case.klo, case.khi, case.v, 128, 32, 129, 0,
                              ws, out)
+
+
+@pytest.mark.gpu
+def test_stream_read_probe_runs():
+    """The measurement aid reads a buffer (whole words and a ragged word count) without error."""
+    buf = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    api.loki_stream_read(buf, buf.numel() * 4)
+    api.loki_stream_read(buf, 16 * 1237)
+    torch.cuda.synchronize()

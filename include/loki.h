@@ -149,6 +149,52 @@ int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_fu
                       int S, void* workspace, size_t workspace_bytes, void* out, void* stream);
 
 /*
+ * The whole decode step of Algorithm 1 (lines 2-9) for a batch whose sequences may
+ * differ in length, optionally including the cache append of the current token
+ * (lines 3-4: rotate the new key, store it and the new value), in the same launches
+ * as the attention.  With args == NULL, or all of its members NULL, it is
+ * loki_decode_attn.
+ *
+ *   seq_lens  device int32 [B] or NULL: rows sequence b holds, counting the current
+ *             token, 1 <= seq_lens[b] <= S_max.  NULL: S_max for every sequence.
+ *   ks        device int32 [B] or NULL: rows sequence b keeps,
+ *             1 <= ks[b] <= min(k_max, seq_lens[b]).  NULL: min(k_max, seq_lens[b]).
+ *             Entries outside their range are clamped into it.
+ *   k_new     device [B, Hkv, D] or NULL: unrotated key of the current token (storage
+ *             type).  When given, Khat row seq_lens[b]-1 of every (b, KV head) is
+ *             overwritten with round(k_new P_h) (columns < d into klo, the rest into
+ *             khi, as loki_rotate_keys does) and V row seq_lens[b]-1 with v_new, before
+ *             anything is scored; the step then sees them like any cached row.
+ *   v_new     device [B, Hkv, D]; required exactly when k_new is given.
+ *
+ * S_max and k_max (1 <= k_max <= S_max <= S_cap) size the workspace
+ * (loki_workspace_bytes(layout, S_max, d, k_max, select_mode)) and out_idx:
+ * out_idx is [B, Hsel, k_max], and a sequence keeping fewer than k_max rows has -1 in
+ * the remaining entries.  klo, khi and v are written only when k_new is given.
+ * Everything else as loki_decode_attn.
+ */
+typedef struct {
+  const int32_t* seq_lens;
+  const int32_t* ks;
+  const void* k_new;
+  const void* v_new;
+} loki_step_args;
+
+int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,
+                     void* v, int S_max, int d, int k_max, int select_mode,
+                     const loki_step_args* args, void* workspace, size_t workspace_bytes, void* out,
+                     int32_t* out_idx, void* stream);
+
+/*
+ * dense_decode_attn with per-sequence lengths: sequence b attends over its first
+ * seq_lens[b] rows (device int32 [B], 1 <= seq_lens[b] <= S_max; NULL: S_max).  The
+ * workspace is sized for S_max (loki_workspace_bytes(layout, S_max, 0, 0, -1)).
+ */
+int dense_decode_step(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S_max, const int32_t* seq_lens, void* workspace, size_t workspace_bytes,
+                      void* out, void* stream);
+
+/*
  * Stage timing for benchmarks.  A profile owns HIP events; when one is attached
  * with loki_profile_attach, the next decode / dense / rotate calls made from the
  * same host thread record an event before and after every kernel they launch (on

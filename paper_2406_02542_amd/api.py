@@ -62,6 +62,10 @@ def lib() -> ctypes.CDLL:
     L.loki_rotate_keys.argtypes = [LP, vp, vp, vp, vp, i32, i32, vp]
     L.loki_decode_attn.restype = i32
     L.loki_decode_attn.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    L.loki_decode_step.restype = i32
+    L.loki_decode_step.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp, vp, vp]
+    L.dense_decode_step.restype = i32
+    L.dense_decode_step.argtypes = [LP, vp, vp, vp, i32, vp, vp, sz, vp, vp]
     L.dense_decode_attn.restype = i32
     L.dense_decode_attn.argtypes = [LP, vp, vp, vp, i32, vp, sz, vp, vp]
     L.loki_profile_create.restype = i32
@@ -191,6 +195,60 @@ def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
         _ptr(out, "out", dt, nq),
         _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k),
         _stream_ptr(stream)), "loki_decode_attn")
+
+
+class StepArgs(ctypes.Structure):
+    """Mirror of ``loki_step_args``."""
+    _fields_ = [("seq_lens", ctypes.c_void_p), ("ks", ctypes.c_void_p),
+                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p)]
+
+
+def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                     khi: Optional[torch.Tensor], v: torch.Tensor, S_max: int, d: int, k_max: int,
+                     select_mode: int, workspace: torch.Tensor, out: torch.Tensor,
+                     out_idx: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
+                     ks: Optional[torch.Tensor] = None, k_new: Optional[torch.Tensor] = None,
+                     v_new: Optional[torch.Tensor] = None, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
+    args = StepArgs(
+        _ptr(seq_lens, "seq_lens", torch.int32, layout.B),
+        _ptr(ks, "ks", torch.int32, layout.B),
+        _ptr(k_new, "k_new", dt, rows * layout.D),
+        _ptr(v_new, "v_new", dt, rows * layout.D))
+    _check(lib().loki_decode_step(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
+        _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S_max, d, k_max, select_mode, ctypes.byref(args),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+        _ptr(out, "out", dt, nq),
+        _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k_max),
+        _stream_ptr(stream)), "loki_decode_step")
+
+
+def dense_decode_step(layout: Layout, q: torch.Tensor, k_full: torch.Tensor, v: torch.Tensor,
+                      S_max: int, seq_lens: Optional[torch.Tensor],
+                      workspace: Optional[torch.Tensor], out: torch.Tensor, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    _check(lib().dense_decode_step(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(k_full, "k_full", dt, rows * layout.S_cap * layout.D),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S_max,
+        _ptr(seq_lens, "seq_lens", torch.int32, layout.B),
+        _ptr(workspace, "workspace", torch.uint8),
+        workspace.numel() if workspace is not None else 0,
+        _ptr(out, "out", dt, nq),
+        _stream_ptr(stream)), "dense_decode_step")
 
 
 def dense_decode_attn(layout: Layout, q: torch.Tensor, k_full: torch.Tensor, v: torch.Tensor,

@@ -158,7 +158,7 @@ __global__ __launch_bounds__(512) void stream_read_kernel(const uint4* __restric
 
 extern "C" {
 
-int loki_version(void) { return 100; }
+int loki_version(void) { return 110; }
 
 const char* loki_status_string(int status) {
   switch (status) {
@@ -225,10 +225,12 @@ int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* 
   return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
 }
 
-int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
-                     const void* khi, const void* v, int S, int d, int k, int select_mode,
-                     void* workspace, size_t workspace_bytes, void* out, int32_t* out_idx,
-                     void* stream) {
+// The decode step behind loki_decode_attn (no per-sequence sizes, no append) and
+// loki_decode_step.
+static int decode_impl(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,
+                       void* v, int S, int d, int k, int select_mode, const Ragged& rg,
+                       const Append& ap, void* workspace, size_t workspace_bytes, void* out,
+                       int32_t* out_idx, void* stream) {
   Shape s;
   const int rc = check_layout(layout, &s);
   if (rc != LOKI_OK) return rc;
@@ -242,12 +244,17 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
   if (k < 1 || k > S) return LOKI_ERR_INVALID_ARG;
   if (d != s.d) return LOKI_ERR_UNSUPPORTED;
+  if ((ap.k_new == nullptr) != (ap.v_new == nullptr)) return LOKI_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(P) || !aligned16(klo) || !aligned16(khi) || !aligned16(v) ||
-      !aligned16(out) || !aligned16(out_idx))
+      !aligned16(out) || !aligned16(out_idx) || !aligned16(ap.k_new) || !aligned16(ap.v_new))
+    return LOKI_ERR_ALIGNMENT;
+  if ((reinterpret_cast<uintptr_t>(rg.seq_lens) & 3u) || (reinterpret_cast<uintptr_t>(rg.ks) & 3u))
     return LOKI_ERR_ALIGNMENT;
   if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
   s.S = S;
   s.k = k;
+  s.rg = rg;
+  s.ap = ap;
   if (s.G == 1) select_mode = LOKI_SELECT_PER_QUERY_HEAD;  // identical; one code path
   const int nsplit = gather_splits(s, select_mode);
   const Workspace w = plan_workspace(s, select_mode, nsplit, workspace);
@@ -266,7 +273,7 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
     return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
   }
   tm.begin("rotate_query");
-  e = launch_qrot(s, q, P, w.qhat, st);
+  e = launch_qrot(s, q, P, w.qhat, klo, khi, v, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("score");
@@ -290,8 +297,35 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   return LOKI_OK;
 }
 
-int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_full, const void* v,
-                      int S, void* workspace, size_t workspace_bytes, void* out, void* stream) {
+int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
+                     const void* khi, const void* v, int S, int d, int k, int select_mode,
+                     void* workspace, size_t workspace_bytes, void* out, int32_t* out_idx,
+                     void* stream) {
+  // nothing is appended, so the caches are only read
+  return decode_impl(layout, q, P, const_cast<void*>(klo), const_cast<void*>(khi),
+                     const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, workspace,
+                     workspace_bytes, out, out_idx, stream);
+}
+
+int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,
+                     void* v, int S_max, int d, int k_max, int select_mode,
+                     const loki_step_args* args, void* workspace, size_t workspace_bytes, void* out,
+                     int32_t* out_idx, void* stream) {
+  Ragged rg;
+  Append ap;
+  if (args) {
+    rg.seq_lens = args->seq_lens;
+    rg.ks = args->ks;
+    ap.k_new = args->k_new;
+    ap.v_new = args->v_new;
+  }
+  return decode_impl(layout, q, P, klo, khi, v, S_max, d, k_max, select_mode, rg, ap, workspace,
+                     workspace_bytes, out, out_idx, stream);
+}
+
+static int dense_impl(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S, const int32_t* seq_lens, void* workspace, size_t workspace_bytes,
+                      void* out, void* stream) {
   Shape s;
   loki_layout L;
   if (!layout) return LOKI_ERR_INVALID_ARG;
@@ -303,7 +337,9 @@ int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_fu
   if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(k_full) || !aligned16(v) || !aligned16(out))
     return LOKI_ERR_ALIGNMENT;
+  if (reinterpret_cast<uintptr_t>(seq_lens) & 3u) return LOKI_ERR_ALIGNMENT;
   s.S = S;
+  s.rg.seq_lens = seq_lens;
   const int nsplit = dense_splits(s);
   const Workspace w = plan_workspace(s, -1, nsplit, workspace);
   if (nsplit > 1) {
@@ -325,6 +361,17 @@ int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_fu
     if (e != hipSuccess) return LOKI_ERR_HIP;
   }
   return LOKI_OK;
+}
+
+int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S, void* workspace, size_t workspace_bytes, void* out, void* stream) {
+  return dense_impl(layout, q, k_full, v, S, nullptr, workspace, workspace_bytes, out, stream);
+}
+
+int dense_decode_step(const loki_layout* layout, const void* q, const void* k_full, const void* v,
+                      int S_max, const int32_t* seq_lens, void* workspace, size_t workspace_bytes,
+                      void* out, void* stream) {
+  return dense_impl(layout, q, k_full, v, S_max, seq_lens, workspace, workspace_bytes, out, stream);
 }
 
 int loki_profile_create(loki_profile** out) {

@@ -25,7 +25,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     const float* __restrict__ sel_score,   // REUSE_LO: [blocks_y, n] approximate scores of sel_idx
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     void* __restrict__ out,         // [B*Hq, 128] storage type when nsplit == 1
-    int Hq, int Gq, int S_cap, int d, int n, int rows_per_block, int nsplit) {
+    int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;           // lanes per row: 16 (bf16) or 32 (fp32)
@@ -41,14 +41,19 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   const int bidx = head0 / Hq;
   const int kv_unit = bidx * (Hq / Gq) + (head0 % Hq) / Gq;
 
+  // list length of this sequence: the rows it keeps (gather: exactly what the select stage
+  // computed) or the rows it holds (dense).  A block whose run starts past the end publishes
+  // the neutral partial (max -big, sum 0).
+  const int n = GATHER ? seq_keep(rag, bidx, n_max, seq_rows(rag, bidx, S_max))
+                       : seq_rows(rag, bidx, n_max);
   const int r0 = blockIdx.x * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
 
   if constexpr (GATHER) {
-    const int32_t* idx = sel_idx + (size_t)blockIdx.y * n;
+    const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
     for (int i = tid; i < r1 - r0; i += kAttThreads) {
       s_idx[i] = idx[r0 + i];
-      if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)blockIdx.y * n + r0 + i];
+      if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)blockIdx.y * n_max + r0 + i];
     }
     __syncthreads();
   }
@@ -140,19 +145,19 @@ template <typename T, int NH, bool GATHER>
 static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block, const void* k_a,
                                    const void* k_b, const void* v, const void* qv,
                                    const int32_t* sel_idx, const float* sel_score, float* partial,
-                                   void* out, int Hq, int Gq, int S_cap, int d, int n,
-                                   hipStream_t st) {
+                                   void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
+                                   const Ragged& rg, hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
   // and there is a residual slab to read at all
   constexpr bool kCanReuse = GATHER && NH == 1;
   if (kCanReuse && sel_score != nullptr && d < kD) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg);
   } else {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, false>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg);
   }
   return hipGetLastError();
 }
@@ -161,11 +166,11 @@ template <typename T, bool GATHER>
 static hipError_t launch_attend_t(int NH, int blocks_y, int nsplit, int rows_per_block,
                                   const void* k_a, const void* k_b, const void* v, const void* qv,
                                   const int32_t* sel_idx, const float* sel_score, float* partial,
-                                  void* out, int Hq, int Gq, int S_cap, int d, int n,
-                                  hipStream_t st) {
+                                  void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
+                                  const Ragged& rg, hipStream_t st) {
 #define LOKI_ATT(NHV)                                                                          \
   return launch_attend_nh<T, NHV, GATHER>(blocks_y, nsplit, rows_per_block, k_a, k_b, v, qv,   \
-                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, st)
+                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, st)
   switch (NH) {
     case 1: LOKI_ATT(1);
     case 2: LOKI_ATT(2);
@@ -189,9 +194,9 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   if (s.dtype == 0)
     return launch_attend_t<F32, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, st);
+                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, st);
   return launch_attend_t<BF16, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, st);
+                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, st);
 }
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
@@ -201,9 +206,9 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)
     return launch_attend_t<F32, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, st);
+                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, st);
+                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
 }
 
 hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,

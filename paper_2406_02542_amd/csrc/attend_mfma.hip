@@ -39,7 +39,7 @@ __global__ __launch_bounds__(kAmThreads) void attend_mfma_kernel(
     const int32_t* __restrict__ sel_idx,  // GATHER: [blocks_y, n]
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     uint16_t* __restrict__ out,     // [B*Hq, 128] bf16 when nsplit == 1
-    int S_cap, int d, int n, int rows_per_block, int nsplit) {
+    int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg) {
   constexpr int QT = GATHER ? 3 : 1;
   __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmRows * kAmPitch];  // 8448 B per wave
   __shared__ int32_t s_idx[GATHER ? kMaxGatherChunk : 1];
@@ -52,11 +52,16 @@ __global__ __launch_bounds__(kAmThreads) void attend_mfma_kernel(
   const size_t head0 = (size_t)kv_unit * NH;
   const bool head_ok = r16 < NH;
 
+  // list length of this sequence: the rows it keeps (gather) or holds (dense); a block whose
+  // run starts past the end publishes the neutral partial
+  const int bidx = kv_unit / Hkv;
+  const int n = GATHER ? seq_keep(rg, bidx, n_max, seq_rows(rg, bidx, S_max))
+                       : seq_rows(rg, bidx, n_max);
   const int r0 = blockIdx.x * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
 
   if constexpr (GATHER) {
-    const int32_t* idx = sel_idx + (size_t)blockIdx.y * n;
+    const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
     for (int i = tid; i < r1 - r0; i += kAmThreads) s_idx[i] = idx[r0 + i];
     __syncthreads();
   }
@@ -251,17 +256,18 @@ template <bool GATHER>
 static hipError_t launch_attend_mfma_nh(int NH, int blocks_y, int nsplit, int rpb, const void* k_a,
                                         const void* k_b, const void* v, const void* qv,
                                         const int32_t* sel_idx, float* partial, void* out, int S_cap,
-                                        int d, int n, hipStream_t st) {
+                                        int d, int n, int Hkv, int S_max, const Ragged& rg,
+                                        hipStream_t st) {
   const dim3 grid(nsplit, blocks_y), block(kAmThreads);
   uint16_t* o16 = static_cast<uint16_t*>(out);
   switch (NH) {
     case 4:
       hipLaunchKernelGGL((attend_mfma_kernel<4, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit);
+                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg);
       break;
     case 8:
       hipLaunchKernelGGL((attend_mfma_kernel<8, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit);
+                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg);
       break;
     default:
       return hipErrorInvalidValue;
@@ -277,7 +283,7 @@ hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const vo
                              const void* v, float* partial, void* out, hipStream_t st) {
   const int rpb = (s.S + nsplit - 1) / nsplit;
   return launch_attend_mfma_nh<false>(s.G, s.B * s.Hkv, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      partial, out, s.S_cap, kD, s.S, st);
+                                      partial, out, s.S_cap, kD, s.S, s.Hkv, s.S, s.rg, st);
 }
 
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
@@ -286,7 +292,7 @@ hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, con
   const int rpb = (s.k + nsplit - 1) / nsplit;
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   return launch_attend_mfma_nh<true>(s.G, s.B * s.Hkv, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     partial, out, s.S_cap, s.d, s.k, st);
+                                     partial, out, s.S_cap, s.d, s.k, s.Hkv, s.S, s.rg, st);
 }
 
 }  // namespace loki

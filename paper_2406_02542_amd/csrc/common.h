@@ -11,6 +11,17 @@ namespace loki {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kNegBig = -1.0e30f;  // "no row seen yet" sentinel for running maxima (finite on purpose)
 
+// Rows sequence b holds and rows it keeps (clamped, so a bad entry cannot send a kernel out of
+// bounds); S_max and k_max are the batch-wide limits every buffer is laid out for.
+__device__ __forceinline__ int seq_rows(const Ragged& rg, int b, int S_max) {
+  if (rg.seq_lens == nullptr) return S_max;
+  return min(max(rg.seq_lens[b], 1), S_max);
+}
+__device__ __forceinline__ int seq_keep(const Ragged& rg, int b, int k_max, int S_b) {
+  const int k = rg.ks != nullptr ? rg.ks[b] : k_max;
+  return max(1, min(k, min(k_max, S_b)));
+}
+
 // Debug builds (-DLOKI_PHASE_TIMING) stamp the 100 MHz wall clock at phase boundaries of the
 // fused kernel's blocks so that its time line can be read back; a no-op otherwise.
 #ifdef LOKI_PHASE_TIMING

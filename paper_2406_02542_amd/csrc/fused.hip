@@ -22,27 +22,33 @@ __host__ __device__ inline int fused_keys_per_thread(int S) {
 // Two blocks share a CU (4 waves per SIMD): the register budget is 128 VGPRs and the compiler
 // is told not to trade load-level parallelism for a higher occupancy that cannot happen.
 // KPT = keys a thread holds in the select stage (8 for S <= 4096, else 16).
-template <typename T, int LPR, bool REUSE_LO, int KPT>
+// APPEND: the block also rotates the unit's new key with the P_h entries it already holds and
+// writes it, with the new value, into row S-1 of the unit's cache before it scores.  The block's
+// own later reads of that row go through the same L1 and see it after the barrier; no other
+// block reads this unit's rows.
+template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND>
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 fused_decode_kernel(
-    const typename T::store_t* __restrict__ klo, const typename T::store_t* __restrict__ khi,
-    const typename T::store_t* __restrict__ v, const typename T::store_t* __restrict__ q,
-    const float* __restrict__ P, typename T::store_t* __restrict__ out,
-    int32_t* __restrict__ out_idx, int Hkv, int S, int S_cap, int d, int k) {
+    const typename T::store_t* klo, const typename T::store_t* khi, const typename T::store_t* v,
+    const typename T::store_t* __restrict__ q, const float* __restrict__ P,
+    typename T::store_t* __restrict__ out, int32_t* __restrict__ out_idx, int Hkv, int S_max,
+    int S_cap, int d, int k_max, Ragged rag, Append ap) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;
   constexpr int RPW = 64 / LPRV;
 
   extern __shared__ __align__(16) unsigned char dyn_smem[];
-  const int per_thread = fused_keys_per_thread(S);               // multiple of 4, <= kFusedKPT
+  const int per_thread = fused_keys_per_thread(S_max);           // multiple of 4, <= kFusedKPT
   float* s_score = reinterpret_cast<float*>(dyn_smem);           // [kFusedThreads * per_thread]
-  int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + kFusedThreads * per_thread);  // [k]
-  float* s_a = reinterpret_cast<float*>(s_idx + k);              // [k]
+  int32_t* s_idx = reinterpret_cast<int32_t*>(s_score + kFusedThreads * per_thread);  // [k_max]
+  float* s_a = reinterpret_cast<float*>(s_idx + k_max);          // [k_max]
 
   __shared__ __align__(16) float s_q[kD];
   __shared__ __align__(8) float s_part[kRotParts][kD];
   __shared__ float s_qhat[1][kD];
+  __shared__ __align__(16) float s_kn[APPEND ? kD : 4];                       // the new key
+  __shared__ __align__(8) float s_partk[APPEND ? kRotParts : 1][APPEND ? kD : 2];
   static_assert(kFusedWaves == kRotParts, "one wave per part of the rotation");
   __shared__ ResidentSelectSmem<kFusedThreads> s_sel;
   __shared__ MergeSmem<kFusedWaves, 1> s_merge;
@@ -50,6 +56,8 @@ fused_decode_kernel(
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
   const int h = unit % Hkv;
+  const int S = seq_rows(rag, unit / Hkv, S_max);
+  const int k = seq_keep(rag, unit / Hkv, k_max, S);
 
   LOKI_STAMP(0);
 #ifdef LOKI_PHASE_TIMING
@@ -71,6 +79,11 @@ fused_decode_kernel(
   // thread's 16 x 2 entries of P_h, then the first slab loads, which do not need qhat and stay
   // in flight during the rotation.
   const float q_mine = T::load1(q + (size_t)unit * kD + (tid & (kD - 1)));  // no branch: no early wait
+  float kn_mine = 0.f, vn_mine = 0.f;
+  if constexpr (APPEND) {
+    kn_mine = T::load1(static_cast<const ST*>(ap.k_new) + (size_t)unit * kD + (tid & (kD - 1)));
+    vn_mine = T::load1(static_cast<const ST*>(ap.v_new) + (size_t)unit * kD + (tid & (kD - 1)));
+  }
   // qhat = q P_h with the association every path uses (8 parts of 16 terms, parts added in
   // order): wave w owns part w, lane l columns 2l and 2l+1; a load instruction of the wave
   // covers one 512-byte row of P_h.
@@ -86,12 +99,13 @@ fused_decode_kernel(
     score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
 
   s_q[tid & (kD - 1)] = q_mine;  // four threads store the same value: no branch to sink the load into
+  if constexpr (APPEND) s_kn[tid & (kD - 1)] = kn_mine;
   __syncthreads();
-  {
+  auto rotate_part = [&](const float* vec, float* part_row) {
     float a0 = 0.f, a1 = 0.f;
 #pragma unroll
     for (int i4 = 0; i4 < kRotPartLen; i4 += 4) {
-      const float4 qq = *reinterpret_cast<const float4*>(&s_q[wave * kRotPartLen + i4]);
+      const float4 qq = *reinterpret_cast<const float4*>(&vec[wave * kRotPartLen + i4]);
       a0 = fmaf(qq.x, pv[i4 + 0].x, a0);
       a1 = fmaf(qq.x, pv[i4 + 0].y, a1);
       a0 = fmaf(qq.y, pv[i4 + 1].x, a0);
@@ -101,8 +115,10 @@ fused_decode_kernel(
       a0 = fmaf(qq.w, pv[i4 + 3].x, a0);
       a1 = fmaf(qq.w, pv[i4 + 3].y, a1);
     }
-    *reinterpret_cast<float2*>(&s_part[wave][2 * lane]) = make_float2(a0, a1);
-  }
+    *reinterpret_cast<float2*>(&part_row[2 * lane]) = make_float2(a0, a1);
+  };
+  rotate_part(s_q, s_part[wave]);
+  if constexpr (APPEND) rotate_part(s_kn, s_partk[wave]);
   __syncthreads();
   if (tid < kD) {
     float sum = 0.f;
@@ -110,7 +126,28 @@ fused_decode_kernel(
     for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[pp][tid];
     s_qhat[0][tid] = sum;
   }
+  if constexpr (APPEND) {
+    // row S-1 of the unit's cache: rotated key (columns < d to the low-rank slab, the rest to
+    // the residual slab) by threads 128..255, value by threads 256..383
+    const size_t row = (size_t)unit * S_cap + (size_t)(S - 1);
+    if (tid >= kD && tid < 2 * kD) {
+      const int j = tid - kD;
+      float sum = 0.f;
+#pragma unroll
+      for (int pp = 0; pp < kRotParts; ++pp) sum += s_partk[pp][j];
+      ST* dst = j < d ? const_cast<ST*>(klo) + row * d + j : const_cast<ST*>(khi) + row * (kD - d) + (j - d);
+      T::store1(dst, sum);
+    } else if (tid >= 2 * kD && tid < 3 * kD) {
+      T::store1(const_cast<ST*>(v) + row * kD + (tid - 2 * kD), vn_mine);
+    }
+  }
   __syncthreads();
+  if constexpr (APPEND && kPipelined) {
+    // the loads put in flight before the rotation may have read row S-1 before it was written
+    constexpr int kFirstTripRows = kFusedWaves * 64 * ScoreTrip<kPipelined ? LPR : 8>::TPI;
+    if (S - 1 < kFirstTripRows)
+      score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
+  }
 
   LOKI_STAMP(1);
   // ---- approximate scores over the low-rank slab, into LDS ------------------------------
@@ -128,7 +165,9 @@ fused_decode_kernel(
   LOKI_STAMP(2);
 
   // ---- top-k in LDS ------------------------------------------------------------------------
-  int32_t* gidx = out_idx ? out_idx + (size_t)unit * k : nullptr;
+  int32_t* gidx = out_idx ? out_idx + (size_t)unit * k_max : nullptr;
+  if (gidx)
+    for (int i = k + tid; i < k_max; i += kFusedThreads) gidx[i] = -1;  // a sequence keeping fewer rows
   block_select_topk_resident<kFusedThreads, KPT>(s_score, S, k, per_thread, s_sel,
                                                        [&](int rank, int pos, float score) {
     s_idx[rank] = pos;
@@ -179,12 +218,11 @@ bool fused_preferred(const Shape& s) {
   return units >= 192 || s.S <= 2048;
 }
 
-template <typename T, int LPR, bool REUSE_LO, int KPT>
-static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, const void* klo,
-                                 const void* khi, const void* v, void* out, int32_t* out_idx,
-                                 hipStream_t st) {
+template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND>
+static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                                 void* v, void* out, int32_t* out_idx, hipStream_t st) {
   using ST = typename T::store_t;
-  auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT>;
+  auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT, APPEND>;
   const size_t lds = fused_dynamic_lds(s);
   static bool attr_set = false;  // benign race: every caller sets the same value
   if (!attr_set) {
@@ -197,31 +235,36 @@ static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, 
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(kFusedThreads), lds, st,
                      static_cast<const ST*>(klo), static_cast<const ST*>(khi),
                      static_cast<const ST*>(v), static_cast<const ST*>(q), P, static_cast<ST*>(out),
-                     out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k);
+                     out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k, s.rg, s.ap);
   return hipGetLastError();
 }
 
+template <typename T, int LPR, bool REUSE_LO, int KPT>
+static hipError_t launch_fused_a(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                                 void* v, void* out, int32_t* out_idx, hipStream_t st) {
+  if (s.ap.k_new != nullptr)
+    return launch_fused_k<T, LPR, REUSE_LO, KPT, true>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_k<T, LPR, REUSE_LO, KPT, false>(s, q, P, klo, khi, v, out, out_idx, st);
+}
+
 template <typename T, int LPR, bool REUSE_LO>
-static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, const void* klo,
-                                 const void* khi, const void* v, void* out, int32_t* out_idx,
-                                 hipStream_t st) {
+static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                                 void* v, void* out, int32_t* out_idx, hipStream_t st) {
   if (fused_keys_per_thread(s.S) <= 8)
-    return launch_fused_k<T, LPR, REUSE_LO, 8>(s, q, P, klo, khi, v, out, out_idx, st);
-  return launch_fused_k<T, LPR, REUSE_LO, kFusedKPT>(s, q, P, klo, khi, v, out, out_idx, st);
+    return launch_fused_a<T, LPR, REUSE_LO, 8>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_a<T, LPR, REUSE_LO, kFusedKPT>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <typename T, int LPR>
-static hipError_t launch_fused_l(const Shape& s, const void* q, const float* P, const void* klo,
-                                 const void* khi, const void* v, void* out, int32_t* out_idx,
-                                 hipStream_t st) {
+static hipError_t launch_fused_l(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                                 void* v, void* out, int32_t* out_idx, hipStream_t st) {
   if (s.d < kD) return launch_fused_r<T, LPR, true>(s, q, P, klo, khi, v, out, out_idx, st);
   return launch_fused_r<T, LPR, false>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <typename T>
-static hipError_t launch_fused_t(const Shape& s, const void* q, const float* P, const void* klo,
-                                 const void* khi, const void* v, void* out, int32_t* out_idx,
-                                 hipStream_t st) {
+static hipError_t launch_fused_t(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                                 void* v, void* out, int32_t* out_idx, hipStream_t st) {
   const int nch = s.d / T::EPC;
   int lpr = 1;
   while (lpr < nch) lpr <<= 1;
@@ -238,9 +281,8 @@ static hipError_t launch_fused_t(const Shape& s, const void* q, const float* P, 
   }
 }
 
-hipError_t launch_fused(const Shape& s, const void* q, const float* P, const void* klo,
-                        const void* khi, const void* v, void* out, int32_t* out_idx,
-                        hipStream_t st) {
+hipError_t launch_fused(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                        void* v, void* out, int32_t* out_idx, hipStream_t st) {
   if (!fused_eligible(s)) return hipErrorInvalidValue;
   return s.dtype == 0 ? launch_fused_t<F32>(s, q, P, klo, khi, v, out, out_idx, st)
                       : launch_fused_t<BF16>(s, q, P, klo, khi, v, out, out_idx, st);

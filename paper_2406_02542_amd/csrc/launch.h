@@ -9,12 +9,27 @@ namespace loki {
 
 constexpr int kD = 128;  // head dimension the kernels are written for
 
+// Per-sequence sizes of a ragged batch, in device memory (a null pointer: the batch-wide value).
+struct Ragged {
+  const int32_t* seq_lens = nullptr;  // [B] cached rows of each sequence, 1..S
+  const int32_t* ks = nullptr;        // [B] rows each sequence keeps, 1..min(k, its seq_len)
+};
+
+// The current token's key and value when the step also appends them to the cache (Algorithm 1
+// lines 3-4 folded into the decode launch); both null otherwise.
+struct Append {
+  const void* k_new = nullptr;  // [B, Hkv, 128] unrotated key, storage type
+  const void* v_new = nullptr;  // [B, Hkv, 128]
+};
+
 struct Shape {
   int B, Hq, Hkv, G;  // G = Hq / Hkv
-  int S, S_cap;
+  int S, S_cap;       // S, k: the largest of the batch when `rg` gives per-sequence values
   int d, k;
   int dtype;        // 0 f32, 1 bf16
   int elem_bytes;   // 4 or 2
+  Ragged rg;
+  Append ap;
 };
 
 // Grid-shaping decisions; pure functions of the shape so that workspace sizing (host only)
@@ -41,7 +56,10 @@ struct Workspace {
 // Lays the workspace out from `base` (may be null to only size it).
 Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base);
 
-hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, hipStream_t st);
+// Rotates every query; with s.ap set also rotates the new key of every unit and writes it and
+// the new value into row seq_len-1 of the unit's cache.
+hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
+                       void* khi, void* v, hipStream_t st);
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st);
 size_t select_scratch_words(int S, int n_sel_heads);
@@ -64,9 +82,8 @@ hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void
 // Fused single-kernel decode step (one query head per KV head only).
 bool fused_eligible(const Shape& s);
 bool fused_preferred(const Shape& s);
-hipError_t launch_fused(const Shape& s, const void* q, const float* P, const void* klo,
-                        const void* khi, const void* v, void* out, int32_t* out_idx,
-                        hipStream_t st);
+hipError_t launch_fused(const Shape& s, const void* q, const float* P, void* klo, void* khi,
+                        void* v, void* out, int32_t* out_idx, hipStream_t st);
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
                          int pos, int n_new, hipStream_t st);
 

@@ -15,12 +15,21 @@ namespace loki {
 // the same association as the fused decode kernel, so every path sees bit-identical qhat.
 constexpr int kQrotCols = 32;
 
-template <typename T, int G>
+// APPEND: the unit's new key is rotated as one more vector beside the G queries and written,
+// with the new value, into row seq_len-1 of the unit's cache; the kernels launched after this
+// one see the row.
+template <typename T, int G, bool APPEND>
 __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __restrict__ q,
                                                    const float* __restrict__ P,
-                                                   float* __restrict__ qhat_out, int Hkv) {
-  __shared__ __align__(16) float s_q[G][kD];
-  __shared__ float s_part[G][kRotParts][kQrotCols];
+                                                   float* __restrict__ qhat_out, int Hkv,
+                                                   typename T::store_t* __restrict__ klo,
+                                                   typename T::store_t* __restrict__ khi,
+                                                   typename T::store_t* __restrict__ v, int S_max,
+                                                   int S_cap, int d, Ragged rg, Append ap) {
+  using ST = typename T::store_t;
+  constexpr int NV = G + (APPEND ? 1 : 0);
+  __shared__ __align__(16) float s_q[NV][kD];
+  __shared__ float s_part[NV][kRotParts][kQrotCols];
   const int tid = threadIdx.x;
   const int unit = blockIdx.x;
   const int h = unit % Hkv;
@@ -33,9 +42,16 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
 #pragma unroll
   for (int ii = 0; ii < kRotPartLen; ++ii) pv[ii] = Ph[(size_t)(part * kRotPartLen + ii) * kD];
   for (int i = tid; i < G * kD; i += 256) s_q[i / kD][i % kD] = T::load1(q + head0 * kD + i);
+  size_t row = 0;
+  if constexpr (APPEND) {
+    if (tid < kD) s_q[G][tid] = T::load1(static_cast<const ST*>(ap.k_new) + (size_t)unit * kD + tid);
+    row = (size_t)unit * S_cap + (size_t)(seq_rows(rg, unit / Hkv, S_max) - 1);
+    if (blockIdx.y == 0 && tid >= kD)  // the value row is copied once per unit
+      v[row * kD + (tid - kD)] = static_cast<const ST*>(ap.v_new)[(size_t)unit * kD + (tid - kD)];
+  }
   __syncthreads();
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
+  for (int g = 0; g < NV; ++g) {
     float acc = 0.f;
 #pragma unroll
     for (int i4 = 0; i4 < kRotPartLen; i4 += 4) {
@@ -48,22 +64,31 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
     s_part[g][part][jl] = acc;
   }
   __syncthreads();
-  for (int i = tid; i < G * kQrotCols; i += 256) {
+  for (int i = tid; i < NV * kQrotCols; i += 256) {
     const int g = i / kQrotCols, jj = i % kQrotCols;
     float sum = 0.f;
 #pragma unroll
     for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[g][pp][jj];
-    qhat_out[(head0 + g) * kD + blockIdx.y * kQrotCols + jj] = sum;
+    const int col = blockIdx.y * kQrotCols + jj;
+    if (g < G) {
+      qhat_out[(head0 + g) * kD + col] = sum;
+    } else {
+      ST* dst = col < d ? klo + row * d + col : khi + row * (kD - d) + (col - d);
+      T::store1(dst, sum);
+    }
   }
 }
 
 template <typename T, int LPR, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_kernel(
     const typename T::store_t* __restrict__ klo, const float* __restrict__ qhat,
-    float* __restrict__ scores, int Hkv, int S, int S_cap, int d, int rows_per_block) {
+    float* __restrict__ scores, int Hkv, int S_max, int S_cap, int d, int rows_per_block,
+    Ragged rg) {
   constexpr int EPC = T::EPC;
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
+  const int S = seq_rows(rg, unit / Hkv, S_max);  // the score buffer keeps the stride S_max
+  if ((int)blockIdx.x * rows_per_block >= S) return;
   const int head0 = unit * G;  // first query head of the group, flattened over batch
 
   const int lane = tid & 63;
@@ -88,11 +113,11 @@ __global__ __launch_bounds__(256) void score_kernel(
                                float m = sc[0];
 #pragma unroll
                                for (int g = 1; g < G; ++g) m = fmaxf(m, sc[g]);
-                               scores[(size_t)unit * S + row] = m;
+                               scores[(size_t)unit * S_max + row] = m;
                              } else {
 #pragma unroll
                                for (int g = 0; g < G; ++g)
-                                 scores[(size_t)(head0 + g) * S + row] = sc[g];
+                                 scores[(size_t)(head0 + g) * S_max + row] = sc[g];
                              }
                            });
 }
@@ -136,8 +161,10 @@ __device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (
 template <int NCH, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_mfma_kernel(
     const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
-    int Hkv, int S, int S_cap, int rows_per_block) {
+    int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg) {
   constexpr int d = 8 * NCH;
+  const int S = seq_rows(rg, (int)blockIdx.y / Hkv, S_max);  // the score buffer keeps the stride S_max
+  if ((int)blockIdx.x * rows_per_block >= S) return;
   constexpr int RB = NCH <= 4 ? 4 / NCH : 1;   // 16-row blocks one load instruction covers
   constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
   constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
@@ -170,7 +197,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
                      (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
-  const bool vec_ok = (S & 3) == 0;
+  const bool vec_ok = (S_max & 3) == 0;
 
   for (int t0 = row0 + wave * RPS; t0 < row_end; t0 += 4 * RPS * UN) {
     uint4 raw[UN][NL];
@@ -212,9 +239,9 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
 #pragma unroll
           for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<16>(head_ok ? v[i] : -3.0e38f);
           writer = r16 == 0;
-          dst = scores + (size_t)unit * S + rowbase;
+          dst = scores + (size_t)unit * S_max + rowbase;
         } else {
-          dst = scores + (size_t)(head0 + (head_ok ? r16 : 0)) * S + rowbase;
+          dst = scores + (size_t)(head0 + (head_ok ? r16 : 0)) * S_max + rowbase;
         }
         if (writer && rowbase < row_end) {
           if (vec_ok && rowbase + 3 < row_end) {
@@ -237,10 +264,10 @@ static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const voi
   dim3 grid((s.S + rpb - 1) / rpb, s.B * s.Hkv);
   if (select_mode == 1) {
     hipLaunchKernelGGL((score_mfma_kernel<NCH, G, true>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb);
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg);
   } else {
     hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb);
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg);
   }
   return hipGetLastError();
 }
@@ -283,10 +310,10 @@ static hipError_t launch_score_g(const Shape& s, int select_mode, const void* q,
   const bool gm = (select_mode == 1) && (G > 1);
   if (gm) {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, (G > 1)>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg);
   } else {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg);
   }
   return hipGetLastError();
 }
@@ -322,23 +349,34 @@ static hipError_t launch_score_t(const Shape& s, int select_mode, const void* q,
   }
 }
 
-template <typename T>
-static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, float* qhat,
-                                hipStream_t st) {
+template <typename T, bool APPEND>
+static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
+                                void* khi, void* v, hipStream_t st) {
   using ST = typename T::store_t;
   const dim3 grid(s.B * s.Hkv, kD / kQrotCols), block(256);
+#define LOKI_QROT(GV)                                                                            \
+  hipLaunchKernelGGL((qrot_kernel<T, GV, APPEND>), grid, block, 0, st, static_cast<const ST*>(q), P, \
+                     qhat, s.Hkv, static_cast<ST*>(klo), static_cast<ST*>(khi), static_cast<ST*>(v), \
+                     s.S, s.S_cap, s.d, s.rg, s.ap);                                             \
+  break
   switch (s.G) {
-    case 1: hipLaunchKernelGGL((qrot_kernel<T, 1>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
-    case 2: hipLaunchKernelGGL((qrot_kernel<T, 2>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
-    case 4: hipLaunchKernelGGL((qrot_kernel<T, 4>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
-    case 8: hipLaunchKernelGGL((qrot_kernel<T, 8>), grid, block, 0, st, static_cast<const ST*>(q), P, qhat, s.Hkv); break;
+    case 1: LOKI_QROT(1);
+    case 2: LOKI_QROT(2);
+    case 4: LOKI_QROT(4);
+    case 8: LOKI_QROT(8);
     default: return hipErrorInvalidValue;
   }
+#undef LOKI_QROT
   return hipGetLastError();
 }
 
-hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, hipStream_t st) {
-  return s.dtype == 0 ? launch_qrot_t<F32>(s, q, P, qhat, st) : launch_qrot_t<BF16>(s, q, P, qhat, st);
+hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
+                       void* khi, void* v, hipStream_t st) {
+  if (s.ap.k_new != nullptr)
+    return s.dtype == 0 ? launch_qrot_t<F32, true>(s, q, P, qhat, klo, khi, v, st)
+                        : launch_qrot_t<BF16, true>(s, q, P, qhat, klo, khi, v, st);
+  return s.dtype == 0 ? launch_qrot_t<F32, false>(s, q, P, qhat, klo, khi, v, st)
+                      : launch_qrot_t<BF16, false>(s, q, P, qhat, klo, khi, v, st);
 }
 
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,

@@ -22,11 +22,15 @@ template <int THREADS>
 __global__ __launch_bounds__(THREADS, 8) void select_resident_kernel(const float* __restrict__ scores,
                                                                   int32_t* __restrict__ sel_idx,
                                                                   float* __restrict__ sel_score,
-                                                                  int S, int k, int per_thread) {
+                                                                  int S_max, int k_max, int per_thread,
+                                                                  int heads_per_seq, Ragged rg) {
   __shared__ ResidentSelectSmem<THREADS> sm;
-  const float* a = scores + (size_t)blockIdx.x * S;
-  int32_t* out = sel_idx + (size_t)blockIdx.x * k;
-  float* outs = sel_score + (size_t)blockIdx.x * k;
+  const int b = (int)blockIdx.x / heads_per_seq;
+  const int S = seq_rows(rg, b, S_max), k = seq_keep(rg, b, k_max, S);
+  const float* a = scores + (size_t)blockIdx.x * S_max;
+  int32_t* out = sel_idx + (size_t)blockIdx.x * k_max;
+  float* outs = sel_score + (size_t)blockIdx.x * k_max;
+  for (int i = k + (int)threadIdx.x; i < k_max; i += THREADS) out[i] = -1;  // a sequence keeping fewer rows
   LOKI_STAMP(0);
   resident_select_clear<THREADS>(sm);
   __syncthreads();
@@ -50,7 +54,9 @@ union StreamScratch {
 template <bool VEC4>
 __global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
     const float* __restrict__ scores, int32_t* __restrict__ sel_idx, float* __restrict__ sel_score,
-    int S, int k) {
+    int S_max, int k_max, int heads_per_seq, Ragged rg) {
+  const int S = seq_rows(rg, (int)blockIdx.x / heads_per_seq, S_max);
+  const int k = seq_keep(rg, (int)blockIdx.x / heads_per_seq, k_max, S);
   // loads a lane keeps in flight: a block streams alone on its CU, so the bytes in flight set
   // its bandwidth (16 x 16 B x 1024 threads = 256 KiB); the unaligned variant uses four
   // scalar loads per step and would spill at that depth
@@ -61,9 +67,10 @@ __global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
   __shared__ uint32_t s_ncand;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const float* a = scores + (size_t)blockIdx.x * S;
-  int32_t* out = sel_idx + (size_t)blockIdx.x * k;
-  float* outs = sel_score + (size_t)blockIdx.x * k;
+  const float* a = scores + (size_t)blockIdx.x * S_max;
+  int32_t* out = sel_idx + (size_t)blockIdx.x * k_max;
+  float* outs = sel_score + (size_t)blockIdx.x * k_max;
+  for (int i = k + tid; i < k_max; i += kStreamThreads) out[i] = -1;  // a sequence keeping fewer rows
 
   // wave w owns positions [w0, w1), a whole number of tiles
   const int per_wave =
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(kStreamThreads) void select_stream_kernel(
   const int w0 = min(S, wave * per_wave), w1 = min(S, w0 + per_wave);
 
   auto load4 = [&](int pos, float (&f)[4], bool (&ok)[4]) {
-    if (VEC4) {  // S % 4 == 0: the head's base and pos are 16-byte aligned, pos + 3 < S
+    if (VEC4 && (S & 3) == 0) {  // the head's base and pos are 16-byte aligned, pos + 3 < S
       const bool in = pos < w1;
       float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
       if (in) v = *reinterpret_cast<const float4*>(a + pos);
@@ -254,12 +261,14 @@ __host__ __device__ inline int mb_meta_stride(int nc) { return 4 * nc + 8; }
 
 __global__ __launch_bounds__(kMbThreads, 8) void mb_hist_kernel(const float* __restrict__ scores,
                                                                 uint32_t* __restrict__ hist_part,
-                                                                int S, int nc) {
+                                                                int S_max, int nc, int heads_per_seq,
+                                                                Ragged rg) {
   __shared__ uint32_t s_hist[2048];
   const int tid = threadIdx.x, chunk = blockIdx.x, head = blockIdx.y;
-  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
+  const int S = seq_rows(rg, head / heads_per_seq, S_max);
+  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);  // <= 0 past a short sequence's end
   uint32_t key[kSelKPT], valid_mask;
-  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S_max + c0, n, kSelKPT, key, valid_mask);
   s_hist[tid] = 0u;
   s_hist[tid + kMbThreads] = 0u;
   __syncthreads();
@@ -273,10 +282,15 @@ __global__ __launch_bounds__(kMbThreads, 8) void mb_hist_kernel(const float* __r
 }
 
 __global__ __launch_bounds__(kMbThreads) void mb_bin_kernel(const uint32_t* __restrict__ hist_part,
-                                                            uint32_t* __restrict__ meta, int k,
-                                                            int nc) {
+                                                            uint32_t* __restrict__ meta,
+                                                            int32_t* __restrict__ sel_idx, int S_max,
+                                                            int k_max, int nc, int heads_per_seq,
+                                                            Ragged rg) {
   __shared__ ResidentSelectSmem<kMbThreads> sm;
   const int tid = threadIdx.x, head = blockIdx.x;
+  const int k = seq_keep(rg, head / heads_per_seq, k_max, seq_rows(rg, head / heads_per_seq, S_max));
+  for (int i = k + tid; i < k_max; i += kMbThreads)
+    sel_idx[(size_t)head * k_max + i] = -1;  // a sequence keeping fewer rows
   const uint32_t* src = hist_part + (size_t)head * nc * 2048;
   uint32_t h0 = 0, h1 = 0;
   for (int c = 0; c < nc; ++c) {
@@ -298,16 +312,18 @@ __global__ __launch_bounds__(kMbThreads) void mb_bin_kernel(const uint32_t* __re
 __global__ __launch_bounds__(kMbThreads, 8) void mb_collect_kernel(const float* __restrict__ scores,
                                                                    uint32_t* __restrict__ meta,
                                                                    uint32_t* __restrict__ cand,
-                                                                   int S, int nc) {
+                                                                   int S_max, int nc,
+                                                                   int heads_per_seq, Ragged rg) {
   __shared__ uint32_t s_ncand, s_gt;
   const int tid = threadIdx.x, lane = tid & 63, chunk = blockIdx.x, head = blockIdx.y;
+  const int S = seq_rows(rg, head / heads_per_seq, S_max);
   const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
   uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
   const uint32_t bin1 = m[4 * nc];
   const int cap = mb_cand_cap(nc);
   uint32_t* my_cand = cand + (size_t)head * kMbChunk + (size_t)chunk * cap;
   uint32_t key[kSelKPT], valid_mask;
-  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S_max + c0, n, kSelKPT, key, valid_mask);
   if (tid == 0) {
     s_ncand = 0u;
     s_gt = 0u;
@@ -335,9 +351,12 @@ __global__ __launch_bounds__(kMbThreads, 8) void mb_collect_kernel(const float* 
 
 __global__ __launch_bounds__(kMbThreads) void mb_resolve_kernel(
     const float* __restrict__ scores, uint32_t* __restrict__ meta, const uint32_t* __restrict__ cand,
-    int32_t* __restrict__ sel_idx, float* __restrict__ sel_score, int S, int k, int nc) {
+    int32_t* __restrict__ sel_idx, float* __restrict__ sel_score, int S_max, int k_max, int nc,
+    int heads_per_seq, Ragged rg) {
   __shared__ ResidentSelectSmem<kMbThreads> sm;
   __shared__ SelectSmem<kMbThreads> generic;
+  const int S = seq_rows(rg, (int)blockIdx.x / heads_per_seq, S_max);
+  const int k = seq_keep(rg, (int)blockIdx.x / heads_per_seq, k_max, S);
   __shared__ uint32_t s_cg[64], s_ce[64];
   __shared__ uint32_t s_over;
   const int tid = threadIdx.x, head = blockIdx.x;
@@ -354,9 +373,9 @@ __global__ __launch_bounds__(kMbThreads) void mb_resolve_kernel(
   __syncthreads();
   if (s_over) {
     if (tid == 0) m[4 * nc + 4] = 1u;
-    const float* a = scores + (size_t)head * S;
-    int32_t* out = sel_idx + (size_t)head * k;
-    float* outs = sel_score + (size_t)head * k;
+    const float* a = scores + (size_t)head * S_max;
+    int32_t* out = sel_idx + (size_t)head * k_max;
+    float* outs = sel_score + (size_t)head * k_max;
     block_select_topk<kMbThreads>(a, S, k, generic, [&](int rank, int pos) {
       out[rank] = pos;
       outs[rank] = a[pos];
@@ -406,16 +425,18 @@ __global__ __launch_bounds__(kMbThreads, 8) void mb_write_kernel(const float* __
                                                                  const uint32_t* __restrict__ meta,
                                                                  int32_t* __restrict__ sel_idx,
                                                                  float* __restrict__ sel_score,
-                                                                 int S, int k, int nc) {
+                                                                 int S_max, int k_max, int nc,
+                                                                 int heads_per_seq, Ragged rg) {
   __shared__ uint32_t s_wave[2][kMbThreads / 64];
   const int chunk = blockIdx.x, head = blockIdx.y;
+  const int S = seq_rows(rg, head / heads_per_seq, S_max);
   const uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
   if (m[4 * nc + 4]) return;  // the head was finished by mb_resolve_kernel
   const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
   uint32_t key[kSelKPT], valid_mask;
-  resident_load_keys<kSelKPT>(scores + (size_t)head * S + c0, n, kSelKPT, key, valid_mask);
-  int32_t* out = sel_idx + (size_t)head * k;
-  float* outs = sel_score + (size_t)head * k;
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S_max + c0, n, kSelKPT, key, valid_mask);
+  int32_t* out = sel_idx + (size_t)head * k_max;
+  float* outs = sel_score + (size_t)head * k_max;
   resident_compact<kMbThreads, kSelKPT>(key, valid_mask, kSelKPT, m[4 * nc + 2], m[4 * nc + 3],
                                         m[2 * nc + 2 * chunk], m[2 * nc + 2 * chunk + 1], s_wave[0],
                                         s_wave[1], [&](int rank, int pos, float score) {
@@ -439,13 +460,15 @@ static hipError_t launch_select_multiblock(const Shape& s, int heads, const floa
   uint32_t* cand = hist_part + (size_t)heads * nc * 2048;
   uint32_t* meta = cand + (size_t)heads * kMbChunk;
   const dim3 wide(nc, heads), narrow(heads), block(kMbThreads);
-  hipLaunchKernelGGL(mb_hist_kernel, wide, block, 0, st, scores, hist_part, s.S, nc);
-  hipLaunchKernelGGL(mb_bin_kernel, narrow, block, 0, st, hist_part, meta, s.k, nc);
-  hipLaunchKernelGGL(mb_collect_kernel, wide, block, 0, st, scores, meta, cand, s.S, nc);
+  const int hps = heads / s.B;  // selecting heads per sequence
+  hipLaunchKernelGGL(mb_hist_kernel, wide, block, 0, st, scores, hist_part, s.S, nc, hps, s.rg);
+  hipLaunchKernelGGL(mb_bin_kernel, narrow, block, 0, st, hist_part, meta, sel_idx, s.S, s.k, nc, hps,
+                     s.rg);
+  hipLaunchKernelGGL(mb_collect_kernel, wide, block, 0, st, scores, meta, cand, s.S, nc, hps, s.rg);
   hipLaunchKernelGGL(mb_resolve_kernel, narrow, block, 0, st, scores, meta, cand, sel_idx,
-                     sel_score, s.S, s.k, nc);
+                     sel_score, s.S, s.k, nc, hps, s.rg);
   hipLaunchKernelGGL(mb_write_kernel, wide, block, 0, st, scores, meta, sel_idx, sel_score, s.S,
-                     s.k, nc);
+                     s.k, nc, hps, s.rg);
   return hipGetLastError();
 }
 
@@ -460,20 +483,21 @@ hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, i
                          float* sel_score, uint32_t* scratch, hipStream_t st) {
   if (scratch != nullptr && select_scratch_words(s.S, n_sel_heads) != 0)
     return launch_select_multiblock(s, n_sel_heads, scores, sel_idx, sel_score, scratch, st);
+  const int hps = n_sel_heads / s.B;  // selecting heads per sequence
   if (s.S <= 512 * kSelKPT) {
     const int per_thread = (((s.S + 511) / 512) + 3) & ~3;
     hipLaunchKernelGGL(select_resident_kernel<512>, dim3(n_sel_heads), dim3(512), 0, st, scores,
-                       sel_idx, sel_score, s.S, s.k, per_thread);
+                       sel_idx, sel_score, s.S, s.k, per_thread, hps, s.rg);
   } else if (s.S <= 1024 * kSelKPT) {
     const int per_thread = (((s.S + 1023) / 1024) + 3) & ~3;
     hipLaunchKernelGGL(select_resident_kernel<1024>, dim3(n_sel_heads), dim3(1024), 0, st, scores,
-                       sel_idx, sel_score, s.S, s.k, per_thread);
+                       sel_idx, sel_score, s.S, s.k, per_thread, hps, s.rg);
   } else if (s.S % 4 == 0) {
     hipLaunchKernelGGL(select_stream_kernel<true>, dim3(n_sel_heads), dim3(kStreamThreads), 0, st,
-                       scores, sel_idx, sel_score, s.S, s.k);
+                       scores, sel_idx, sel_score, s.S, s.k, hps, s.rg);
   } else {
     hipLaunchKernelGGL(select_stream_kernel<false>, dim3(n_sel_heads), dim3(kStreamThreads), 0, st,
-                       scores, sel_idx, sel_score, s.S, s.k);
+                       scores, sel_idx, sel_score, s.S, s.k, hps, s.rg);
   }
   return hipGetLastError();
 }

@@ -124,7 +124,7 @@ def _rng(seed: int, tensor_id: int, unit: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[(seed << 20) ^ tensor_id, unit]))
 
 
-_T_P, _T_K, _T_V, _T_Q, _T_HEAVY = 1, 2, 3, 4, 5
+_T_P, _T_K, _T_V, _T_Q, _T_HEAVY, _T_LEN, _T_KNEW, _T_VNEW = 1, 2, 3, 4, 5, 6, 7, 8
 
 
 def spectrum(D: int, tau: float) -> np.ndarray:
@@ -243,3 +243,33 @@ def make_inputs(w: Workload, threads: int = 8) -> dict:
         "khat": make_khat(w, threads),
         "v": make_v(w, threads),
     }
+
+
+def make_step_inputs(w: Workload, P: np.ndarray, ragged: bool = True, min_frac: float = 0.25) -> dict:
+    """Per-sequence sizes and the current token's key / value for a whole decode step.
+
+    * ``seq_lens`` [B] int32: a length mix of a serving batch, S * u with u uniform in
+      [min_frac, 1]; sequence 0 is full (S) and, with B > 1, sequence 1 is the shortest
+      allowed, so both ends are always present.  ``ragged=False``: all S.
+    * ``ks`` [B] int32: max(1, floor(k_f * seq_len)) with k_f = k / S (Section 4.2
+      states k as a fraction of the sequence).
+    * ``k_new`` [B, Hkv, D]: one more key per unit from the cache's law, in the model's
+      own basis (unrounded rotated draw @ P_h^T), storage-rounded float32.
+    * ``v_new`` [B, Hkv, D] ~ N(0,1), storage-rounded float32."""
+    g = _rng(w.seed, _T_LEN)
+    lo = max(1, int(np.ceil(min_frac * w.S)))
+    lens = g.integers(lo, w.S + 1, size=w.B).astype(np.int32) if ragged else np.full(w.B, w.S, np.int32)
+    if ragged:
+        lens[0] = w.S
+        if w.B > 1:
+            lens[1] = lo
+    kf = w.k / w.S
+    ks = np.maximum(1, np.floor(kf * lens.astype(np.float64))).astype(np.int32)
+    ks = np.minimum(ks, np.minimum(lens, w.k)).astype(np.int32)
+    scale = np.sqrt(spectrum(w.D, w.tau) ** 2 + w.noise_var)
+    c = _rng(w.seed, _T_KNEW).standard_normal((w.B, w.Hkv, w.D)) * scale[None, None, :]
+    k_new = np.einsum("bhj,hij->bhi", c, P.astype(np.float64))  # c @ P_h^T
+    v_new = _rng(w.seed, _T_VNEW).standard_normal((w.B, w.Hkv, w.D))
+    return {"seq_lens": lens, "ks": ks,
+            "k_new": round_storage(k_new.astype(np.float32), w.dtype),
+            "v_new": round_storage(v_new.astype(np.float32), w.dtype)}

@@ -1,0 +1,241 @@
+"""GPU parity of the whole decode step (loki_decode_step: per-sequence lengths and the
+cache append of the current token folded into the decode launches; Algorithm 1 lines 2-9)
+and of dense_decode_step, against the CPU oracle.
+
+Protocol.  The rows the GPU appended are read back and checked on their own against the
+oracle's rotation (bf16: one unit in the last place plus fp32 accumulation, as for
+loki_rotate_keys; values bit-exact); they are then put into the oracle's cache, so that a
+last-place difference in the new key cannot cascade into the selection, and the oracle's
+step (without append) is compared with the GPU's outputs and index lists under the usual
+tolerances, sequence by sequence with each sequence's own length and k.  Rows past a
+sequence's end hold 3e4 in K and -3e4 in V on the GPU: any use of them would show."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import loki_oracle as O
+from paper_2406_02542_amd import api, synth
+from tests.parity import OUT_TOL, TORCH_DT, check_index_set, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=None, use_ks=True):
+    x = synth.make_inputs(w)
+    st = synth.make_step_inputs(w, x["P"], ragged=ragged)
+    if lens is not None:
+        st["seq_lens"] = np.asarray(lens, np.int32)
+        st["ks"] = np.minimum(np.maximum(1, (w.k * st["seq_lens"].astype(np.int64)) // w.S),
+                              np.minimum(st["seq_lens"], w.k)).astype(np.int32)
+    if ks is not None:
+        st["ks"] = np.asarray(ks, np.int32)
+    lens_np, ks_np = st["seq_lens"], st["ks"]
+    if not use_ks:
+        ks_np = np.minimum(lens_np, w.k).astype(np.int32)
+    S_cap = S_cap or w.S
+    say(f"case {w} mode {mode} path {path:#x} ragged {ragged} append {append} lens {lens_np.tolist()[:8]} ks {ks_np.tolist()[:8]}")
+    tdt = TORCH_DT[w.dtype]
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, w.D, w.d, S_cap, tdt)
+    klo, khi, v = api.alloc_cache(lay)
+    klo.fill_(3e4)
+    v.fill_(-3e4)
+    if khi is not None:
+        khi.fill_(3e4)
+    kh = to_dev(x["khat"], w.dtype)
+    vv = to_dev(x["v"], w.dtype)
+    for b in range(w.B):
+        n = int(lens_np[b]) - (1 if append else 0)  # the append fills the last row itself
+        klo[b, :, :n] = kh[b, :, :n, :w.d]
+        if khi is not None:
+            khi[b, :, :n] = kh[b, :, :n, w.d:]
+        v[b, :, :n] = vv[b, :, :n]
+    q = to_dev(x["q"], w.dtype)
+    P = torch.from_numpy(x["P"]).cuda()
+    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+    out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=tdt, device="cuda")
+    eff_mode = 0 if w.G == 1 else mode
+    hsel = w.Hq if eff_mode == 0 else w.Hkv
+    idx = torch.full((w.B, hsel, w.k), -7, dtype=torch.int32, device="cuda")
+    api.loki_decode_step(
+        lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path, ws, out, idx,
+        seq_lens=torch.from_numpy(lens_np).cuda() if ragged or lens is not None else None,
+        ks=torch.from_numpy(ks_np).cuda() if use_ks and (ragged or lens is not None or ks is not None) else None,
+        k_new=to_dev(st["k_new"], w.dtype) if append else None,
+        v_new=to_dev(st["v_new"], w.dtype) if append else None)
+    torch.cuda.synchronize()
+    out_g = out.float().cpu().numpy().astype(np.float64)
+    idx_g = idx.cpu().numpy()
+
+    khat = x["khat"].astype(np.float64).copy()
+    vref = x["v"].astype(np.float64).copy()
+    if append:
+        kcat = torch.cat([klo, khi], dim=-1) if khi is not None else klo
+        for b in range(w.B):
+            r = int(lens_np[b]) - 1
+            got_k = kcat[b, :, r].float().cpu().numpy().astype(np.float64)
+            got_v = v[b, :, r].float().cpu().numpy().astype(np.float64)
+            np.testing.assert_array_equal(got_v, st["v_new"][b].astype(np.float64))
+            for h in range(w.Hkv):
+                ref64 = O.rotate_keys(st["k_new"][b, h][None, :], x["P"][h])[0]
+                ref = O.to_storage(ref64, w.dtype)
+                if w.dtype == "bf16":
+                    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+                    mag = np.abs(st["k_new"][b, h].astype(np.float64)) @ np.abs(x["P"][h].astype(np.float64))
+                    assert np.all(np.abs(got_k[h] - ref) <= ulp * 1.0000001 + 1e-6 * mag), (b, h)
+                else:
+                    assert np.max(np.abs(got_k[h] - ref64)) / np.linalg.norm(ref64) < 2e-6, (b, h)
+            khat[b, :, r] = got_k
+            vref[b, :, r] = got_v
+            # nothing else was written
+            if r + 1 < S_cap:
+                assert torch.all(kcat[b, :, r + 1:] == 3e4) and torch.all(v[b, :, r + 1:] == -3e4)
+            if r > 0:
+                assert torch.equal(kcat[b, :, :r], kh[b, :, :r]) and torch.equal(v[b, :, :r], vv[b, :, :r])
+    out_o, idx_o, sc_o, _, _ = O.loki_decode_step(x["q"], x["P"], khat, vref, w.d, w.k, eff_mode,
+                                                  seq_lens=lens_np, ks=ks_np)
+    tol = OUT_TOL[w.dtype]
+    swaps, max_err = 0, 0.0
+    for b in range(w.B):
+        S_b, k_b = int(lens_np[b]), int(ks_np[b])
+        for h in range(w.Hkv):
+            qheads = range(h * w.G, (h + 1) * w.G)
+            same = {}
+            for hs in (qheads if eff_mode == 0 else [h]):
+                assert np.all(idx_g[b, hs, k_b:] == -1), f"b={b} head={hs}: index list not padded with -1"
+                same[hs] = check_index_set(idx_g[b, hs, :k_b], idx_o[b, hs, :k_b], sc_o[b, hs, :S_b], S_b,
+                                           k_b, f"{w.name} b={b} sel_head={hs}")
+            for hq in qheads:
+                hs = hq if eff_mode == 0 else h
+                ref = out_o[b, hq]
+                if not same[hs]:
+                    swaps += 1
+                    qhat = O.rotate_query(x["q"][b, hq], x["P"][h])
+                    ref = O.attend_selected(qhat, khat[b, h, :S_b], vref[b, h, :S_b],
+                                            idx_g[b, hs, :k_b].astype(np.int64))
+                err = float(np.max(np.abs(out_g[b, hq] - ref)))
+                max_err = max(max_err, err)
+                assert err <= tol, f"{w.name} b={b} hq={hq}: |out - oracle| = {err:.3e} > {tol}"
+    say(f"   max_err {max_err:.3e} heads_with_swaps {swaps}")
+    return out_g, idx_g
+
+
+# ------------------------------------------------------------- one query head per KV head --
+@pytest.mark.parametrize("path", [api.PATH_FUSED, api.PATH_SPLIT])
+@pytest.mark.parametrize("ragged,append", [(True, False), (False, True), (True, True)])
+def test_step_fp32_mha(path, ragged, append):
+    w = synth.Workload("step_f32", 5, 4, 4, 128, 1500, "f32", 32, 300, seed=9100)
+    run_step_case(w, 0, ragged, append, path=path)
+
+
+@pytest.mark.parametrize("path", [api.PATH_FUSED, api.PATH_SPLIT])
+@pytest.mark.parametrize("S,k", [(4096, 1024), (6000, 700)])
+def test_step_bf16_mha(path, S, k):
+    """S = 4096: 8 keys per thread in the fused select; 6000: 16.  Ragged and appending."""
+    w = synth.Workload("step_bf16", 6, 8, 8, 128, S, "bf16", 32, k, seed=9200)
+    run_step_case(w, 0, True, True, path=path)
+
+
+@pytest.mark.parametrize("path", [api.PATH_FUSED, api.PATH_SPLIT])
+def test_step_append_into_short_sequences(path):
+    """The new row lies inside the range the fused kernel pre-loads before it rotates
+    (first 1024 rows): sequence lengths 1, 2, 300, 1024, 1025 and the full 2048."""
+    w = synth.Workload("step_short", 6, 2, 2, 128, 2048, "bf16", 32, 64, seed=9300)
+    run_step_case(w, 0, True, True, path=path, lens=[2048, 1, 2, 300, 1024, 1025])
+
+
+def test_step_full_rank_cache_has_no_residual_slab():
+    """d = D: the whole rotated key goes to the low-rank slab (Exact-TopK of Section 5)."""
+    w = synth.Workload("step_dD", 3, 4, 4, 128, 900, "bf16", 128, 100, seed=9400)
+    run_step_case(w, 0, True, True)
+
+
+def test_step_default_k_is_min_of_k_and_length():
+    """ks = NULL: a sequence shorter than k keeps all its rows."""
+    w = synth.Workload("step_defk", 4, 2, 2, 128, 1024, "f32", 32, 512, seed=9500)
+    run_step_case(w, 0, True, False, lens=[1024, 100, 512, 513], use_ks=False)
+
+
+# ------------------------------------------------------------------------ grouped queries --
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("G,dtype", [(4, "bf16"), (8, "bf16"), (2, "bf16"), (4, "f32")])
+def test_step_gqa(mode, G, dtype):
+    """Split path: matrix-core and vector scoring, resident select, vector and matrix-core
+    gather, with several gather splits whose tail blocks are empty for short sequences."""
+    w = synth.Workload(f"step_g{G}", 4, 2 * G, 2, 128, 5000, dtype, 32, 1200, seed=9600 + G)
+    run_step_case(w, mode, True, True)
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_step_long_sequences_multiblock_select(mode):
+    """S_max = 40000 (three chunks of the multi-block select): one full sequence, one inside
+    the first chunk, one ending just past a chunk boundary."""
+    w = synth.Workload("step_long", 3, 4, 1, 128, 40000, "bf16", 16, 2500, seed=9700)
+    run_step_case(w, mode, True, True, lens=[40000, 9000, 16385 + 16384])
+
+
+# ------------------------------------------------------------------- identities and errors --
+def test_step_without_options_equals_decode_attn_bitwise():
+    w = synth.Workload("step_id", 2, 8, 2, 128, 3000, "bf16", 32, 500, seed=9800)
+    x = synth.make_inputs(w)
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, w.d, w.S, torch.bfloat16)
+    klo, khi, v = api.alloc_cache(lay)
+    kh = to_dev(x["khat"], "bf16")
+    klo.copy_(kh[..., :w.d]); khi.copy_(kh[..., w.d:]); v.copy_(to_dev(x["v"], "bf16"))
+    q, P = to_dev(x["q"], "bf16"), torch.from_numpy(x["P"]).cuda()
+    for mode in (0, 1):
+        ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+        o1 = torch.empty((w.B, w.Hq, 128), dtype=torch.bfloat16, device="cuda")
+        o2 = torch.empty_like(o1)
+        api.loki_decode_attn(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, o1)
+        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, o2)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
+        # uniform lengths given explicitly change nothing either
+        lens = torch.full((w.B,), w.S, dtype=torch.int32, device="cuda")
+        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, o2, seq_lens=lens)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2)
+
+
+def test_step_rejects_half_an_append():
+    w = synth.Workload("step_err", 1, 2, 2, 128, 64, "bf16", 32, 16, seed=9900)
+    lay = api.make_layout(1, 2, 2, 128, 32, 64, torch.bfloat16)
+    klo, khi, v = api.alloc_cache(lay)
+    q = torch.zeros((1, 2, 128), dtype=torch.bfloat16, device="cuda")
+    P = torch.zeros((2, 128, 128), device="cuda")
+    ws = api.alloc_workspace(lay, 64, 32, 16, 0)
+    out = torch.empty_like(q)
+    kn = torch.zeros((1, 2, 128), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(api.LokiError) as e:
+        api.loki_decode_step(lay, q, P, klo, khi, v, 64, 32, 16, 0, ws, out, k_new=kn)
+    assert e.value.status == 1
+
+
+# --------------------------------------------------------------------------- dense baseline --
+@pytest.mark.parametrize("G,dtype", [(1, "bf16"), (4, "bf16"), (8, "bf16"), (2, "f32")])
+def test_dense_step_ragged(G, dtype):
+    w = synth.Workload(f"dense_g{G}", 4, 2 * G, 2, 128, 3000, dtype, 32, 8, seed=9950 + G)
+    x = synth.make_inputs(w)
+    lens = synth.make_step_inputs(w, x["P"])["seq_lens"]
+    say(f"case {w} lens {lens.tolist()}")
+    tdt = TORCH_DT[dtype]
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, w.d, w.S, tdt)
+    kfull = torch.full((w.B, w.Hkv, w.S, 128), 3e4, dtype=tdt, device="cuda")
+    v = torch.full((w.B, w.Hkv, w.S, 128), -3e4, dtype=tdt, device="cuda")
+    kh, vv = to_dev(x["khat"], dtype), to_dev(x["v"], dtype)
+    for b in range(w.B):
+        kfull[b, :, :lens[b]] = kh[b, :, :lens[b]]
+        v[b, :, :lens[b]] = vv[b, :, :lens[b]]
+    ws = torch.empty(max(api.loki_workspace_bytes(lay, w.S, 0, 0, -1), 256), dtype=torch.uint8, device="cuda")
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=tdt, device="cuda")
+    api.dense_decode_step(lay, to_dev(x["q"], dtype), kfull, v, w.S, torch.from_numpy(lens).cuda(), ws, out)
+    torch.cuda.synchronize()
+    got = out.float().cpu().numpy().astype(np.float64)
+    for b in range(w.B):
+        ref = O.dense_decode_batch(x["q"][b:b + 1], x["khat"][b:b + 1, :, :lens[b]], x["v"][b:b + 1, :, :lens[b]])
+        err = np.max(np.abs(got[b] - ref[0]))
+        assert err <= OUT_TOL[dtype], f"b={b}: {err:.3e}"

@@ -376,3 +376,110 @@ def test_heavy_recipe_gives_peaked_attention():
         qhat = O.rotate_query(x["q"][0, g], x["P"][0])
         p = O.softmax(x["khat"][0, 0].astype(np.float64) @ qhat / math.sqrt(128))
         assert p[pos].sum() > 0.9
+
+
+# ------------------------------------------------- whole step: ragged batch + append --
+def _step_case(seed=31, B=3, Hq=4, Hkv=2, D=8, S=40):
+    rng = np.random.default_rng(seed)
+    P = np.stack([synth.orthogonal_basis(seed, h, D) for h in range(Hkv)])
+    q = rng.standard_normal((B, Hq, D))
+    K = rng.standard_normal((B, Hkv, S, D))
+    V = rng.standard_normal((B, Hkv, S, D))
+    return rng, P, q, K, V
+
+
+def test_step_without_options_is_the_batch_function():
+    _, P, q, K, V = _step_case()
+    Khat = O.rotate_keys_batch(K, P)
+    for mode in (0, 1):
+        o0, i0, a0 = O.loki_decode_batch(q, P, Khat, V, 3, 7, mode)
+        o1, i1, a1, K1, V1 = O.loki_decode_step(q, P, Khat, V, 3, 7, mode)
+        np.testing.assert_array_equal(o0, o1)
+        np.testing.assert_array_equal(i0, i1)
+        np.testing.assert_array_equal(a0, a1)
+        np.testing.assert_array_equal(K1, Khat)
+        np.testing.assert_array_equal(V1, V)
+
+
+def test_step_ragged_ignores_rows_past_each_sequence_and_pads_indices():
+    """Each sequence is Algorithm 1 on its own first seq_len rows, whatever lies behind them;
+    with every row kept it is Eq. 1 on those rows of the unrotated cache (Lemma 4.1)."""
+    _, P, q, K, V = _step_case()
+    B, Hkv, S, D = K.shape
+    G = q.shape[1] // Hkv
+    Khat = O.rotate_keys_batch(K, P)
+    lens = np.array([S, 9, 23])
+    ks = np.array([7, 2, 5])
+    junk_K, junk_V = Khat.copy(), V.copy()
+    for b in range(B):
+        junk_K[b, :, lens[b]:] = 1e6   # would win every ranking if it were looked at
+        junk_V[b, :, lens[b]:] = -1e6
+    out, idx, sc, _, _ = O.loki_decode_step(q, P, junk_K, junk_V, 3, 7, 0, seq_lens=lens, ks=ks)
+    for b in range(B):
+        for hq in range(q.shape[1]):
+            h = hq // G
+            o1, i1, _ = O.loki_attention(q[b, hq], P[h], Khat[b, h, :lens[b]], V[b, h, :lens[b]], 3, ks[b])
+            np.testing.assert_array_equal(out[b, hq], o1)
+            np.testing.assert_array_equal(idx[b, hq, :ks[b]], i1)
+            assert np.all(idx[b, hq, ks[b]:] == -1)
+            assert np.all(np.isnan(sc[b, hq, lens[b]:])) and not np.any(np.isnan(sc[b, hq, :lens[b]]))
+    # default ks = min(k_max, seq_len); k_max = S keeps every row of every sequence
+    full, idx_full, _, _, _ = O.loki_decode_step(q, P, junk_K, junk_V, 3, S, 1, seq_lens=lens)
+    for b in range(B):
+        for hq in range(q.shape[1]):
+            h = hq // G
+            ref = O.dense_attention(q[b, hq], K[b, h, :lens[b]], V[b, h, :lens[b]])
+            np.testing.assert_allclose(full[b, hq], ref, rtol=1e-10, atol=1e-12)
+        assert np.array_equal(idx_full[b, 0, :lens[b]], np.arange(lens[b]))
+
+
+def test_step_keeping_one_row_returns_that_value_row():
+    """k = 1: the softmax over one row is 1, so the output is the value row of the best
+    approximate score (closed form)."""
+    _, P, q, K, V = _step_case(seed=32)
+    Khat = O.rotate_keys_batch(K, P)
+    lens = np.array([40, 17, 5])
+    out, idx, sc, _, _ = O.loki_decode_step(q, P, Khat, V, 4, 6, 0, seq_lens=lens, ks=np.array([1, 1, 1]))
+    G = q.shape[1] // K.shape[1]
+    for b in range(3):
+        for hq in range(q.shape[1]):
+            qhat = q[b, hq] @ P[hq // G]
+            best = int(np.argmax(Khat[b, hq // G, :lens[b], :4] @ qhat[:4]))
+            assert idx[b, hq, 0] == best
+            np.testing.assert_allclose(out[b, hq], V[b, hq // G, best], rtol=1e-14)
+
+
+def test_step_append_writes_the_rotated_rounded_key_then_attends():
+    """Lines 3-4: row seq_len-1 becomes round(k_new P_h) / v_new, checked against torch's own
+    double-precision product and bfloat16 cast; the attention then sees the new row (a key
+    that dominates the ranking and the softmax must pull the output to v_new)."""
+    rng, P, q, K, V = _step_case(seed=33)
+    B, Hkv, S, D = K.shape
+    G = q.shape[1] // Hkv
+    Khat = O.to_bf16(O.rotate_keys_batch(K, P))
+    lens = np.array([S, 12, 30])
+    k_new = O.to_bf16(rng.standard_normal((B, Hkv, D)))
+    v_new = O.to_bf16(rng.standard_normal((B, Hkv, D)))
+    out, idx, sc, K1, V1 = O.loki_decode_step(q, P, Khat, V, 3, 5, 0, seq_lens=lens, k_new=k_new,
+                                              v_new=v_new, storage="bf16")
+    for b in range(B):
+        for h in range(Hkv):
+            want = (torch.from_numpy(k_new[b, h]) @ torch.from_numpy(P[h])).to(torch.bfloat16).double().numpy()
+            np.testing.assert_array_equal(K1[b, h, lens[b] - 1], want)
+            np.testing.assert_array_equal(V1[b, h, lens[b] - 1], v_new[b, h])
+            untouched = np.ones(S, bool)
+            untouched[lens[b] - 1] = False
+            np.testing.assert_array_equal(K1[b, h, untouched], Khat[b, h, untouched])
+            np.testing.assert_array_equal(V1[b, h, untouched], V[b, h, untouched])
+            for g in range(G):
+                hq = h * G + g
+                o1, i1, _ = O.loki_attention(q[b, hq], P[h], K1[b, h, :lens[b]], V1[b, h, :lens[b]], 3, 5)
+                np.testing.assert_array_equal(out[b, hq], o1)
+    assert not np.shares_memory(K1, Khat)
+    # a new key aligned with the query, 200x longer than the cached ones: selected, weight ~ 1
+    big = np.stack([[60.0 * q[b, h * G] for h in range(Hkv)] for b in range(B)])
+    out2, idx2, _, _, _ = O.loki_decode_step(q, P, Khat, V, 3, 5, 0, seq_lens=lens, k_new=big, v_new=v_new)
+    for b in range(B):
+        for h in range(Hkv):
+            assert lens[b] - 1 in idx2[b, h * G]
+            np.testing.assert_allclose(out2[b, h * G], v_new[b, h], atol=1e-6)

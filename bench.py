@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="skip the loki_rotate_keys timing")
+    ap.add_argument("--no-step", action="store_true",
+                    help="skip the loki_decode_step timings (append folded in; ragged batch)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference point for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -232,6 +234,57 @@ def main():
         log(f"[bench] rotate prefill {t_pre * 1e6:.1f} us, append {t_app * 1e6:.1f} us")
         del k_pre, k_one, rklo, rkhi
 
+    # the whole step with the cache append folded in, and a ragged batch (loki_decode_step)
+    step = None
+    if not args.no_step:
+        log("[bench] timing loki_decode_step")
+        st_in = synth.make_step_inputs(w, x["P"], ragged=True)
+        k_new = torch.from_numpy(st_in["k_new"]).to("cuda").to(tdt)
+        v_new = torch.from_numpy(st_in["v_new"]).to("cuda").to(tdt)
+        lens = torch.from_numpy(st_in["seq_lens"]).to("cuda")
+        ks = torch.from_numpy(st_in["ks"]).to("cuda")
+
+        def append_step(i):
+            klo, khi, v, _ = caches[i % len(caches)]
+            api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path_bits, ws, out,
+                                 None, k_new=k_new, v_new=v_new, stream=stream)
+
+        def separate_step(i):
+            klo, khi, v, _ = caches[i % len(caches)]
+            api.loki_rotate_keys(lay, k_new.view(w.B, w.Hkv, 1, w.D), P, klo, khi, w.S - 1, 1, stream)
+            v[:, :, w.S - 1, :] = v_new
+            api.loki_decode_attn(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path_bits, ws, out,
+                                 None, stream)
+
+        def ragged_step(i):
+            klo, khi, v, _ = caches[i % len(caches)]
+            api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path_bits, ws, out,
+                                 None, seq_lens=lens, ks=ks, k_new=k_new, v_new=v_new, stream=stream)
+
+        def ragged_dense(i):
+            _, _, v, kf = caches[i % len(caches)]
+            api.dense_decode_step(lay, q, kf, v, w.S, lens, wsd, out, stream)
+
+        t_app = timed(append_step, args.steps, args.warmup)
+        t_sep = timed(separate_step, args.steps, args.warmup)
+        t_rag = timed(ragged_step, args.steps, args.warmup)
+        t_rd = timed(ragged_dense, args.steps, args.warmup)
+        e = w.elem_bytes
+        sel_per_unit = 1 if (mode == 1 or w.G == 1) else w.G
+        rag_bytes = float(sum(w.Hkv * (int(L) * w.d + sel_per_unit * int(K) * 2 * w.D) * e
+                              for L, K in zip(st_in["seq_lens"], st_in["ks"])))
+        rag_dense_bytes = float(sum(w.Hkv * int(L) * 2 * w.D * e for L in st_in["seq_lens"]))
+        step = {"append_folded_in_us": t_app * 1e6,
+                "rotate_keys_then_value_copy_then_decode_us": t_sep * 1e6,
+                "ragged": {"seq_lens_min_mean_max": [int(st_in["seq_lens"].min()),
+                                                     float(st_in["seq_lens"].mean()),
+                                                     int(st_in["seq_lens"].max())],
+                           "us": t_rag * 1e6, "hbm_gbps": rag_bytes / t_rag / 1e9,
+                           "dense_us": t_rd * 1e6, "dense_hbm_gbps": rag_dense_bytes / t_rd / 1e9,
+                           "speedup_vs_dense": t_rd / t_rag}}
+        log(f"[bench] step with append {t_app * 1e6:.1f} us (separate calls {t_sep * 1e6:.1f} us); "
+            f"ragged {t_rag * 1e6:.1f} us, dense ragged {t_rd * 1e6:.1f} us")
+
     ab = algorithmic_bytes(w, mode)
 
     # the read ceiling of this device: a trivial kernel streaming as many bytes as one decode
@@ -288,6 +341,7 @@ def main():
         "dense_kernels_us": k_dense,
         "speedup_vs_dense": (t_dense / t_loki) if t_dense else None,
         "rotate_keys": rot,
+        "decode_step": step,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -94,6 +94,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-rotate", action="store_true", help="skip the loki_rotate_keys timing")
+    ap.add_argument("--no-variants", action="store_true",
+                    help="skip Exact-TopK (d = D) and PCAAttn (Algorithm 2) on the same shape")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the loki_decode_step timings (append folded in; ragged batch)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -285,6 +287,42 @@ def main():
         log(f"[bench] step with append {t_app * 1e6:.1f} us (separate calls {t_sep * 1e6:.1f} us); "
             f"ragged {t_rag * 1e6:.1f} us, dense ragged {t_rd * 1e6:.1f} us")
 
+    # the paper's two comparison variants on the same kernels: Exact-TopK (Section 5: d = D, the
+    # ranking scores are the exact logits) and PCAAttn (Appendix E, Algorithm 2)
+    variants = None
+    if not args.no_variants:
+        log("[bench] timing Exact-TopK and PCAAttn")
+        e = w.elem_bytes
+        units = w.B * w.Hkv
+        sel_per_unit = 1 if (mode == 1 or w.G == 1) else w.G
+        lay_full = api.make_layout(w.B, w.Hq, w.Hkv, w.D, w.D, w.S, tdt)
+        ws_full = api.alloc_workspace(lay_full, w.S, w.D, w.k, mode)
+        ws_pca = torch.empty(api.loki_workspace_bytes(lay, w.S, w.d, 0, -2), dtype=torch.uint8,
+                             device="cuda")
+
+        def exact_topk_step(i):
+            _, _, v, kf = caches[i % len(caches)]  # the unsplit rotated cache is the d = D layout
+            api.loki_decode_attn(lay_full, q, P, kf, None, v, w.S, w.D, w.k, mode, ws_full, out, None,
+                                 stream)
+
+        def pca_step(i):
+            klo, _, v, _ = caches[i % len(caches)]
+            api.loki_pca_attn(lay, q, P, klo, v, w.S, w.d, ws_pca, out, stream)
+
+        t_et = timed(exact_topk_step, args.steps, args.warmup)
+        t_pca = timed(pca_step, args.steps, args.warmup)
+        # Exact-TopK: S D for the scores; with one query head per KV head the scores are the logits
+        # and only the k value rows follow, otherwise k key and value rows per selecting head
+        row_elems = w.D if w.G == 1 else 2 * w.D
+        et_bytes = units * (w.S * w.D + sel_per_unit * w.k * row_elems) * e
+        pca_bytes = units * w.S * (w.d + w.D) * e
+        variants = {"exact_topk": {"d": w.D, "k": w.k, "us": t_et * 1e6, "algorithmic_bytes": et_bytes,
+                                   "hbm_gbps": et_bytes / t_et / 1e9},
+                    "pca_attn": {"d": w.d, "us": t_pca * 1e6, "algorithmic_bytes": pca_bytes,
+                                 "hbm_gbps": pca_bytes / t_pca / 1e9}}
+        log(f"[bench] Exact-TopK {t_et * 1e6:.1f} us, PCAAttn {t_pca * 1e6:.1f} us")
+        del ws_full, ws_pca
+
     ab = algorithmic_bytes(w, mode)
 
     # the read ceiling of this device: a trivial kernel streaming as many bytes as one decode
@@ -342,6 +380,7 @@ def main():
         "speedup_vs_dense": (t_dense / t_loki) if t_dense else None,
         "rotate_keys": rot,
         "decode_step": step,
+        "variants": variants,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

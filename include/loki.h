@@ -195,6 +195,18 @@ int dense_decode_step(const loki_layout* layout, const void* q, const void* k_fu
                       void* out, void* stream);
 
 /*
+ * Appendix E, Algorithm 2 (PCAAttn, the variant the paper tried and set aside): the
+ * attention weights come from the first d rotated columns alone, over all S rows,
+ *   out = softmax(qhat[:d] Klo^T / sqrt(D)) V,
+ * so only the low-rank slab of the key cache is read (with d = D it is Eq. 1 in the
+ * rotated basis).  Arguments as loki_decode_attn; the workspace holds the rotated
+ * queries and split partials: loki_workspace_bytes(layout, S, d, 0, -2).
+ */
+int loki_pca_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
+                  const void* v, int S, int d, void* workspace, size_t workspace_bytes, void* out,
+                  void* stream);
+
+/*
  * Stage timing for benchmarks.  A profile owns HIP events; when one is attached
  * with loki_profile_attach, the next decode / dense / rotate calls made from the
  * same host thread record an event before and after every kernel they launch (on

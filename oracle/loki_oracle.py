@@ -220,6 +220,28 @@ def loki_decode_step(q, P, Khat, V, d: int, k_max: int, select_mode: int = 0,
     return out, idx, scores, Khat, V
 
 
+def pca_attention(q, P, Khat, V, d: int) -> np.ndarray:
+    """PCAAttn (Appendix E, Algorithm 2): the weights come from the first d rotated
+    columns alone, over every row, still scaled by 1/sqrt(D):
+    softmax(qhat[:d] Khat[:, :d]^T / sqrt(D)) V."""
+    qhat = rotate_query(q, P)
+    D = qhat.shape[0]
+    return softmax(approx_scores(qhat, Khat, d) / math.sqrt(D)) @ np.asarray(V, dtype=np.float64)
+
+
+def pca_attention_batch(q, P, Khat, V, d: int, units=None) -> np.ndarray:
+    """PCAAttn for every query head; q [B,Hq,D], P [Hkv,D,D], Khat,V [B,Hkv,S,D]."""
+    B, Hq, D = q.shape
+    Hkv = P.shape[0]
+    G = Hq // Hkv
+    out = np.full((B, Hq, D), np.nan)
+    todo = units if units is not None else [(b, h) for b in range(B) for h in range(Hkv)]
+    for b, h in todo:
+        for g in range(G):
+            out[b, h * G + g] = pca_attention(q[b, h * G + g], P[h], Khat[b, h], V[b, h], d)
+    return out
+
+
 def dense_decode_batch(q, K, V, units=None) -> np.ndarray:
     """Eq. 1 for every query head; q [B,Hq,D], K,V [B,Hkv,S,D]."""
     B, Hq, D = q.shape

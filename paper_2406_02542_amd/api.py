@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
     L.loki_decode_step.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp, vp, vp]
     L.dense_decode_step.restype = i32
     L.dense_decode_step.argtypes = [LP, vp, vp, vp, i32, vp, vp, sz, vp, vp]
+    L.loki_pca_attn.restype = i32
+    L.loki_pca_attn.argtypes = [LP, vp, vp, vp, vp, i32, i32, vp, sz, vp, vp]
     L.dense_decode_attn.restype = i32
     L.dense_decode_attn.argtypes = [LP, vp, vp, vp, i32, vp, sz, vp, vp]
     L.loki_profile_create.restype = i32
@@ -267,6 +269,24 @@ def dense_decode_attn(layout: Layout, q: torch.Tensor, k_full: torch.Tensor, v: 
         workspace.numel() if workspace is not None else 0,
         _ptr(out, "out", dt, nq),
         _stream_ptr(stream)), "dense_decode_attn")
+
+
+def loki_pca_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                  v: torch.Tensor, S: int, d: int, workspace: torch.Tensor, out: torch.Tensor,
+                  stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    _check(lib().loki_pca_attn(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S, d,
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+        _ptr(out, "out", dt, nq),
+        _stream_ptr(stream)), "loki_pca_attn")
 
 
 def loki_stream_read(buf: torch.Tensor, nbytes: int, stream=None) -> None:

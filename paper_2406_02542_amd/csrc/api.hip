@@ -51,6 +51,7 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
     off += align_up(bytes, 256);
     return r;
   };
+  if (select_mode == -2) w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
   if (select_mode >= 0) {
     const size_t heads_sel = (select_mode == 1) ? (size_t)s.B * s.Hkv : heads_q;
     w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
@@ -193,10 +194,11 @@ int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int sel
   if (!bytes) return LOKI_ERR_INVALID_ARG;
   if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
   s.S = S;
-  if (select_mode < 0) {
-    *bytes = plan_workspace(s, -1, dense_splits(s), nullptr).total_bytes;
+  if (select_mode == -1 || select_mode == -2) {  // dense baseline; PCAAttn (rotated queries too)
+    *bytes = plan_workspace(s, select_mode, dense_splits(s), nullptr).total_bytes;
     return LOKI_OK;
   }
+  if (select_mode < 0) return LOKI_ERR_INVALID_ARG;
   select_mode &= ~LOKI_PATH_MASK;
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
@@ -372,6 +374,42 @@ int dense_decode_step(const loki_layout* layout, const void* q, const void* k_fu
                       int S_max, const int32_t* seq_lens, void* workspace, size_t workspace_bytes,
                       void* out, void* stream) {
   return dense_impl(layout, q, k_full, v, S_max, seq_lens, workspace, workspace_bytes, out, stream);
+}
+
+int loki_pca_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,
+                  const void* v, int S, int d, void* workspace, size_t workspace_bytes, void* out,
+                  void* stream) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!q || !P || !klo || !v || !out || !workspace) return LOKI_ERR_INVALID_ARG;
+  if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
+  if (d != s.d) return LOKI_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(P) || !aligned16(klo) || !aligned16(v) || !aligned16(out))
+    return LOKI_ERR_ALIGNMENT;
+  if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+  s.S = S;
+  const int nsplit = dense_splits(s);
+  const Workspace w = plan_workspace(s, -2, nsplit, workspace);
+  if (w.total_bytes > workspace_bytes) return LOKI_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  StageTimer tm(st);
+  hipError_t e;
+  tm.begin("rotate_query");
+  e = launch_qrot(s, q, P, w.qhat, nullptr, nullptr, nullptr, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  tm.begin("pca_attend");
+  e = launch_pca_attend(s, nsplit, w.qhat, klo, v, w.partial, out, st);
+  tm.end();
+  if (e != hipSuccess) return LOKI_ERR_HIP;
+  if (nsplit > 1) {
+    tm.begin("combine");
+    e = launch_combine(s, nsplit, w.partial, out, st);
+    tm.end();
+    if (e != hipSuccess) return LOKI_ERR_HIP;
+  }
+  return LOKI_OK;
 }
 
 int loki_profile_create(loki_profile** out) {

@@ -15,7 +15,9 @@ namespace loki {
 constexpr int kAttThreads = 256;
 constexpr int kAttWaves = kAttThreads / 64;
 
-template <typename T, int NH, bool GATHER, bool REUSE_LO>
+// LO_ONLY (with GATHER = false): every row, rotated query, logits from the low-rank slab alone
+// (Appendix E, Algorithm 2).
+template <typename T, int NH, bool GATHER, bool REUSE_LO, bool LO_ONLY = false>
 __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     const void* __restrict__ k_a,   // GATHER: klo [units, S_cap, d]; dense: K [units, S_cap, 128]
     const void* __restrict__ k_b,   // GATHER: khi [units, S_cap, 128-d]; dense: unused
@@ -62,7 +64,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   float qr[NH][EPC];
 #pragma unroll
   for (int g = 0; g < NH; ++g) {
-    if constexpr (GATHER) {
+    if constexpr (GATHER || LO_ONLY) {
       const float* qh = static_cast<const float*>(qv) + (size_t)(head0 + g) * kD + c * EPC;
 #pragma unroll
       for (int e = 0; e < EPC; ++e) qr[g][e] = qh[e];
@@ -73,8 +75,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     }
   }
 
-  const RowAddr ra = make_row_addr<T, REUSE_LO>(k_a, k_b, v, (size_t)kv_unit, S_cap,
-                                                GATHER ? d : kD, c);
+  const RowAddr ra = make_row_addr<T, REUSE_LO, LO_ONLY>(k_a, k_b, v, (size_t)kv_unit, S_cap,
+                                                         (GATHER || LO_ONLY) ? d : kD, c);
   AttendAcc<T, NH> acc;
   acc.init();
   attend_rows<T, NH, kAttWaves * RPW, GATHER, REUSE_LO>(acc, qr, ra, s_idx, s_a, wave * RPW + rg,
@@ -148,9 +150,9 @@ static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block,
                                    void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
                                    const Ragged& rg, hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
-  // and there is a residual slab to read at all
+  // (d = 128, Exact-TopK of Section 5: it is the whole logit and no key is read again)
   constexpr bool kCanReuse = GATHER && NH == 1;
-  if (kCanReuse && sel_score != nullptr && d < kD) {
+  if (kCanReuse && sel_score != nullptr) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
                        Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg);
@@ -209,6 +211,34 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
                                        nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
+}
+
+template <typename T, int NH>
+static hipError_t launch_pca_nh(const Shape& s, int nsplit, int rpb, const float* qhat, const void* klo,
+                                const void* v, float* partial, void* out, hipStream_t st) {
+  hipLaunchKernelGGL((attend_kernel<T, NH, false, false, true>), dim3(nsplit, s.B * s.Hkv),
+                     dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, out,
+                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t launch_pca_t(const Shape& s, int nsplit, int rpb, const float* qhat, const void* klo,
+                               const void* v, float* partial, void* out, hipStream_t st) {
+  switch (s.G) {
+    case 1: return launch_pca_nh<T, 1>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+    case 2: return launch_pca_nh<T, 2>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+    case 4: return launch_pca_nh<T, 4>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+    case 8: return launch_pca_nh<T, 8>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_pca_attend(const Shape& s, int nsplit, const float* qhat, const void* klo,
+                             const void* v, float* partial, void* out, hipStream_t st) {
+  const int rpb = div_up(s.S, nsplit);
+  return s.dtype == 0 ? launch_pca_t<F32>(s, nsplit, rpb, qhat, klo, v, partial, out, st)
+                      : launch_pca_t<BF16>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
 }
 
 hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,

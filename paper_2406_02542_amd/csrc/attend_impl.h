@@ -47,17 +47,18 @@ struct RowAddr {
 };
 
 // c = lane's chunk index inside a row (0 .. 128/EPC-1).  k_a holds the first d columns
-// (d = 128: the whole row), k_b the rest.
-template <typename T, bool REUSE_LO>
+// (d = 128: the whole row), k_b the rest.  LO_ONLY: the logit uses the first d columns only
+// (Algorithm 2, PCAAttn); lanes past them read no key at all.
+template <typename T, bool REUSE_LO, bool LO_ONLY = false>
 __device__ __forceinline__ RowAddr make_row_addr(const void* k_a, const void* k_b, const void* v,
                                                  size_t kv_unit, int S_cap, int d, int c) {
   const int nlo = d / T::EPC;
   const bool in_lo = c < nlo;
   RowAddr ra;
-  ra.k_load = !(REUSE_LO && in_lo);
-  ra.k_row_bytes = in_lo ? (size_t)d * T::kBytes : (size_t)(kD - d) * T::kBytes;
-  const char* kb = in_lo ? static_cast<const char*>(k_a) + (size_t)c * 16
-                         : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
+  ra.k_load = LO_ONLY ? in_lo : !(REUSE_LO && in_lo);
+  ra.k_row_bytes = (in_lo || LO_ONLY) ? (size_t)d * T::kBytes : (size_t)(kD - d) * T::kBytes;
+  const char* kb = (in_lo || LO_ONLY) ? static_cast<const char*>(k_a) + (size_t)(in_lo ? c : 0) * 16
+                                      : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
   ra.k_base = kb + kv_unit * S_cap * ra.k_row_bytes;
   ra.v_row_bytes = (size_t)kD * T::kBytes;
   ra.v_base = static_cast<const char*>(v) + kv_unit * S_cap * ra.v_row_bytes + (size_t)c * 16;

@@ -258,8 +258,9 @@ static hipError_t launch_fused_r(const Shape& s, const void* q, const float* P, 
 template <typename T, int LPR>
 static hipError_t launch_fused_l(const Shape& s, const void* q, const float* P, void* klo, void* khi,
                                  void* v, void* out, int32_t* out_idx, hipStream_t st) {
-  if (s.d < kD) return launch_fused_r<T, LPR, true>(s, q, P, klo, khi, v, out, out_idx, st);
-  return launch_fused_r<T, LPR, false>(s, q, P, klo, khi, v, out, out_idx, st);
+  // the ranking score is reused as the low-rank part of the exact logit; with d = 128
+  // (Exact-TopK of Section 5) it is the whole logit and the attention stage reads no key
+  return launch_fused_r<T, LPR, true>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <typename T>

@@ -77,6 +77,9 @@ hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const vo
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
                               const void* khi, const void* v, const int32_t* sel_idx, float* partial,
                               void* out, hipStream_t st);
+// Appendix E, Algorithm 2: every row, logits from the low-rank slab alone.
+hipError_t launch_pca_attend(const Shape& s, int nsplit, const float* qhat, const void* klo,
+                             const void* v, float* partial, void* out, hipStream_t st);
 hipError_t launch_combine(const Shape& s, int nsplit, const float* partial, void* out,
                           hipStream_t st);
 // Fused single-kernel decode step (one query head per KV head only).

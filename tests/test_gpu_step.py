@@ -239,3 +239,29 @@ def test_dense_step_ragged(G, dtype):
         ref = O.dense_decode_batch(x["q"][b:b + 1], x["khat"][b:b + 1, :, :lens[b]], x["v"][b:b + 1, :, :lens[b]])
         err = np.max(np.abs(got[b] - ref[0]))
         assert err <= OUT_TOL[dtype], f"b={b}: {err:.3e}"
+
+
+# ---------------------------------------------------------------- PCAAttn (Algorithm 2) --
+@pytest.mark.parametrize("G,dtype,d,S", [(1, "f32", 32, 1500), (1, "bf16", 32, 4096), (2, "bf16", 16, 3001),
+                                         (4, "bf16", 64, 5000), (8, "bf16", 32, 2000), (4, "f32", 128, 700),
+                                         (1, "bf16", 128, 1000)])
+def test_pca_attn(G, dtype, d, S):
+    """softmax(qhat[:d] Klo^T / sqrt(D)) V over all rows; the residual slab is never passed."""
+    w = synth.Workload(f"pca_g{G}", 3, 2 * G, 2, 128, S, dtype, d, 8, seed=9990 + G)
+    x = synth.make_inputs(w)
+    say(f"case {w}")
+    tdt = TORCH_DT[dtype]
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, d, S + 5, tdt)
+    klo, _, v = api.alloc_cache(lay)
+    klo.fill_(3e4); v.fill_(-3e4)
+    kh = to_dev(x["khat"], dtype)
+    klo[:, :, :S] = kh[..., :d]
+    v[:, :, :S] = to_dev(x["v"], dtype)
+    ws = torch.empty(api.loki_workspace_bytes(lay, S, d, 0, -2), dtype=torch.uint8, device="cuda")
+    out = torch.full((w.B, w.Hq, 128), float("nan"), dtype=tdt, device="cuda")
+    api.loki_pca_attn(lay, to_dev(x["q"], dtype), torch.from_numpy(x["P"]).cuda(), klo, v, S, d, ws, out)
+    torch.cuda.synchronize()
+    ref = O.pca_attention_batch(x["q"], x["P"], x["khat"], x["v"], d)
+    err = np.max(np.abs(out.float().cpu().numpy() - ref))
+    say(f"   max_err {err:.3e}")
+    assert err <= OUT_TOL[dtype]

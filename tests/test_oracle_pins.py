@@ -483,3 +483,36 @@ def test_step_append_writes_the_rotated_rounded_key_then_attends():
         for h in range(Hkv):
             assert lens[b] - 1 in idx2[b, h * G]
             np.testing.assert_allclose(out2[b, h * G], v_new[b, h], atol=1e-6)
+
+
+# ------------------------------------------------------------ PCAAttn (Algorithm 2) --
+def test_pca_attention_pins():
+    """Appendix E: weights from the first d rotated columns, scale 1/sqrt(D) (not sqrt(d)),
+    all rows, values untouched."""
+    q, P, K, V = _rand_case(41, S=50, D=16)
+    Khat = O.rotate_keys(K, P)
+    # d = D: Eq. 1 on the unrotated inputs (Lemma 4.1)
+    np.testing.assert_allclose(O.pca_attention(q, P, Khat, V, 16), O.dense_attention(q, K, V),
+                               rtol=1e-11, atol=1e-13)
+    # torch's attention in the d-dimensional subspace with the scale given explicitly
+    d = 5
+    qh = torch.from_numpy(q @ P)[None, None, None, :d]
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        qh, torch.from_numpy(Khat[:, :d])[None, None], torch.from_numpy(V)[None, None],
+        scale=1.0 / math.sqrt(16))[0, 0, 0].numpy()
+    got = O.pca_attention(q, P, Khat, V, d)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+    wrong_scale = torch.nn.functional.scaled_dot_product_attention(
+        qh, torch.from_numpy(Khat[:, :d])[None, None], torch.from_numpy(V)[None, None])[0, 0, 0].numpy()
+    assert np.max(np.abs(got - wrong_scale)) > 1e-3  # sqrt(d) would be a different function
+    # columns past d are never looked at; V = 1 gives 1
+    junk = Khat.copy()
+    junk[:, d:] = 1e5
+    np.testing.assert_array_equal(O.pca_attention(q, P, junk, V, d), got)
+    np.testing.assert_allclose(O.pca_attention(q, P, Khat, np.ones_like(V), d), 1.0, rtol=1e-14)
+    # batch form and head mapping
+    rng = np.random.default_rng(42)
+    Pb = np.stack([synth.orthogonal_basis(42, h, 8) for h in range(2)])
+    qb, Kb, Vb = rng.standard_normal((2, 4, 8)), rng.standard_normal((2, 2, 30, 8)), rng.standard_normal((2, 2, 30, 8))
+    ob = O.pca_attention_batch(qb, Pb, Kb, Vb, 3)
+    np.testing.assert_array_equal(ob[1, 3], O.pca_attention(qb[1, 3], Pb[1], Kb[1, 1], Vb[1, 1], 3))

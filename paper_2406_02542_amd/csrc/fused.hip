@@ -22,6 +22,29 @@ __host__ __device__ inline int fused_keys_per_thread(int S) {
 // Two blocks share a CU (4 waves per SIMD): the register budget is 128 VGPRs and the compiler
 // is told not to trade load-level parallelism for a higher occupancy that cannot happen.
 // KPT = keys a thread holds in the select stage (8 for S <= 4096, else 16).
+// Which (sequence, head) unit a block works on.  Uniform batches: unit = block.  Ragged batches
+// (up to 64 sequences): the sequences are ranked by length and handed out so that the two
+// blocks that share a CU (block i and block i + half the grid, when the whole grid is resident)
+// get a long and a short sequence: the first half of the grid takes the longest sequences in
+// descending order, the second half the rest in ascending order.  Every wave computes the same
+// answer from the length array (lane l ranks sequence l), so no barrier is needed.
+__device__ __forceinline__ int fused_unit_of_block(const Ragged& rag, int B, int Hkv, int block) {
+  if (rag.seq_lens == nullptr || B > 64 || B < 2) return block;
+  const int lane = threadIdx.x & 63;
+  const int mine = lane < B ? rag.seq_lens[lane] : 0;
+  int rank = 0;
+  for (int j = 0; j < B; ++j) {
+    const int other = rag.seq_lens[j];
+    rank += (other > mine || (other == mine && j < lane)) ? 1 : 0;
+  }
+  const int pos = block / Hkv, half = (B + 1) / 2;
+  const int want = pos < half ? pos : B - 1 - (pos - half);
+  const unsigned long long hit = __ballot(lane < B && rank == want);
+  if (hit == 0ull) return block;              // cannot happen: the ranks are a permutation of 0..B-1
+  const int b = __ffsll((long long)hit) - 1;  // exactly one lane holds each rank
+  return b * Hkv + block % Hkv;
+}
+
 // APPEND: the block also rotates the unit's new key with the P_h entries it already holds and
 // writes it, with the new value, into row S-1 of the unit's cache before it scores.  The block's
 // own later reads of that row go through the same L1 and see it after the barrier; no other
@@ -54,7 +77,8 @@ fused_decode_kernel(
   __shared__ MergeSmem<kFusedWaves, 1> s_merge;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int unit = blockIdx.x;        // = b * H + h; one query head per KV head here
+  // = b * H + h; one query head per KV head here
+  const int unit = fused_unit_of_block(rag, (int)gridDim.x / Hkv, Hkv, (int)blockIdx.x);
   const int h = unit % Hkv;
   const int S = seq_rows(rag, unit / Hkv, S_max);
   const int k = seq_keep(rag, unit / Hkv, k_max, S);
@@ -94,9 +118,13 @@ fused_decode_kernel(
     for (int ii = 0; ii < kRotPartLen; ++ii)
       pv[ii] = *reinterpret_cast<const float2*>(Ph + (size_t)ii * kD);
   }
-  ScoreTrip<kPipelined ? LPR : 8> first_trip;
-  if constexpr (kPipelined)
+  ScoreTrip<kPipelined ? LPR : 8> first_trip, second_trip;
+  constexpr int kTripRows = kFusedWaves * 64 * ScoreTrip<kPipelined ? LPR : 8>::TPI;
+  if constexpr (kPipelined) {
     score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
+    if constexpr (!APPEND)  // the appending variant has no registers to spare during the rotation
+      score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64 + kTripRows, S, second_trip);
+  }
 
   s_q[tid & (kD - 1)] = q_mine;  // four threads store the same value: no branch to sink the load into
   if constexpr (APPEND) s_kn[tid & (kD - 1)] = kn_mine;
@@ -144,9 +172,9 @@ fused_decode_kernel(
   __syncthreads();
   if constexpr (APPEND && kPipelined) {
     // the loads put in flight before the rotation may have read row S-1 before it was written
-    constexpr int kFirstTripRows = kFusedWaves * 64 * ScoreTrip<kPipelined ? LPR : 8>::TPI;
-    if (S - 1 < kFirstTripRows)
+    if (S - 1 < kTripRows)
       score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
+    score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64 + kTripRows, S, second_trip);
   }
 
   LOKI_STAMP(1);
@@ -157,7 +185,8 @@ fused_decode_kernel(
     for (int e = 0; e < EPC; ++e) qr[0][e] = cact ? s_qhat[0][cs * EPC + e] : 0.f;
     auto to_lds = [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; };
     if constexpr (kPipelined)
-      score_rows_pipelined<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, qr, 0, S, first_trip, to_lds);
+      score_rows_pipelined<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, qr, 0, S, first_trip,
+                                                   second_trip, to_lds);
     else
       score_rows<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, cact, qr, 0, S, to_lds);
   }

@@ -124,22 +124,23 @@ __device__ __forceinline__ void score_trip(const ScoreTrip<LPR>& cur, const floa
   }
 }
 
-// `first` holds the trip of tile0 = row0 + wave*64, already in flight.  Two register buffers
-// take turns (the loop body handles two trips), so a trip's loads stay in flight while the
-// previous trip is scored and no buffer is ever copied; the loads past the last trip are
-// clamped re-reads of the last row.
+// `t0` and `t1` hold the trips of tile0 = row0 + wave*64 and tile0 + one stride, already in
+// flight (the caller can issue them before it has qhat at all).  The two register buffers take
+// turns (the loop body handles two trips), so two trips' loads stay in flight while a trip is
+// scored and no buffer is ever copied; the loads past the last trip are clamped re-reads of
+// the last row.
 template <typename T, int LPR, int G, int WAVES, typename Emit>
 __device__ __forceinline__ void score_rows_pipelined(const char* base, size_t row_bytes,
                                                      const float (&qr)[G][T::EPC], int row0,
-                                                     int row_end, ScoreTrip<LPR>& first, Emit emit) {
+                                                     int row_end, ScoreTrip<LPR>& t0,
+                                                     ScoreTrip<LPR>& t1, Emit emit) {
   constexpr int kStride = WAVES * 64 * ScoreTrip<LPR>::TPI;
   const int wave = threadIdx.x >> 6;
-  ScoreTrip<LPR> other;
   for (int tile0 = row0 + wave * 64; tile0 < row_end; tile0 += 2 * kStride) {
-    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + kStride, row_end, other);
-    score_trip<T, LPR, G, WAVES>(first, qr, tile0, row_end, emit);
-    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 2 * kStride, row_end, first);
-    score_trip<T, LPR, G, WAVES>(other, qr, tile0 + kStride, row_end, emit);
+    score_trip<T, LPR, G, WAVES>(t0, qr, tile0, row_end, emit);
+    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 2 * kStride, row_end, t0);
+    score_trip<T, LPR, G, WAVES>(t1, qr, tile0 + kStride, row_end, emit);
+    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 3 * kStride, row_end, t1);
   }
 }
 

@@ -25,7 +25,9 @@ int score_rows_per_block(const Shape& s) {
 
 int gather_splits(const Shape& s, int select_mode) {
   const int heads = (select_mode == 1) ? s.B * s.Hkv : s.B * s.Hq;
-  int n = div_up(4 * kNumCU, heads);
+  // about two blocks per CU: a block's set-up and merge cost as much as a few hundred rows, and
+  // a launch that needs no split also needs no combine kernel
+  int n = div_up(2 * kNumCU, heads);
   const int max_n = s.k / 128 > 0 ? s.k / 128 : 1;
   if (n > max_n) n = max_n;
   const int min_n = div_up(s.k, kMaxGatherChunk);

@@ -15,8 +15,12 @@
 //                                              needs rows contiguous per lane: V tiles pass
 //                                              through LDS (row pitch 264 B, conflict-free
 //                                              2-byte column reads)
-// q is bf16 for the dense baseline (exact); the rotated query of the gather is fp32 and enters
-// as three bf16 terms like everywhere else.
+// q is bf16 for the dense baseline (exact).  The rotated query of the gather is fp32 and enters
+// as two bf16 terms (16 significant bits): unlike the ranking scores, these logits decide no
+// index, and a relative error of 2^-17 in them is far below the bf16 rounding of the output;
+// the third term would cost 16 registers and a third of the first product's matrix work.
+// Three waves per SIMD (168 registers) is the budget, so that three blocks share a CU (the
+// 8-head gather needs more registers and runs two).
 #include "attend_impl.h"
 
 namespace loki {
@@ -29,9 +33,9 @@ constexpr int kAmWaves = kAmThreads / 64;
 constexpr int kAmRows = 32;        // rows per wave step
 constexpr int kAmPitch = 264;      // bytes per V row in LDS: 256 + 8 keeps column reads conflict-free
 
-// QT = number of bf16 terms q enters with (1: q is bf16; 3: q is fp32)
+// QT = number of bf16 terms q enters with (1: q is bf16; 2: q is fp32)
 template <int NH, bool GATHER>
-__global__ __launch_bounds__(kAmThreads) void attend_mfma_kernel(
+__global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void attend_mfma_kernel(
     const void* __restrict__ k_a,   // GATHER: klo [units, S_cap, d]; dense: K [units, S_cap, 128]
     const void* __restrict__ k_b,   // GATHER: khi [units, S_cap, 128-d]; dense: unused
     const void* __restrict__ v,     // [units, S_cap, 128]
@@ -40,7 +44,7 @@ __global__ __launch_bounds__(kAmThreads) void attend_mfma_kernel(
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     uint16_t* __restrict__ out,     // [B*Hq, 128] bf16 when nsplit == 1
     int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg) {
-  constexpr int QT = GATHER ? 3 : 1;
+  constexpr int QT = GATHER ? 2 : 1;
   __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmRows * kAmPitch];  // 8448 B per wave
   __shared__ int32_t s_idx[GATHER ? kMaxGatherChunk : 1];
   __shared__ MergeSmem<kAmWaves, NH> s_merge;

@@ -202,6 +202,30 @@ def main():
     log("[bench] timing loki")
     t_loki = timed(loki_step, args.steps, args.warmup)
     log(f"[bench] loki {t_loki * 1e6:.1f} us/step; per-kernel pass")
+
+    # the same steps replayed from a captured graph (one step per cache copy in the graph): the
+    # library allocates nothing and records no memset, so its launches can be captured as they are
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        for i in range(len(caches)):
+            klo_, khi_, v_, _ = caches[i]
+            api.loki_decode_attn(lay, q, P, klo_, khi_, v_, w.S, w.d, w.k, mode | path_bits, ws, out,
+                                 None, side)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    n_rep = max(1, args.steps // len(caches))
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t_g = time.perf_counter()
+    for _ in range(n_rep):
+        graph.replay()
+    torch.cuda.synchronize()
+    t_graph = (time.perf_counter() - t_g) / (n_rep * len(caches))
+    log(f"[bench] loki from a captured graph {t_graph * 1e6:.1f} us/step")
     k_loki = per_kernel(loki_step, args.steps)
     t_dense, k_dense = None, {}
     if not args.no_dense:
@@ -373,6 +397,7 @@ def main():
         "tokens_heads_per_s": w.B * w.Hq / t_loki,
         "step_hbm_gbps": ab["step"] / t_loki / 1e9,
         "step_hbm_frac": ab["step"] / t_loki / 1e9 / HBM_PEAK_GBPS,
+        "graph_replay_us_per_step": t_graph * 1e6,
         "kernels_us": k_loki,
         "dense_us_per_step": t_dense * 1e6 if t_dense else None,
         "dense_hbm_gbps": ab["dense_attend"] / t_dense / 1e9 if t_dense else None,

@@ -431,10 +431,11 @@ __global__ __launch_bounds__(kMbThreads, 8) void mb_write_kernel(const float* __
   const int chunk = blockIdx.x, head = blockIdx.y;
   const int S = seq_rows(rg, head / heads_per_seq, S_max);
   const uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
-  if (m[4 * nc + 4]) return;  // the head was finished by mb_resolve_kernel
   const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
   uint32_t key[kSelKPT], valid_mask;
+  // keys first: their loads do not wait for the bookkeeping words read below
   resident_load_keys<kSelKPT>(scores + (size_t)head * S_max + c0, n, kSelKPT, key, valid_mask);
+  if (m[4 * nc + 4]) return;  // the head was finished by mb_resolve_kernel
   int32_t* out = sel_idx + (size_t)head * k_max;
   float* outs = sel_score + (size_t)head * k_max;
   resident_compact<kMbThreads, kSelKPT>(key, valid_mask, kSelKPT, m[4 * nc + 2], m[4 * nc + 3],

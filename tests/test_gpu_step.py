@@ -265,3 +265,52 @@ def test_pca_attn(G, dtype, d, S):
     err = np.max(np.abs(out.float().cpu().numpy() - ref))
     say(f"   max_err {err:.3e}")
     assert err <= OUT_TOL[dtype]
+
+
+# ------------------------------------------------------------------------- graph capture --
+@pytest.mark.parametrize("G,mode", [(1, 0), (4, 0), (4, 1)])
+def test_decode_step_replays_from_a_captured_graph(G, mode):
+    """The library allocates nothing and records no memset, so a step can be captured once and
+    replayed: every replay (with eager work and synchronisations in between, and with the
+    inputs changed in place) must equal the eager result on the same inputs bit for bit."""
+    w = synth.Workload(f"graph_g{G}", 2, 2 * G, 2, 128, 3000, "bf16", 32, 600, seed=9970 + G)
+    x = synth.make_inputs(w)
+    st = synth.make_step_inputs(w, x["P"])
+    lay = api.make_layout(w.B, w.Hq, w.Hkv, 128, w.d, w.S, torch.bfloat16)
+    klo, khi, v = api.alloc_cache(lay)
+    kh = to_dev(x["khat"], "bf16")
+    klo.copy_(kh[..., :w.d]); khi.copy_(kh[..., w.d:]); v.copy_(to_dev(x["v"], "bf16"))
+    q, P = to_dev(x["q"], "bf16"), torch.from_numpy(x["P"]).cuda()
+    lens, ks = torch.from_numpy(st["seq_lens"]).cuda(), torch.from_numpy(st["ks"]).cuda()
+    k_new, v_new = to_dev(st["k_new"], "bf16"), to_dev(st["v_new"], "bf16")
+    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+    out_g = torch.zeros((w.B, w.Hq, 128), dtype=torch.bfloat16, device="cuda")
+    out_e = torch.zeros_like(out_g)
+
+    def step(out):
+        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, out, None,
+                             seq_lens=lens, ks=ks, k_new=k_new, v_new=v_new)
+
+    step(out_e)  # warm-up outside the capture (first-launch set-up of the kernels)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        step(out_g)
+        graph.capture_end()
+    torch.cuda.synchronize()
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    for it in range(4):
+        # new query and new token in place: the graph reads them through the same pointers
+        q.copy_(torch.randn(q.shape, device="cuda", generator=gen).to(torch.bfloat16))
+        k_new.copy_((0.3 * torch.randn(k_new.shape, device="cuda", generator=gen)).to(torch.bfloat16))
+        v_new.copy_(torch.randn(v_new.shape, device="cuda", generator=gen).to(torch.bfloat16))
+        torch.cuda.synchronize()
+        out_g.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        step(out_e)
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay {it} differs from the eager step"
+        assert torch.isfinite(out_g.float()).all()

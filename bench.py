@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--no-rotate", action="store_true", help="skip the loki_rotate_keys timing")
     ap.add_argument("--no-variants", action="store_true",
                     help="skip Exact-TopK (d = D) and PCAAttn (Algorithm 2) on the same shape")
+    ap.add_argument("--no-pca-fit", action="store_true",
+                    help="skip the calibration timing (loki_pca_fit on synthetic keys)")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the loki_decode_step timings (append folded in; ragged batch)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -347,6 +349,29 @@ def main():
         log(f"[bench] Exact-TopK {t_et * 1e6:.1f} us, PCAAttn {t_pca * 1e6:.1f} us")
         del ws_full, ws_pca
 
+    # calibration (Section 3.1): PCA of 65 536 keys per KV head of the workload's shape
+    pca = None
+    if not args.no_pca_fit:
+        log("[bench] timing loki_pca_fit")
+        n_cal = 65536
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(w.seed + 1)
+        cal = torch.randn((w.Hkv, n_cal, w.D), device="cuda", generator=gen).to(tdt)
+        Pfit = torch.empty((w.Hkv, w.D, w.D), device="cuda")
+        lam = torch.empty((w.Hkv, w.D), device="cuda")
+        wsp = torch.empty(api.loki_pca_workspace_bytes(lay, n_cal), dtype=torch.uint8, device="cuda")
+
+        def fit_step(i):
+            api.loki_pca_fit(lay, cal, n_cal, Pfit, lam, wsp, stream)
+
+        t_fit = timed(fit_step, 5, 1)
+        k_fit = per_kernel(fit_step, 5)
+        gram_bytes = w.Hkv * n_cal * w.D * w.elem_bytes
+        pca = {"keys_per_head": n_cal, "heads": w.Hkv, "us": t_fit * 1e6, "stages_us": k_fit,
+               "gram_hbm_gbps": gram_bytes / (k_fit["pca_gram"] * 1e-6) / 1e9}
+        log(f"[bench] pca_fit {t_fit * 1e6:.0f} us: {k_fit}")
+        del cal, wsp
+
     ab = algorithmic_bytes(w, mode)
 
     # the read ceiling of this device: a trivial kernel streaming as many bytes as one decode
@@ -406,6 +431,7 @@ def main():
         "rotate_keys": rot,
         "decode_step": step,
         "variants": variants,
+        "pca_fit": pca,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -207,6 +207,38 @@ int loki_pca_attn(const loki_layout* layout, const void* q, const float* P, cons
                   void* stream);
 
 /*
+ * Section 3.1: the PCA of a set of calibration keys that produces the basis P.
+ *   keys        [Hkv, n_rows, D] device, storage type of layout->dtype (layout's B,
+ *               Hq, S_cap and d_split are not used)
+ *   P           [Hkv, D, D] fp32 out: column j = j-th principal component (eigenvector of
+ *               the sample covariance of the head's keys, mean removed), decreasing
+ *               eigenvalue; the largest-magnitude entry of every column is positive
+ *   eigenvalues [Hkv, D] fp32 out, decreasing
+ *   workspace   >= loki_pca_workspace_bytes(layout, n_rows), 256-B aligned
+ * Covariance: matrix cores with fp32 accumulation per run of rows, runs added in fp64;
+ * eigensolver: cyclic Jacobi in fp64.  2 <= n_rows.
+ */
+int loki_pca_workspace_bytes(const loki_layout* layout, long long n_rows, size_t* bytes);
+int loki_pca_fit(const loki_layout* layout, const void* keys, long long n_rows, float* P,
+                 float* eigenvalues, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Section 3.1, Eq. 2 (Rank@v): for each of n_heads spectra (device fp32 [n_heads, D],
+ * decreasing), the smallest d whose first d eigenvalues hold at least v_percent per cent
+ * of the total; ranks is device int32 [n_heads].  0 < v_percent <= 100.
+ */
+int loki_rank_at(const float* eigenvalues, int n_heads, int D, float v_percent, int32_t* ranks,
+                 void* stream);
+
+/*
+ * Section 6.3 (agreement of two selections, Figure 6 left): Jaccard similarity
+ * |A n B| / |A u B| of n_lists pairs of ascending index lists (device int32
+ * [n_lists, k], entries < 0 are padding at the end); out is device fp32 [n_lists].
+ */
+int loki_index_jaccard(const int32_t* idx_a, const int32_t* idx_b, int n_lists, int k, float* out,
+                       void* stream);
+
+/*
  * Stage timing for benchmarks.  A profile owns HIP events; when one is attached
  * with loki_profile_attach, the next decode / dense / rotate calls made from the
  * same host thread record an event before and after every kernel they launch (on

@@ -292,6 +292,14 @@ def rank_at(eigenvalues, v: float) -> int:
     return len(lam)
 
 
+def jaccard(a, b) -> float:
+    """|A n B| / |A u B| of two index sets (Section 6.3 compares the selection of Loki with
+    that of exact top-k this way); negative entries are padding."""
+    A = {int(x) for x in a if x >= 0}
+    B = {int(x) for x in b if x >= 0}
+    return len(A & B) / len(A | B) if (A or B) else 1.0
+
+
 def theoretical_speedup(D: int, S: int, d: int, k: int, exact: bool = True) -> float:
     """Section 4.2 cost model: 2DS / (dS + 2Dk + 2D^2), or its large-S limit
     1 / (d_f/2 + k_f) when ``exact`` is False."""

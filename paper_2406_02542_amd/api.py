@@ -68,6 +68,14 @@ def lib() -> ctypes.CDLL:
     L.dense_decode_step.argtypes = [LP, vp, vp, vp, i32, vp, vp, sz, vp, vp]
     L.loki_pca_attn.restype = i32
     L.loki_pca_attn.argtypes = [LP, vp, vp, vp, vp, i32, i32, vp, sz, vp, vp]
+    L.loki_pca_workspace_bytes.restype = i32
+    L.loki_pca_workspace_bytes.argtypes = [LP, ctypes.c_longlong, ctypes.POINTER(sz)]
+    L.loki_pca_fit.restype = i32
+    L.loki_pca_fit.argtypes = [LP, vp, ctypes.c_longlong, vp, vp, vp, sz, vp]
+    L.loki_rank_at.restype = i32
+    L.loki_rank_at.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp]
+    L.loki_index_jaccard.restype = i32
+    L.loki_index_jaccard.argtypes = [vp, vp, i32, i32, vp, vp]
     L.dense_decode_attn.restype = i32
     L.dense_decode_attn.argtypes = [LP, vp, vp, vp, i32, vp, sz, vp, vp]
     L.loki_profile_create.restype = i32
@@ -287,6 +295,40 @@ def loki_pca_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.T
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
         _ptr(out, "out", dt, nq),
         _stream_ptr(stream)), "loki_pca_attn")
+
+
+def loki_pca_workspace_bytes(layout: Layout, n_rows: int) -> int:
+    n = ctypes.c_size_t()
+    _check(lib().loki_pca_workspace_bytes(ctypes.byref(layout), n_rows, ctypes.byref(n)),
+           "loki_pca_workspace_bytes")
+    return n.value
+
+
+def loki_pca_fit(layout: Layout, keys: torch.Tensor, n_rows: int, P: torch.Tensor,
+                 eigenvalues: torch.Tensor, workspace: torch.Tensor, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    _check(lib().loki_pca_fit(
+        ctypes.byref(layout),
+        _ptr(keys, "keys", dt, layout.Hkv * n_rows * layout.D), n_rows,
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(eigenvalues, "eigenvalues", torch.float32, layout.Hkv * layout.D),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+        _stream_ptr(stream)), "loki_pca_fit")
+
+
+def loki_rank_at(eigenvalues: torch.Tensor, v_percent: float, ranks: torch.Tensor, stream=None) -> None:
+    n, D = eigenvalues.shape
+    _check(lib().loki_rank_at(_ptr(eigenvalues, "eigenvalues", torch.float32, n * D), n, D, v_percent,
+                              _ptr(ranks, "ranks", torch.int32, n), _stream_ptr(stream)), "loki_rank_at")
+
+
+def loki_index_jaccard(idx_a: torch.Tensor, idx_b: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    k = idx_a.shape[-1]
+    n = idx_a.numel() // k
+    _check(lib().loki_index_jaccard(_ptr(idx_a, "idx_a", torch.int32, n * k),
+                                    _ptr(idx_b, "idx_b", torch.int32, n * k), n, k,
+                                    _ptr(out, "out", torch.float32, n), _stream_ptr(stream)),
+           "loki_index_jaccard")
 
 
 def loki_stream_read(buf: torch.Tensor, nbytes: int, stream=None) -> None:

@@ -414,6 +414,54 @@ int loki_pca_attn(const loki_layout* layout, const void* q, const float* P, cons
   return LOKI_OK;
 }
 
+int loki_pca_workspace_bytes(const loki_layout* layout, long long n_rows, size_t* bytes) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!bytes || n_rows < 2 || n_rows > (1LL << 40)) return LOKI_ERR_INVALID_ARG;
+  *bytes = pca_workspace_bytes(s.Hkv, n_rows);
+  return LOKI_OK;
+}
+
+int loki_pca_fit(const loki_layout* layout, const void* keys, long long n_rows, float* P,
+                 float* eigenvalues, void* workspace, size_t workspace_bytes, void* stream) {
+  Shape s;
+  const int rc = check_layout(layout, &s);
+  if (rc != LOKI_OK) return rc;
+  if (!keys || !P || !eigenvalues || !workspace) return LOKI_ERR_INVALID_ARG;
+  if (n_rows < 2 || n_rows > (1LL << 40)) return LOKI_ERR_INVALID_ARG;
+  if (!aligned16(keys) || !aligned16(P) || !aligned16(eigenvalues)) return LOKI_ERR_ALIGNMENT;
+  if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+  if (pca_workspace_bytes(s.Hkv, n_rows) > workspace_bytes) return LOKI_ERR_WORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  StageTimer tm(st);
+  static const char* const kStageNames[3] = {"pca_gram", "pca_covariance", "pca_eigensolve"};
+  for (int stage = 0; stage < 3; ++stage) {
+    tm.begin(kStageNames[stage]);
+    const hipError_t e =
+        launch_pca_stage(stage, s.Hkv, s.dtype, keys, n_rows, P, eigenvalues, workspace, st);
+    tm.end();
+    if (e != hipSuccess) return LOKI_ERR_HIP;
+  }
+  return LOKI_OK;
+}
+
+int loki_rank_at(const float* eigenvalues, int n_heads, int D, float v_percent, int32_t* ranks,
+                 void* stream) {
+  if (!eigenvalues || !ranks || n_heads < 1 || D < 1) return LOKI_ERR_INVALID_ARG;
+  if (!(v_percent > 0.f) || v_percent > 100.f) return LOKI_ERR_INVALID_ARG;
+  const hipError_t e = launch_rank_at(eigenvalues, n_heads, D, v_percent, ranks,
+                                      static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+}
+
+int loki_index_jaccard(const int32_t* idx_a, const int32_t* idx_b, int n_lists, int k, float* out,
+                       void* stream) {
+  if (!idx_a || !idx_b || !out || n_lists < 1 || k < 1) return LOKI_ERR_INVALID_ARG;
+  const hipError_t e = launch_jaccard(idx_a, idx_b, n_lists, k, out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+}
+
 int loki_profile_create(loki_profile** out) {
   if (!out) return LOKI_ERR_INVALID_ARG;
   loki_profile* p = new (std::nothrow) loki_profile();

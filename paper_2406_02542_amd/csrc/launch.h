@@ -87,6 +87,14 @@ bool fused_eligible(const Shape& s);
 bool fused_preferred(const Shape& s);
 hipError_t launch_fused(const Shape& s, const void* q, const float* P, void* klo, void* khi,
                         void* v, void* out, int32_t* out_idx, hipStream_t st);
+// Calibration and diagnostics (calibrate.hip).
+size_t pca_workspace_bytes(int Hkv, long long N);
+hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, long long N, float* P,
+                            float* eigenvalues, void* workspace, hipStream_t st);
+hipError_t launch_rank_at(const float* eigenvalues, int n, int Dn, float v_percent, int32_t* ranks,
+                          hipStream_t st);
+hipError_t launch_jaccard(const int32_t* a, const int32_t* b, int n_lists, int k, float* out,
+                          hipStream_t st);
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
                          int pos, int n_new, hipStream_t st);
 

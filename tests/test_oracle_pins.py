@@ -516,3 +516,10 @@ def test_pca_attention_pins():
     qb, Kb, Vb = rng.standard_normal((2, 4, 8)), rng.standard_normal((2, 2, 30, 8)), rng.standard_normal((2, 2, 30, 8))
     ob = O.pca_attention_batch(qb, Pb, Kb, Vb, 3)
     np.testing.assert_array_equal(ob[1, 3], O.pca_attention(qb[1, 3], Pb[1], Kb[1, 1], Vb[1, 1], 3))
+
+
+def test_jaccard_closed_forms():
+    assert O.jaccard([1, 2, 3], [1, 2, 3]) == 1.0
+    assert O.jaccard([1, 2, 3], [4, 5, 6]) == 0.0
+    assert O.jaccard([0, 1, 2, 3], [2, 3, 4, 5]) == pytest.approx(2 / 6)
+    assert O.jaccard([0, 5, -1, -1], [5, 7, 9, -1]) == pytest.approx(1 / 4)  # -1 = padding

@@ -35,6 +35,12 @@ BATTERY = [
     pins.test_bf16_rounding_matches_torch,
     pins.test_rank_at_closed_form,
     pins.test_cost_model_prints_2p6x,
+    pins.test_step_without_options_is_the_batch_function,
+    pins.test_step_ragged_ignores_rows_past_each_sequence_and_pads_indices,
+    pins.test_step_keeping_one_row_returns_that_value_row,
+    pins.test_step_append_writes_the_rotated_rounded_key_then_attends,
+    pins.test_pca_attention_pins,
+    pins.test_jaccard_closed_forms,
 ]
 
 
@@ -85,6 +91,9 @@ MUTATIONS = {
     # helpers
     "bf16 truncation instead of rounding": ("to_bf16", lambda x: (np.asarray(x, np.float64).astype(np.float32).view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32).astype(np.float64)),
     "rank_at off by one": ("rank_at", lambda ev, v: max(1, _real_rank_at(ev, v) - 1)),
+    "PCAAttn scaled by sqrt(d)": ("pca_attention", lambda q, P, Khat, V, d: O.softmax(O.approx_scores(O.rotate_query(q, P), Khat, d) / math.sqrt(d)) @ np.asarray(V, float)),
+    "PCAAttn over the d LAST columns": ("pca_attention", lambda q, P, Khat, V, d: O.softmax((np.asarray(Khat, float)[:, -d:] @ O.rotate_query(q, P)[-d:]) / math.sqrt(len(q))) @ np.asarray(V, float)),
+    "Jaccard over the smaller set": ("jaccard", lambda a, b: len(set(a) & set(b)) / max(1, min(len(set(a)), len(set(b))))),
     "speed-up formula without the factor 1/2": ("theoretical_speedup", lambda D, S, d, k, exact=True: 1.0 / (d / D + k / S)),
 }
 _real_rank_at = O.rank_at
@@ -128,3 +137,26 @@ def test_product_package_never_imports_the_oracle():
     # and the oracle does not import the product
     otext = open(os.path.join(ROOT, "oracle", "loki_oracle.py")).read()
     assert "paper_2406_02542_amd" not in otext
+
+
+def _step_mutant(**change):
+    real = O.loki_decode_step
+
+    def mutant(q, P, Khat, V, d, k_max, select_mode=0, seq_lens=None, ks=None, k_new=None, v_new=None,
+               storage="f32", units=None):
+        if change.get("ignore_lens"):
+            seq_lens = None if ks is None else np.maximum(np.asarray(ks), np.asarray(seq_lens))
+        if change.get("append_row_off_by_one") and k_new is not None and seq_lens is not None:
+            seq2 = np.asarray(seq_lens) - 1
+            out = real(q, P, Khat, V, d, k_max, select_mode, np.maximum(seq2, np.asarray(ks) if ks is not None else 1), ks, k_new, v_new, storage, units)
+            return out
+        if change.get("no_rounding"):
+            storage = "f32"
+        return real(q, P, Khat, V, d, k_max, select_mode, seq_lens, ks, k_new, v_new, storage, units)
+    return mutant
+
+
+@pytest.mark.parametrize("change", ["ignore_lens", "append_row_off_by_one", "no_rounding"])
+def test_planted_mistake_in_the_step_is_caught(change, monkeypatch):
+    monkeypatch.setattr(O, "loki_decode_step", _step_mutant(**{change: True}))
+    assert battery_fails(), f"no pin noticed: {change}"

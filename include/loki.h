@@ -167,6 +167,16 @@ int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_fu
  *             anything is scored; the step then sees them like any cached row.
  *   v_new     device [B, Hkv, D]; required exactly when k_new is given.
  *
+ *   queries_per_seq  m; 0 or 1: one new token per sequence.  m > 1 (chunked or speculative
+ *             decoding): the last m tokens of every sequence are decoded at once.  Every
+ *             per-sequence argument then has m consecutive entries per sequence, token j of
+ *             sequence b at entry b m + j: q, out [B, m, Hq, D]; out_idx [B, m, Hsel, k_max];
+ *             k_new, v_new [B, m, Hkv, D]; seq_lens, ks [B m], seq_lens required, with
+ *             seq_lens[b m + j] = rows token j may see, counting itself (the causal limit:
+ *             normally rows_b - (m - 1 - j)).  Entry b m + j appends to row
+ *             seq_lens[b m + j] - 1 of sequence b's cache; all m rows are written before
+ *             anything is scored.  The workspace is sized for a layout with B m in place of B.
+ *
  * S_max and k_max (1 <= k_max <= S_max <= S_cap) size the workspace
  * (loki_workspace_bytes(layout, S_max, d, k_max, select_mode)) and out_idx:
  * out_idx is [B, Hsel, k_max], and a sequence keeping fewer than k_max rows has -1 in
@@ -178,6 +188,7 @@ typedef struct {
   const int32_t* ks;
   const void* k_new;
   const void* v_new;
+  int32_t queries_per_seq;
 } loki_step_args;
 
 int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,

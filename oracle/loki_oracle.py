@@ -182,41 +182,52 @@ def loki_decode_batch(q, P, Khat, V, d: int, k: int, select_mode: int = 0,
 
 def loki_decode_step(q, P, Khat, V, d: int, k_max: int, select_mode: int = 0,
                      seq_lens=None, ks=None, k_new=None, v_new=None, storage: str = "f32",
-                     units=None):
+                     units=None, queries_per_seq: int = 1):
     """The whole step of Algorithm 1 (lines 2-9), sequence by sequence.
 
-    Sequence b holds seq_lens[b] rows (default: all S of Khat) and keeps ks[b] of them
-    (default min(k_max, seq_lens[b])).  With k_new / v_new [B,Hkv,D] given, row
-    seq_lens[b]-1 of each (b, KV head) first becomes the rotated new key, rounded to
-    the storage type (lines 3-4), and the new value.  Each sequence is then
+    Entry e of the batch holds seq_lens[e] rows (default: all S of Khat) and keeps ks[e] of
+    them (default min(k_max, seq_lens[e])).  With k_new / v_new [E,Hkv,D] given, row
+    seq_lens[e]-1 of each (entry, KV head) first becomes the rotated new key, rounded to
+    the storage type (lines 3-4), and the new value.  Each entry is then
     loki_decode_batch on its own rows.
 
-    Returns (out [B,Hq,D], idx [B,Hsel,k_max] padded with -1, scores [B,Hsel,S]
-    NaN past each sequence's end, Khat, V): the last two are copies of the caches
+    queries_per_seq = m > 1: m consecutive entries (the last m tokens of one sequence)
+    share one cached sequence: q [B m,Hq,D] against Khat, V [B,Hkv,S,D]; all their rows are
+    appended first, then entry e attends over the first seq_lens[e] rows of sequence e // m
+    (its causal limit).
+
+    Returns (out [E,Hq,D], idx [E,Hsel,k_max] padded with -1, scores [E,Hsel,S]
+    NaN past each entry's end, Khat, V): the last two are copies of the caches
     after the append."""
-    B, Hq, D = q.shape
+    E, Hq, D = q.shape
     Hkv = P.shape[0]
     S = Khat.shape[2]
+    m = queries_per_seq
+    assert E == Khat.shape[0] * m
     Hsel = Hq if select_mode == SELECT_PER_QUERY_HEAD else Hkv
     Khat = np.array(Khat, dtype=np.float64, copy=True)
     V = np.array(V, dtype=np.float64, copy=True)
-    out = np.full((B, Hq, D), np.nan)
-    idx = np.full((B, Hsel, k_max), -1, dtype=np.int64)
-    scores = np.full((B, Hsel, S), np.nan)
-    for b in range(B):
-        S_b = S if seq_lens is None else int(seq_lens[b])
-        k_b = min(k_max, S_b) if ks is None else int(ks[b])
-        assert 1 <= k_b <= min(k_max, S_b) <= S
-        heads = [h for h in range(Hkv) if units is None or (b, h) in units]
-        if k_new is not None:
-            for h in heads:
-                Khat[b, h, S_b - 1] = to_storage(rotate_keys(k_new[b, h][None, :], P[h])[0], storage)
-                V[b, h, S_b - 1] = v_new[b, h]
-        o, i, a = loki_decode_batch(q[b:b + 1], P, Khat[b:b + 1, :, :S_b], V[b:b + 1, :, :S_b], d,
-                                    k_b, select_mode, units=[(0, h) for h in heads])
-        out[b] = o[0]
-        idx[b, :, :k_b] = i[0]
-        scores[b, :, :S_b] = a[0]
+    out = np.full((E, Hq, D), np.nan)
+    idx = np.full((E, Hsel, k_max), -1, dtype=np.int64)
+    scores = np.full((E, Hsel, S), np.nan)
+    S_of = [S if seq_lens is None else int(seq_lens[e]) for e in range(E)]
+    if k_new is not None:
+        for e in range(E):
+            for h in range(Hkv):
+                if units is None or (e, h) in units:
+                    Khat[e // m, h, S_of[e] - 1] = to_storage(rotate_keys(k_new[e, h][None, :], P[h])[0], storage)
+                    V[e // m, h, S_of[e] - 1] = v_new[e, h]
+    for e in range(E):
+        S_e = S_of[e]
+        k_e = min(k_max, S_e) if ks is None else int(ks[e])
+        assert 1 <= k_e <= min(k_max, S_e) <= S
+        heads = [h for h in range(Hkv) if units is None or (e, h) in units]
+        c = e // m
+        o, i, a = loki_decode_batch(q[e:e + 1], P, Khat[c:c + 1, :, :S_e], V[c:c + 1, :, :S_e], d,
+                                    k_e, select_mode, units=[(0, h) for h in heads])
+        out[e] = o[0]
+        idx[e, :, :k_e] = i[0]
+        scores[e, :, :S_e] = a[0]
     return out, idx, scores, Khat, V
 
 

@@ -210,7 +210,8 @@ def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
 class StepArgs(ctypes.Structure):
     """Mirror of ``loki_step_args``."""
     _fields_ = [("seq_lens", ctypes.c_void_p), ("ks", ctypes.c_void_p),
-                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p)]
+                ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
+                ("queries_per_seq", ctypes.c_int32)]
 
 
 def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
@@ -218,16 +219,19 @@ def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
                      select_mode: int, workspace: torch.Tensor, out: torch.Tensor,
                      out_idx: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
                      ks: Optional[torch.Tensor] = None, k_new: Optional[torch.Tensor] = None,
-                     v_new: Optional[torch.Tensor] = None, stream=None) -> None:
+                     v_new: Optional[torch.Tensor] = None, queries_per_seq: int = 1,
+                     stream=None) -> None:
     dt = _torch_dtype(layout)
+    m = max(1, queries_per_seq)
     rows = layout.B * layout.Hkv
-    nq = layout.B * layout.Hq * layout.D
+    nq = layout.B * m * layout.Hq * layout.D
     hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
     args = StepArgs(
-        _ptr(seq_lens, "seq_lens", torch.int32, layout.B),
-        _ptr(ks, "ks", torch.int32, layout.B),
-        _ptr(k_new, "k_new", dt, rows * layout.D),
-        _ptr(v_new, "v_new", dt, rows * layout.D))
+        _ptr(seq_lens, "seq_lens", torch.int32, layout.B * m),
+        _ptr(ks, "ks", torch.int32, layout.B * m),
+        _ptr(k_new, "k_new", dt, rows * m * layout.D),
+        _ptr(v_new, "v_new", dt, rows * m * layout.D),
+        queries_per_seq)
     _check(lib().loki_decode_step(
         ctypes.byref(layout),
         _ptr(q, "q", dt, nq),
@@ -238,7 +242,7 @@ def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
         S_max, d, k_max, select_mode, ctypes.byref(args),
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
         _ptr(out, "out", dt, nq),
-        _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k_max),
+        _ptr(out_idx, "out_idx", torch.int32, layout.B * m * hsel * k_max),
         _stream_ptr(stream)), "loki_decode_step")
 
 

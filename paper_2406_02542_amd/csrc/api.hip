@@ -238,6 +238,14 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   Shape s;
   const int rc = check_layout(layout, &s);
   if (rc != LOKI_OK) return rc;
+  if (rg.queries < 1 || rg.queries > 64) return LOKI_ERR_INVALID_ARG;
+  if (rg.queries > 1) {
+    // every query of a sequence is a batch entry of its own from here on; the kernels map
+    // entry b back to the cache of sequence b / queries
+    if ((long long)s.B * rg.queries * s.Hq > 0x7fffffffLL / 128) return LOKI_ERR_INVALID_ARG;
+    if (rg.seq_lens == nullptr) return LOKI_ERR_INVALID_ARG;  // each query has its own causal length
+    s.B *= rg.queries;
+  }
   if (!q || !P || !klo || !v || !out || !workspace) return LOKI_ERR_INVALID_ARG;
   if (s.d < 128 && !khi) return LOKI_ERR_INVALID_ARG;
   const int path = select_mode & LOKI_PATH_MASK;
@@ -320,6 +328,7 @@ int loki_decode_step(const loki_layout* layout, const void* q, const float* P, v
   if (args) {
     rg.seq_lens = args->seq_lens;
     rg.ks = args->ks;
+    rg.queries = args->queries_per_seq > 0 ? args->queries_per_seq : 1;
     ap.k_new = args->k_new;
     ap.v_new = args->v_new;
   }

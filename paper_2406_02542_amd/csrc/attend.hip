@@ -75,7 +75,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     }
   }
 
-  const RowAddr ra = make_row_addr<T, REUSE_LO, LO_ONLY>(k_a, k_b, v, (size_t)kv_unit, S_cap,
+  const RowAddr ra = make_row_addr<T, REUSE_LO, LO_ONLY>(k_a, k_b, v,
+                                                         (size_t)cache_unit(rag, kv_unit, Hq / Gq), S_cap,
                                                          (GATHER || LO_ONLY) ? d : kD, c);
   AttendAcc<T, NH> acc;
   acc.init();

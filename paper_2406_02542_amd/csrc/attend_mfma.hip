@@ -111,9 +111,10 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     kpitch[step] = in_lo ? (size_t)(GATHER ? d : kD) * 2 : (size_t)(kD - d) * 2;
     const char* base = in_lo ? static_cast<const char*>(k_a) + (size_t)c * 16
                              : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
-    kptr[step] = base + (size_t)kv_unit * S_cap * kpitch[step];
+    kptr[step] = base + (size_t)cache_unit(rg, kv_unit, Hkv) * S_cap * kpitch[step];
   }
-  const char* vptr = static_cast<const char*>(v) + (size_t)kv_unit * S_cap * (kD * 2) + (size_t)kgrp * 16;
+  const char* vptr = static_cast<const char*>(v) + (size_t)cache_unit(rg, kv_unit, Hkv) * S_cap * (kD * 2) +
+                     (size_t)kgrp * 16;
   unsigned char* my_v = s_v[wave];
 
   float m_run = kNegBig, l_run = 0.f;   // head r16, this lane's share of the rows

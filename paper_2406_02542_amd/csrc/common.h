@@ -22,6 +22,11 @@ __device__ __forceinline__ int seq_keep(const Ragged& rg, int b, int k_max, int 
   return max(1, min(k, min(k_max, S_b)));
 }
 
+// The (sequence, KV head) whose cache rows batch-entry unit `unit` = b * Hkv + h works on.
+__device__ __forceinline__ int cache_unit(const Ragged& rg, int unit, int Hkv) {
+  return rg.queries <= 1 ? unit : (unit / Hkv / rg.queries) * Hkv + unit % Hkv;
+}
+
 // Debug builds (-DLOKI_PHASE_TIMING) stamp the 100 MHz wall clock at phase boundaries of the
 // fused kernel's blocks so that its time line can be read back; a no-op otherwise.
 #ifdef LOKI_PHASE_TIMING

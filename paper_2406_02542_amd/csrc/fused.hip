@@ -237,6 +237,8 @@ size_t fused_dynamic_lds(const Shape& s) {
 }
 
 bool fused_eligible(const Shape& s) {
+  // several new tokens per sequence: a block would read rows appended by other blocks of the launch
+  if (s.rg.queries > 1) return false;
   return s.G == 1 && s.S <= kFusedMaxS && s.k <= kFusedMaxK;
 }
 

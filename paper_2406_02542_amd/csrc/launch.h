@@ -13,6 +13,8 @@ constexpr int kD = 128;  // head dimension the kernels are written for
 struct Ragged {
   const int32_t* seq_lens = nullptr;  // [B] cached rows of each sequence, 1..S
   const int32_t* ks = nullptr;        // [B] rows each sequence keeps, 1..min(k, its seq_len)
+  int queries = 1;  // consecutive batch entries that share one cached sequence (several new
+                    // tokens per sequence: entry b reads and appends to the cache of b / queries)
 };
 
 // The current token's key and value when the step also appends them to the cache (Algorithm 1

@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
   size_t row = 0;
   if constexpr (APPEND) {
     if (tid < kD) s_q[G][tid] = T::load1(static_cast<const ST*>(ap.k_new) + (size_t)unit * kD + tid);
-    row = (size_t)unit * S_cap + (size_t)(seq_rows(rg, unit / Hkv, S_max) - 1);
+    row = (size_t)cache_unit(rg, unit, Hkv) * S_cap + (size_t)(seq_rows(rg, unit / Hkv, S_max) - 1);
     if (blockIdx.y == 0 && tid >= kD)  // the value row is copied once per unit
       v[row * kD + (tid - kD)] = static_cast<const ST*>(ap.v_new)[(size_t)unit * kD + (tid - kD)];
   }
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void score_kernel(
       qr[g][e] = cact ? qhat[(size_t)(head0 + g) * kD + c * EPC + e] : 0.f;
 
   const size_t row_bytes = (size_t)d * T::kBytes;
-  const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
+  const char* base = reinterpret_cast<const char*>(klo) + (size_t)cache_unit(rg, unit, Hkv) * S_cap * row_bytes +
                      (size_t)(cact ? c : 0) * 16;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   // where this lane's chunk of load j sits inside a step
   const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
   const size_t row_bytes = (size_t)d * 2;
-  const char* base = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * row_bytes +
+  const char* base = reinterpret_cast<const char*>(klo) + (size_t)cache_unit(rg, unit, Hkv) * S_cap * row_bytes +
                      (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);

@@ -39,6 +39,11 @@ def test_layout_struct_matches_header():
     assert [f[0] for f in api.Layout._fields_] == ["B", "Hq", "Hkv", "D", "d_split", "S_cap", "dtype"]
 
 
+def test_step_args_struct_matches_header():
+    assert [f[0] for f in api.StepArgs._fields_] == ["seq_lens", "ks", "k_new", "v_new", "queries_per_seq"]
+    assert ctypes.sizeof(api.StepArgs) == 4 * 8 + 8  # four pointers, one int32, padding
+
+
 def test_cache_and_workspace_sizes():
     lay = api.make_layout(16, 32, 32, 128, 32, 4096, torch.bfloat16)
     klo, khi, v = api.loki_cache_bytes(lay)

@@ -314,3 +314,83 @@ def test_decode_step_replays_from_a_captured_graph(G, mode):
         torch.cuda.synchronize()
         assert torch.equal(out_g, out_e), f"replay {it} differs from the eager step"
         assert torch.isfinite(out_g.float()).all()
+
+
+# ------------------------------------------------------- several new tokens per sequence --
+@pytest.mark.parametrize("G,dtype,mode", [(1, "bf16", 0), (4, "bf16", 0), (4, "bf16", 1), (2, "f32", 0)])
+def test_step_with_several_new_tokens_per_sequence(G, dtype, mode):
+    """queries_per_seq = 3 (chunked / speculative decoding): token j of a sequence is appended
+    at its own row and attends up to and including it; entries of one sequence share its
+    cache.  Same protocol as the single-token cases."""
+    m, B = 3, 3
+    w = synth.Workload(f"multi_g{G}", B, 2 * G, 2, 128, 2500, dtype, 32, 400, seed=14000 + G)
+    wq = w.replace(B=B * m)
+    x = synth.make_inputs(w)
+    xq = synth.make_inputs(wq.replace(S=8))   # only its q is used
+    st = synth.make_step_inputs(wq, x["P"])    # k_new, v_new for B m entries
+    rows = np.array([2500, 700, 1337])         # rows of each sequence after the chunk
+    lens = np.array([rows[b] - (m - 1 - j) for b in range(B) for j in range(m)], np.int32)
+    ks = np.maximum(1, (w.k * lens.astype(np.int64)) // w.S).astype(np.int32)
+    say(f"case {w} m {m} mode {mode} lens {lens.tolist()} ks {ks.tolist()}")
+    tdt = TORCH_DT[dtype]
+    lay = api.make_layout(B, w.Hq, w.Hkv, 128, w.d, w.S, tdt)
+    klo, khi, v = api.alloc_cache(lay)
+    klo.fill_(3e4); khi.fill_(3e4); v.fill_(-3e4)
+    kh, vv = to_dev(x["khat"], dtype), to_dev(x["v"], dtype)
+    for b in range(B):
+        n = int(rows[b]) - m
+        klo[b, :, :n] = kh[b, :, :n, :w.d]; khi[b, :, :n] = kh[b, :, :n, w.d:]; v[b, :, :n] = vv[b, :, :n]
+    lay_ws = api.make_layout(B * m, w.Hq, w.Hkv, 128, w.d, w.S, tdt)
+    ws = api.alloc_workspace(lay_ws, w.S, w.d, w.k, mode)
+    out = torch.full((B * m, w.Hq, 128), float("nan"), dtype=tdt, device="cuda")
+    hsel = w.Hq if mode == 0 or G == 1 else w.Hkv
+    idx = torch.full((B * m, hsel, w.k), -7, dtype=torch.int32, device="cuda")
+    api.loki_decode_step(lay, to_dev(xq["q"], dtype), torch.from_numpy(x["P"]).cuda(), klo, khi, v, w.S,
+                         w.d, w.k, mode, ws, out, idx, seq_lens=torch.from_numpy(lens).cuda(),
+                         ks=torch.from_numpy(ks).cuda(), k_new=to_dev(st["k_new"], dtype),
+                         v_new=to_dev(st["v_new"], dtype), queries_per_seq=m)
+    torch.cuda.synchronize()
+    out_g = out.float().cpu().numpy().astype(np.float64)
+    idx_g = idx.cpu().numpy()
+    # the GPU's appended rows (checked against the oracle's rotation) go into the oracle's cache
+    kcat = torch.cat([klo, khi], dim=-1).float().cpu().numpy().astype(np.float64)
+    khat, vref = x["khat"].astype(np.float64).copy(), x["v"].astype(np.float64).copy()
+    for e in range(B * m):
+        b, r = e // m, int(lens[e]) - 1
+        for h in range(w.Hkv):
+            ref64 = O.rotate_keys(st["k_new"][e, h][None, :], x["P"][h])[0]
+            ref = O.to_storage(ref64, dtype)
+            if dtype == "bf16":
+                ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref), 1e-30))) - 7)
+                mag = np.abs(st["k_new"][e, h].astype(np.float64)) @ np.abs(x["P"][h].astype(np.float64))
+                assert np.all(np.abs(kcat[b, h, r] - ref) <= ulp * 1.0000001 + 1e-6 * mag)
+            else:
+                assert np.max(np.abs(kcat[b, h, r] - ref64)) / np.linalg.norm(ref64) < 2e-6
+        khat[b, :, r] = kcat[b, :, r]
+        vref[b, :, r] = st["v_new"][e].astype(np.float64)
+        assert np.array_equal(v[b, :, r].float().cpu().numpy(), st["v_new"][e])
+    for b in range(B):
+        assert torch.all(klo[b, :, rows[b]:] == 3e4) and torch.all(v[b, :, rows[b]:] == -3e4)
+    eff_mode = 0 if G == 1 else mode
+    out_o, idx_o, sc_o, _, _ = O.loki_decode_step(xq["q"], x["P"], khat, vref, w.d, w.k, eff_mode,
+                                                  seq_lens=lens, ks=ks, queries_per_seq=m)
+    tol, max_err = OUT_TOL[dtype], 0.0
+    for e in range(B * m):
+        S_e, k_e, b = int(lens[e]), int(ks[e]), e // m
+        for h in range(w.Hkv):
+            qheads = range(h * G, (h + 1) * G)
+            same = {}
+            for hs in (qheads if eff_mode == 0 else [h]):
+                assert np.all(idx_g[e, hs, k_e:] == -1)
+                same[hs] = check_index_set(idx_g[e, hs, :k_e], idx_o[e, hs, :k_e], sc_o[e, hs, :S_e], S_e, k_e,
+                                           f"entry {e} sel_head {hs}")
+            for hq in qheads:
+                hs = hq if eff_mode == 0 else h
+                ref = out_o[e, hq]
+                if not same[hs]:
+                    qhat = O.rotate_query(xq["q"][e, hq], x["P"][h])
+                    ref = O.attend_selected(qhat, khat[b, h, :S_e], vref[b, h, :S_e], idx_g[e, hs, :k_e].astype(np.int64))
+                err = float(np.max(np.abs(out_g[e, hq] - ref)))
+                max_err = max(max_err, err)
+                assert err <= tol, f"entry {e} hq {hq}: {err:.3e}"
+    say(f"   max_err {max_err:.3e}")

@@ -39,6 +39,7 @@ BATTERY = [
     pins.test_step_ragged_ignores_rows_past_each_sequence_and_pads_indices,
     pins.test_step_keeping_one_row_returns_that_value_row,
     pins.test_step_append_writes_the_rotated_rounded_key_then_attends,
+    pins.test_step_with_several_new_tokens_is_sequential_decoding,
     pins.test_pca_attention_pins,
     pins.test_jaccard_closed_forms,
 ]
@@ -143,20 +144,32 @@ def _step_mutant(**change):
     real = O.loki_decode_step
 
     def mutant(q, P, Khat, V, d, k_max, select_mode=0, seq_lens=None, ks=None, k_new=None, v_new=None,
-               storage="f32", units=None):
+               storage="f32", units=None, queries_per_seq=1):
+        if change.get("later_tokens_visible") and queries_per_seq > 1 and k_new is not None:
+            return _chunk_all_visible(real, q, P, Khat, V, d, k_max, select_mode, seq_lens, ks, k_new,
+                                      v_new, storage, queries_per_seq)
         if change.get("ignore_lens"):
             seq_lens = None if ks is None else np.maximum(np.asarray(ks), np.asarray(seq_lens))
         if change.get("append_row_off_by_one") and k_new is not None and seq_lens is not None:
             seq2 = np.asarray(seq_lens) - 1
-            out = real(q, P, Khat, V, d, k_max, select_mode, np.maximum(seq2, np.asarray(ks) if ks is not None else 1), ks, k_new, v_new, storage, units)
+            out = real(q, P, Khat, V, d, k_max, select_mode, np.maximum(seq2, np.asarray(ks) if ks is not None else 1), ks, k_new, v_new, storage, units, queries_per_seq)
             return out
         if change.get("no_rounding"):
             storage = "f32"
-        return real(q, P, Khat, V, d, k_max, select_mode, seq_lens, ks, k_new, v_new, storage, units)
+        return real(q, P, Khat, V, d, k_max, select_mode, seq_lens, ks, k_new, v_new, storage, units,
+                    queries_per_seq)
     return mutant
 
 
-@pytest.mark.parametrize("change", ["ignore_lens", "append_row_off_by_one", "no_rounding"])
+def _chunk_all_visible(real, q, P, Khat, V, d, k_max, mode, seq_lens, ks, k_new, v_new, storage, m):
+    """Mistake: appends the chunk at the right rows but lets every token attend over all of it."""
+    _, _, _, K1, V1 = real(q, P, Khat, V, d, k_max, mode, seq_lens, ks, k_new, v_new, storage, None, m)
+    full = np.repeat(np.asarray(seq_lens).reshape(-1, m).max(axis=1), m) if m > 1 else seq_lens
+    out, idx, sc, _, _ = real(q, P, K1, V1, d, k_max, mode, full, ks, None, None, storage, None, m)
+    return out, idx, sc, K1, V1
+
+
+@pytest.mark.parametrize("change", ["ignore_lens", "append_row_off_by_one", "no_rounding", "later_tokens_visible"])
 def test_planted_mistake_in_the_step_is_caught(change, monkeypatch):
     monkeypatch.setattr(O, "loki_decode_step", _step_mutant(**{change: True}))
     assert battery_fails(), f"no pin noticed: {change}"

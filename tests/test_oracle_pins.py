@@ -523,3 +523,28 @@ def test_jaccard_closed_forms():
     assert O.jaccard([1, 2, 3], [4, 5, 6]) == 0.0
     assert O.jaccard([0, 1, 2, 3], [2, 3, 4, 5]) == pytest.approx(2 / 6)
     assert O.jaccard([0, 5, -1, -1], [5, 7, 9, -1]) == pytest.approx(1 / 4)  # -1 = padding
+
+
+def test_step_with_several_new_tokens_is_sequential_decoding():
+    """queries_per_seq = m: the same outputs, index lists and cache as m single-token steps
+    run one after the other (token j appended, then decoded, before token j+1 exists)."""
+    rng, P, q1, K, V = _step_case(seed=34, B=2, Hq=4, Hkv=2, D=8, S=30)
+    m = 3
+    Khat = O.to_bf16(O.rotate_keys_batch(K, P))
+    rows = np.array([30, 11])                       # rows of each sequence after the chunk
+    q = rng.standard_normal((2 * m, 4, 8))
+    k_new = O.to_bf16(rng.standard_normal((2 * m, 2, 8)))
+    v_new = O.to_bf16(rng.standard_normal((2 * m, 2, 8)))
+    lens = np.array([rows[b] - (m - 1 - j) for b in range(2) for j in range(m)])
+    ks = np.minimum(4, lens)
+    out, idx, sc, K1, V1 = O.loki_decode_step(q, P, Khat, V, 3, 4, 0, seq_lens=lens, ks=ks, k_new=k_new,
+                                              v_new=v_new, storage="bf16", queries_per_seq=m)
+    Kc, Vc = Khat, V
+    for j in range(m):
+        e = np.array([b * m + j for b in range(2)])
+        o_j, i_j, _, Kc, Vc = O.loki_decode_step(q[e], P, Kc, Vc, 3, 4, 0, seq_lens=lens[e], ks=ks[e],
+                                                 k_new=k_new[e], v_new=v_new[e], storage="bf16")
+        np.testing.assert_array_equal(out[e], o_j)
+        np.testing.assert_array_equal(idx[e], i_j)
+    np.testing.assert_array_equal(K1, Kc)
+    np.testing.assert_array_equal(V1, Vc)

@@ -49,7 +49,8 @@ extern "C" {
 typedef enum {
   LOKI_OK = 0,
   LOKI_ERR_INVALID_ARG = 1,     /* null pointer, size out of range, Hq % Hkv != 0 ...   */
-  LOKI_ERR_UNSUPPORTED = 2,     /* D != 128, unknown dtype, d not loadable in 16-B units  */
+  LOKI_ERR_UNSUPPORTED = 2,     /* D != 128, unknown dtype, d not loadable in 16-B units,
+                                   Hq / Hkv not in {1, 2, 4, 8}, B * Hq > 65535           */
   LOKI_ERR_ALIGNMENT = 3,       /* a base pointer is not 16-byte aligned                  */
   LOKI_ERR_WORKSPACE = 4,       /* workspace smaller than loki_workspace_bytes reports    */
   LOKI_ERR_HIP = 5              /* the HIP runtime reported an error at launch            */
@@ -73,7 +74,7 @@ enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
 enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_MASK = 0x300 };
 
 typedef struct {
-  int32_t B;        /* sequences in the batch                         */
+  int32_t B;        /* sequences in the batch; B * Hq <= 65535           */
   int32_t Hq;       /* query heads                                    */
   int32_t Hkv;      /* KV heads; Hq % Hkv == 0                        */
   int32_t D;        /* head dimension (128)                           */

@@ -113,8 +113,8 @@ static int check_layout(const loki_layout* L, Shape* s) {
   if ((L->d_split * eb) % 16 != 0) return LOKI_ERR_UNSUPPORTED;
   const int G = L->Hq / L->Hkv;
   if (G != 1 && G != 2 && G != 4 && G != 8) return LOKI_ERR_UNSUPPORTED;
-  // element counts must fit the kernels' 64-bit row arithmetic with 32-bit row indices
-  if ((long long)L->B * L->Hq > 0x7fffffffLL / 128) return LOKI_ERR_INVALID_ARG;
+  // heads index the second grid dimension of several kernels (at most 65 535 blocks)
+  if ((long long)L->B * L->Hq > 65535) return LOKI_ERR_UNSUPPORTED;
   s->B = L->B;
   s->Hq = L->Hq;
   s->Hkv = L->Hkv;
@@ -242,7 +242,7 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   if (rg.queries > 1) {
     // every query of a sequence is a batch entry of its own from here on; the kernels map
     // entry b back to the cache of sequence b / queries
-    if ((long long)s.B * rg.queries * s.Hq > 0x7fffffffLL / 128) return LOKI_ERR_INVALID_ARG;
+    if ((long long)s.B * rg.queries * s.Hq > 65535) return LOKI_ERR_UNSUPPORTED;
     if (rg.seq_lens == nullptr) return LOKI_ERR_INVALID_ARG;  // each query has its own causal length
     s.B *= rg.queries;
   }

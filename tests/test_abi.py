@@ -81,6 +81,8 @@ def test_rejects_bad_arguments_before_launch():
     assert L.loki_workspace_bytes(by(bad), 512, 32, 8, 0, by(n)) == 2    # D != 128
     bad = api.Layout(2, 8, 2, 128, 12, 512, 1)
     assert L.loki_workspace_bytes(by(bad), 512, 12, 8, 0, by(n)) == 2    # 24-byte slab rows
+    bad = api.Layout(2048, 32, 32, 128, 32, 512, 1)
+    assert L.loki_workspace_bytes(by(bad), 512, 32, 8, 0, by(n)) == 2    # B * Hq beyond the grid limit
     bad = api.Layout(2, 8, 2, 128, 32, 512, 9)
     assert L.loki_workspace_bytes(by(bad), 512, 32, 8, 0, by(n)) == 2    # dtype
     # compute entry points: every failure below is detected on the host, nothing is launched

@@ -293,6 +293,34 @@ def main():
             _, _, v, kf = caches[i % len(caches)]
             api.dense_decode_step(lay, q, kf, v, w.S, lens, wsd, out, stream)
 
+        # the same step on a paged cache: the rows of cache copy 0 scattered over randomly ordered
+        # physical pages of 256 rows (a quarter of the pool unused)
+        page_rows = 256
+        pps = (w.S + page_rows - 1) // page_rows
+        n_pages = w.B * pps * 4 // 3 + 1
+        gen_p = torch.Generator(device="cpu")
+        gen_p.manual_seed(w.seed)
+        table = torch.randperm(n_pages, generator=gen_p)[:w.B * pps].to(torch.int32).view(w.B, pps).cuda()
+
+        def to_pool(c):
+            pool = torch.zeros((n_pages, w.Hkv, page_rows, c.shape[-1]), dtype=tdt, device="cuda")
+            pad = pps * page_rows - c.shape[2]
+            if pad:
+                c = torch.nn.functional.pad(c, (0, 0, 0, pad))
+            pool[table.view(-1).long()] = c.view(w.B, w.Hkv, pps, page_rows, -1).permute(0, 2, 1, 3, 4).reshape(
+                w.B * pps, w.Hkv, page_rows, -1)
+            return pool
+
+        pools = [to_pool(caches[0][0]), to_pool(caches[0][1]) if caches[0][1] is not None else None,
+                 to_pool(caches[0][2])]
+
+        def paged_step(i):
+            api.loki_decode_step(lay, q, P, pools[0], pools[1], pools[2], w.S, w.d, w.k, mode | path_bits,
+                                 ws, out, None, k_new=k_new, v_new=v_new, page_table=table,
+                                 page_rows=page_rows, n_pages=n_pages, stream=stream)
+
+        t_paged = timed(paged_step, args.steps, args.warmup)
+        del pools
         t_app = timed(append_step, args.steps, args.warmup)
         t_sep = timed(separate_step, args.steps, args.warmup)
         t_rag = timed(ragged_step, args.steps, args.warmup)
@@ -303,6 +331,8 @@ def main():
                               for L, K in zip(st_in["seq_lens"], st_in["ks"])))
         rag_dense_bytes = float(sum(w.Hkv * int(L) * 2 * w.D * e for L in st_in["seq_lens"]))
         step = {"append_folded_in_us": t_app * 1e6,
+                "paged_cache": {"page_rows": page_rows, "pool_pages": n_pages,
+                                "append_folded_in_us": t_paged * 1e6},
                 "rotate_keys_then_value_copy_then_decode_us": t_sep * 1e6,
                 "ragged": {"seq_lens_min_mean_max": [int(st_in["seq_lens"].min()),
                                                      float(st_in["seq_lens"].mean()),
@@ -310,6 +340,7 @@ def main():
                            "us": t_rag * 1e6, "hbm_gbps": rag_bytes / t_rag / 1e9,
                            "dense_us": t_rd * 1e6, "dense_hbm_gbps": rag_dense_bytes / t_rd / 1e9,
                            "speedup_vs_dense": t_rd / t_rag}}
+        log(f"[bench] paged cache, step with append {t_paged * 1e6:.1f} us")
         log(f"[bench] step with append {t_app * 1e6:.1f} us (separate calls {t_sep * 1e6:.1f} us); "
             f"ragged {t_rag * 1e6:.1f} us, dense ragged {t_rd * 1e6:.1f} us")
 

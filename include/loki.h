@@ -178,6 +178,14 @@ int dense_decode_attn(const loki_layout* layout, const void* q, const void* k_fu
  *             seq_lens[b m + j] - 1 of sequence b's cache; all m rows are written before
  *             anything is scored.  The workspace is sized for a layout with B m in place of B.
  *
+ *   page_table  device int32 [B, pages_per_seq] or NULL.  When given, the cache is paged:
+ *             klo, khi and v are pools [n_pages, Hkv, page_rows, d | D - d | D] and row s of
+ *             sequence b lives in physical page page_table[b * pages_per_seq + s / page_rows]
+ *             at row s % page_rows, the same page of all three pools.  page_rows is a power of
+ *             two >= 256; pages_per_seq * page_rows >= S_max; entries are clamped into
+ *             [0, n_pages); n_pages * Hkv * page_rows < 2^31.  layout->S_cap is then only the
+ *             bound of S_max.
+ *
  * S_max and k_max (1 <= k_max <= S_max <= S_cap) size the workspace
  * (loki_workspace_bytes(layout, S_max, d, k_max, select_mode)) and out_idx:
  * out_idx is [B, Hsel, k_max], and a sequence keeping fewer than k_max rows has -1 in
@@ -190,6 +198,10 @@ typedef struct {
   const void* k_new;
   const void* v_new;
   int32_t queries_per_seq;
+  int32_t page_rows;
+  const int32_t* page_table;
+  int32_t pages_per_seq;
+  int32_t n_pages;
 } loki_step_args;
 
 int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,

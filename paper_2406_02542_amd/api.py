@@ -211,7 +211,9 @@ class StepArgs(ctypes.Structure):
     """Mirror of ``loki_step_args``."""
     _fields_ = [("seq_lens", ctypes.c_void_p), ("ks", ctypes.c_void_p),
                 ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
-                ("queries_per_seq", ctypes.c_int32)]
+                ("queries_per_seq", ctypes.c_int32), ("page_rows", ctypes.c_int32),
+                ("page_table", ctypes.c_void_p), ("pages_per_seq", ctypes.c_int32),
+                ("n_pages", ctypes.c_int32)]
 
 
 def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
@@ -220,7 +222,10 @@ def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
                      out_idx: Optional[torch.Tensor] = None, seq_lens: Optional[torch.Tensor] = None,
                      ks: Optional[torch.Tensor] = None, k_new: Optional[torch.Tensor] = None,
                      v_new: Optional[torch.Tensor] = None, queries_per_seq: int = 1,
-                     stream=None) -> None:
+                     page_table: Optional[torch.Tensor] = None, page_rows: int = 0,
+                     n_pages: int = 0, stream=None) -> None:
+    """With ``page_table`` [B, pages_per_seq] (int32), ``klo``/``khi``/``v`` are the paged
+    pools [n_pages, Hkv, page_rows, width]."""
     dt = _torch_dtype(layout)
     m = max(1, queries_per_seq)
     rows = layout.B * layout.Hkv
@@ -231,14 +236,17 @@ def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
         _ptr(ks, "ks", torch.int32, layout.B * m),
         _ptr(k_new, "k_new", dt, rows * m * layout.D),
         _ptr(v_new, "v_new", dt, rows * m * layout.D),
-        queries_per_seq)
+        queries_per_seq, page_rows,
+        _ptr(page_table, "page_table", torch.int32, layout.B),
+        (page_table.numel() // layout.B) if page_table is not None else 0, n_pages)
+    cache_rows = (n_pages * layout.Hkv * page_rows) if page_table is not None else rows * layout.S_cap
     _check(lib().loki_decode_step(
         ctypes.byref(layout),
         _ptr(q, "q", dt, nq),
         _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
-        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
-        _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
-        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        _ptr(klo, "klo", dt, cache_rows * layout.d_split),
+        _ptr(khi, "khi", dt, cache_rows * (layout.D - layout.d_split)),
+        _ptr(v, "v", dt, cache_rows * layout.D),
         S_max, d, k_max, select_mode, ctypes.byref(args),
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
         _ptr(out, "out", dt, nq),

@@ -34,19 +34,43 @@ def is_stale() -> bool:
     return any(os.path.getmtime(d) > built for d in deps)
 
 
-def build(verbose: bool = True) -> str:
-    """Compiles every HIP source into paper_2406_02542_amd/libloki.so (always recompiles)."""
-    cmd = [find_hipcc()] + HIPCC_FLAGS + ["-o", LIB_PATH + ".tmp"] + \
-        [os.path.join(CSRC, f) for f in SOURCES]
-    if verbose:
-        print("[build]", " ".join(cmd), flush=True)
+def _run(cmd):
     proc = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in proc.stderr.splitlines() if noise not in l)
-    if proc.returncode != 0:
-        raise RuntimeError(f"hipcc failed ({proc.returncode}):\n{proc.stdout}\n{err}")
-    if verbose and err.strip():
-        print(err, file=sys.stderr)
+    return proc.returncode, proc.stdout, err
+
+
+def build(verbose: bool = True) -> str:
+    """Compiles every HIP source into paper_2406_02542_amd/libloki.so (always recompiles):
+    one object per source, compiled in parallel, then one link."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = find_hipcc()
+    obj_dir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+
+    def compile_one(src):
+        obj = os.path.join(obj_dir, os.path.splitext(src)[0] + ".o")
+        cmd = [hipcc] + flags + ["-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print("[build]", " ".join(cmd), flush=True)
+        return (src, obj) + _run(cmd)
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 4)) as ex:
+        results = list(ex.map(compile_one, SOURCES))
+    for src, obj, rc, out, err in results:
+        if rc != 0:
+            raise RuntimeError(f"hipcc failed on {src} ({rc}):\n{out}\n{err}")
+        if verbose and err.strip():
+            print(err, file=sys.stderr)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH + ".tmp"] + \
+        [r[1] for r in results]
+    if verbose:
+        print("[build]", " ".join(link), flush=True)
+    rc, out, err = _run(link)
+    if rc != 0:
+        raise RuntimeError(f"link failed ({rc}):\n{out}\n{err}")
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     return LIB_PATH
 

@@ -19,8 +19,15 @@ int score_rows_per_block(const Shape& s) {
   const int max_chunks = div_up(s.S, 2 * kScoreRowsPerStep);
   if (nchunks > max_chunks) nchunks = max_chunks;
   if (nchunks < 1) nchunks = 1;
-  const int rows = div_up(s.S, nchunks);
-  return div_up(rows, kScoreRowsPerStep) * kScoreRowsPerStep;
+  int rows = div_up(div_up(s.S, nchunks), kScoreRowsPerStep) * kScoreRowsPerStep;
+  if (s.pg.table != nullptr) {
+    // a block must lie inside one page: the largest power of two (>= 256) within rows and the page
+    const int page_rows = 1 << s.pg.lg_rows;
+    int r = kScoreRowsPerStep;
+    while (2 * r <= rows && 2 * r <= page_rows) r *= 2;
+    rows = r;
+  }
+  return rows;
 }
 
 int gather_splits(const Shape& s, int select_mode) {
@@ -233,8 +240,8 @@ int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* 
 // loki_decode_step.
 static int decode_impl(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,
                        void* v, int S, int d, int k, int select_mode, const Ragged& rg,
-                       const Append& ap, void* workspace, size_t workspace_bytes, void* out,
-                       int32_t* out_idx, void* stream) {
+                       const Append& ap, const Paging& pg, void* workspace, size_t workspace_bytes,
+                       void* out, int32_t* out_idx, void* stream) {
   Shape s;
   const int rc = check_layout(layout, &s);
   if (rc != LOKI_OK) return rc;
@@ -263,10 +270,19 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   if ((reinterpret_cast<uintptr_t>(rg.seq_lens) & 3u) || (reinterpret_cast<uintptr_t>(rg.ks) & 3u))
     return LOKI_ERR_ALIGNMENT;
   if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+  if (pg.table != nullptr) {
+    const int page_rows = 1 << pg.lg_rows;
+    if (pg.lg_rows < 8 || pg.lg_rows > 24 || pg.pages_per_seq < 1 || pg.n_pages < 1)
+      return LOKI_ERR_INVALID_ARG;
+    if ((long long)pg.pages_per_seq * page_rows < S) return LOKI_ERR_INVALID_ARG;
+    if ((long long)pg.n_pages * s.Hkv * page_rows > 0x7fffffffLL) return LOKI_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(pg.table) & 3u) return LOKI_ERR_ALIGNMENT;
+  }
   s.S = S;
   s.k = k;
   s.rg = rg;
   s.ap = ap;
+  s.pg = pg;
   if (s.G == 1) select_mode = LOKI_SELECT_PER_QUERY_HEAD;  // identical; one code path
   const int nsplit = gather_splits(s, select_mode);
   const Workspace w = plan_workspace(s, select_mode, nsplit, workspace);
@@ -315,8 +331,8 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
                      void* stream) {
   // nothing is appended, so the caches are only read
   return decode_impl(layout, q, P, const_cast<void*>(klo), const_cast<void*>(khi),
-                     const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, workspace,
-                     workspace_bytes, out, out_idx, stream);
+                     const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, Paging{},
+                     workspace, workspace_bytes, out, out_idx, stream);
 }
 
 int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,
@@ -325,6 +341,16 @@ int loki_decode_step(const loki_layout* layout, const void* q, const float* P, v
                      int32_t* out_idx, void* stream) {
   Ragged rg;
   Append ap;
+  Paging pg;
+  if (args && args->page_table) {
+    int lg = 0;
+    while (lg < 31 && (1 << lg) < args->page_rows) ++lg;
+    if (args->page_rows < 1 || (1 << lg) != args->page_rows) return LOKI_ERR_INVALID_ARG;
+    pg.table = args->page_table;
+    pg.lg_rows = lg;
+    pg.pages_per_seq = args->pages_per_seq;
+    pg.n_pages = args->n_pages;
+  }
   if (args) {
     rg.seq_lens = args->seq_lens;
     rg.ks = args->ks;
@@ -332,7 +358,7 @@ int loki_decode_step(const loki_layout* layout, const void* q, const float* P, v
     ap.k_new = args->k_new;
     ap.v_new = args->v_new;
   }
-  return decode_impl(layout, q, P, klo, khi, v, S_max, d, k_max, select_mode, rg, ap, workspace,
+  return decode_impl(layout, q, P, klo, khi, v, S_max, d, k_max, select_mode, rg, ap, pg, workspace,
                      workspace_bytes, out, out_idx, stream);
 }
 

@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     const float* __restrict__ sel_score,   // REUSE_LO: [blocks_y, n] approximate scores of sel_idx
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     void* __restrict__ out,         // [B*Hq, 128] storage type when nsplit == 1
-    int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag) {
+    int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag, Paging pg) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;           // lanes per row: 16 (bf16) or 32 (fp32)
@@ -51,10 +51,14 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   const int r0 = blockIdx.x * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
 
+  // a paged cache: the list in LDS holds rows of the pool and the slabs are addressed from their start
+  const bool paged = GATHER && pg.table != nullptr;
+  const int cache_b = bidx / max(rag.queries, 1);
   if constexpr (GATHER) {
     const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
     for (int i = tid; i < r1 - r0; i += kAttThreads) {
-      s_idx[i] = idx[r0 + i];
+      const int pos = idx[r0 + i];
+      s_idx[i] = paged ? (int32_t)cache_row(pg, cache_b, kv_unit % (Hq / Gq), Hq / Gq, S_cap, pos) : pos;
       if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)blockIdx.y * n_max + r0 + i];
     }
     __syncthreads();
@@ -76,7 +80,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   }
 
   const RowAddr ra = make_row_addr<T, REUSE_LO, LO_ONLY>(k_a, k_b, v,
-                                                         (size_t)cache_unit(rag, kv_unit, Hq / Gq), S_cap,
+                                                         paged ? (size_t)0 : (size_t)cache_unit(rag, kv_unit, Hq / Gq), S_cap,
                                                          (GATHER || LO_ONLY) ? d : kD, c);
   AttendAcc<T, NH> acc;
   acc.init();
@@ -149,18 +153,18 @@ static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block,
                                    const void* k_b, const void* v, const void* qv,
                                    const int32_t* sel_idx, const float* sel_score, float* partial,
                                    void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
-                                   const Ragged& rg, hipStream_t st) {
+                                   const Ragged& rg, const Paging& pg, hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
   // (d = 128, Exact-TopK of Section 5: it is the whole logit and no key is read again)
   constexpr bool kCanReuse = GATHER && NH == 1;
   if (kCanReuse && sel_score != nullptr) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg);
   } else {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, false>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg);
   }
   return hipGetLastError();
 }
@@ -170,10 +174,10 @@ static hipError_t launch_attend_t(int NH, int blocks_y, int nsplit, int rows_per
                                   const void* k_a, const void* k_b, const void* v, const void* qv,
                                   const int32_t* sel_idx, const float* sel_score, float* partial,
                                   void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
-                                  const Ragged& rg, hipStream_t st) {
+                                  const Ragged& rg, const Paging& pg, hipStream_t st) {
 #define LOKI_ATT(NHV)                                                                          \
   return launch_attend_nh<T, NHV, GATHER>(blocks_y, nsplit, rows_per_block, k_a, k_b, v, qv,   \
-                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, st)
+                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, st)
   switch (NH) {
     case 1: LOKI_ATT(1);
     case 2: LOKI_ATT(2);
@@ -197,9 +201,9 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   if (s.dtype == 0)
     return launch_attend_t<F32, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, st);
+                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, st);
   return launch_attend_t<BF16, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, st);
+                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, st);
 }
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
@@ -209,9 +213,9 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)
     return launch_attend_t<F32, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
+                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, st);
+                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, st);
 }
 
 template <typename T, int NH>
@@ -219,7 +223,7 @@ static hipError_t launch_pca_nh(const Shape& s, int nsplit, int rpb, const float
                                 const void* v, float* partial, void* out, hipStream_t st) {
   hipLaunchKernelGGL((attend_kernel<T, NH, false, false, true>), dim3(nsplit, s.B * s.Hkv),
                      dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, out,
-                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg);
+                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{});
   return hipGetLastError();
 }
 

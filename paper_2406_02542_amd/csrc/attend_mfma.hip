@@ -43,7 +43,8 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     const int32_t* __restrict__ sel_idx,  // GATHER: [blocks_y, n]
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     uint16_t* __restrict__ out,     // [B*Hq, 128] bf16 when nsplit == 1
-    int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg) {
+    int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg,
+    Paging pg) {
   constexpr int QT = GATHER ? 2 : 1;
   __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmRows * kAmPitch];  // 8448 B per wave
   __shared__ int32_t s_idx[GATHER ? kMaxGatherChunk : 1];
@@ -64,11 +65,18 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
   const int r0 = blockIdx.x * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
 
+  // a paged cache: the list in LDS holds rows of the pool and the slabs are addressed from their start
+  const bool paged = GATHER && pg.table != nullptr;
   if constexpr (GATHER) {
     const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
-    for (int i = tid; i < r1 - r0; i += kAmThreads) s_idx[i] = idx[r0 + i];
+    const int cache_b = bidx / max(rg.queries, 1);
+    for (int i = tid; i < r1 - r0; i += kAmThreads) {
+      const int pos = idx[r0 + i];
+      s_idx[i] = paged ? (int32_t)cache_row(pg, cache_b, kv_unit % Hkv, Hkv, S_cap, pos) : pos;
+    }
     __syncthreads();
   }
+  const size_t addr_unit = paged ? (size_t)0 : (size_t)cache_unit(rg, kv_unit, Hkv);
 
   // B operand of the first product: q of head r16, columns 32*step + 8*kgrp .. +7
   am_bf16x8_t bq[4][QT];
@@ -111,10 +119,9 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     kpitch[step] = in_lo ? (size_t)(GATHER ? d : kD) * 2 : (size_t)(kD - d) * 2;
     const char* base = in_lo ? static_cast<const char*>(k_a) + (size_t)c * 16
                              : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
-    kptr[step] = base + (size_t)cache_unit(rg, kv_unit, Hkv) * S_cap * kpitch[step];
+    kptr[step] = base + addr_unit * S_cap * kpitch[step];
   }
-  const char* vptr = static_cast<const char*>(v) + (size_t)cache_unit(rg, kv_unit, Hkv) * S_cap * (kD * 2) +
-                     (size_t)kgrp * 16;
+  const char* vptr = static_cast<const char*>(v) + addr_unit * S_cap * (kD * 2) + (size_t)kgrp * 16;
   unsigned char* my_v = s_v[wave];
 
   float m_run = kNegBig, l_run = 0.f;   // head r16, this lane's share of the rows
@@ -262,17 +269,17 @@ static hipError_t launch_attend_mfma_nh(int NH, int blocks_y, int nsplit, int rp
                                         const void* k_b, const void* v, const void* qv,
                                         const int32_t* sel_idx, float* partial, void* out, int S_cap,
                                         int d, int n, int Hkv, int S_max, const Ragged& rg,
-                                        hipStream_t st) {
+                                        const Paging& pg, hipStream_t st) {
   const dim3 grid(nsplit, blocks_y), block(kAmThreads);
   uint16_t* o16 = static_cast<uint16_t*>(out);
   switch (NH) {
     case 4:
       hipLaunchKernelGGL((attend_mfma_kernel<4, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg);
+                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
       break;
     case 8:
       hipLaunchKernelGGL((attend_mfma_kernel<8, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg);
+                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
       break;
     default:
       return hipErrorInvalidValue;
@@ -288,7 +295,7 @@ hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const vo
                              const void* v, float* partial, void* out, hipStream_t st) {
   const int rpb = (s.S + nsplit - 1) / nsplit;
   return launch_attend_mfma_nh<false>(s.G, s.B * s.Hkv, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      partial, out, s.S_cap, kD, s.S, s.Hkv, s.S, s.rg, st);
+                                      partial, out, s.S_cap, kD, s.S, s.Hkv, s.S, s.rg, Paging{}, st);
 }
 
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
@@ -297,7 +304,7 @@ hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, con
   const int rpb = (s.k + nsplit - 1) / nsplit;
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   return launch_attend_mfma_nh<true>(s.G, s.B * s.Hkv, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     partial, out, s.S_cap, s.d, s.k, s.Hkv, s.S, s.rg, st);
+                                     partial, out, s.S_cap, s.d, s.k, s.Hkv, s.S, s.rg, s.pg, st);
 }
 
 }  // namespace loki

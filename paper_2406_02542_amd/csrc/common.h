@@ -27,6 +27,17 @@ __device__ __forceinline__ int cache_unit(const Ragged& rg, int unit, int Hkv) {
   return rg.queries <= 1 ? unit : (unit / Hkv / rg.queries) * Hkv + unit % Hkv;
 }
 
+// Row index, from the start of a slab, of row s of cache unit (sequence cb, KV head h): the
+// contiguous layout, or through the page table (entries clamped, so a bad one cannot leave the
+// pool).
+__device__ __forceinline__ long long cache_row(const Paging& pg, int cb, int h, int Hkv, int S_cap,
+                                               int s) {
+  if (pg.table == nullptr) return ((long long)cb * Hkv + h) * S_cap + s;
+  int page = pg.table[(long long)cb * pg.pages_per_seq + (s >> pg.lg_rows)];
+  page = min(max(page, 0), pg.n_pages - 1);
+  return ((((long long)page * Hkv + h) << pg.lg_rows) | (long long)(s & ((1 << pg.lg_rows) - 1)));
+}
+
 // Debug builds (-DLOKI_PHASE_TIMING) stamp the 100 MHz wall clock at phase boundaries of the
 // fused kernel's blocks so that its time line can be read back; a no-op otherwise.
 #ifdef LOKI_PHASE_TIMING

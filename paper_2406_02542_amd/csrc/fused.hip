@@ -3,6 +3,8 @@
 // enough units to fill the chip: rotate q, score the low-rank slab into LDS, select the top-k
 // in LDS, then attend over the selected rows — no score buffer, index list or partial result
 // ever leaves the CU, and there is no launch boundary between the stages.
+#include <type_traits>
+
 #include "attend_impl.h"
 #include "score_impl.h"
 #include "select_impl.h"
@@ -49,13 +51,30 @@ __device__ __forceinline__ int fused_unit_of_block(const Ragged& rag, int B, int
 // writes it, with the new value, into row S-1 of the unit's cache before it scores.  The block's
 // own later reads of that row go through the same L1 and see it after the barrier; no other
 // block reads this unit's rows.
-template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND>
+// Slab rows of a paged cache: the sequence's page list sits in LDS; a row's page is looked up
+// per lane (rows past the end are clamped to the last row, which may lie in an earlier page).
+struct PagedRows {
+  const char* base;       // this lane's chunk of row 0 of the pool
+  size_t row_bytes;
+  const int32_t* pages;   // LDS: physical page of every logical page of the sequence
+  int lg, Hkv, h;
+  __device__ __forceinline__ long long pool_row(int row) const {
+    return ((((long long)pages[row >> lg] * Hkv + h) << lg) | (long long)(row & ((1 << lg) - 1)));
+  }
+  __device__ __forceinline__ const char* operator()(int row) const {
+    return base + pool_row(row) * (long long)row_bytes;
+  }
+};
+constexpr int kFusedMaxPages = kFusedMaxS / 256;  // pages are at least 256 rows
+
+// PAGED: the three slabs are pools addressed through the sequence's page list (see Paging).
+template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND, bool PAGED>
 __global__ __launch_bounds__(kFusedThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void
 fused_decode_kernel(
     const typename T::store_t* klo, const typename T::store_t* khi, const typename T::store_t* v,
     const typename T::store_t* __restrict__ q, const float* __restrict__ P,
     typename T::store_t* __restrict__ out, int32_t* __restrict__ out_idx, int Hkv, int S_max,
-    int S_cap, int d, int k_max, Ragged rag, Append ap) {
+    int S_cap, int d, int k_max, Ragged rag, Append ap, Paging pg) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;
@@ -75,6 +94,7 @@ fused_decode_kernel(
   static_assert(kFusedWaves == kRotParts, "one wave per part of the rotation");
   __shared__ ResidentSelectSmem<kFusedThreads> s_sel;
   __shared__ MergeSmem<kFusedWaves, 1> s_merge;
+  __shared__ int32_t s_pages[PAGED ? kFusedMaxPages : 1];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // = b * H + h; one query head per KV head here
@@ -96,8 +116,19 @@ fused_decode_kernel(
   const int cs = lane % LPR;
   const bool cact = cs < d / EPC;
   const size_t slab_row_bytes = (size_t)d * T::kBytes;
-  const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * slab_row_bytes +
-                     (size_t)(cact ? cs : 0) * 16;
+  using Rows = std::conditional_t<PAGED, PagedRows, ContiguousRows>;
+  Rows slab;
+  if constexpr (PAGED) {
+    // the sequence's page list, clamped into the pool; readable after the first barrier below
+    if (tid < kFusedMaxPages && tid < pg.pages_per_seq)
+      s_pages[tid] = min(max(pg.table[(size_t)(unit / Hkv) * pg.pages_per_seq + tid], 0), pg.n_pages - 1);
+    slab = PagedRows{reinterpret_cast<const char*>(klo) + (size_t)(cact ? cs : 0) * 16, slab_row_bytes,
+                     s_pages, pg.lg_rows, Hkv, h};
+  } else {
+    slab = ContiguousRows{reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * slab_row_bytes +
+                              (size_t)(cact ? cs : 0) * 16,
+                          slab_row_bytes};
+  }
   constexpr bool kPipelined = LPR <= 8;
   // Issue order = the order the results are needed in (loads return in order): q, then this
   // thread's 16 x 2 entries of P_h, then the first slab loads, which do not need qhat and stay
@@ -120,15 +151,19 @@ fused_decode_kernel(
   }
   ScoreTrip<kPipelined ? LPR : 8> first_trip, second_trip;
   constexpr int kTripRows = kFusedWaves * 64 * ScoreTrip<kPipelined ? LPR : 8>::TPI;
-  if constexpr (kPipelined) {
-    score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
+  if constexpr (kPipelined && !PAGED) {  // (a paged cache needs its page list in LDS first)
+    score_load_trip<LPR, kFusedWaves>(slab, wave * 64, S, first_trip);
     if constexpr (!APPEND)  // the appending variant has no registers to spare during the rotation
-      score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64 + kTripRows, S, second_trip);
+      score_load_trip<LPR, kFusedWaves>(slab, wave * 64 + kTripRows, S, second_trip);
   }
 
   s_q[tid & (kD - 1)] = q_mine;  // four threads store the same value: no branch to sink the load into
   if constexpr (APPEND) s_kn[tid & (kD - 1)] = kn_mine;
   __syncthreads();
+  if constexpr (kPipelined && PAGED && !APPEND) {  // the page list is in LDS now
+    score_load_trip<LPR, kFusedWaves>(slab, wave * 64, S, first_trip);
+    score_load_trip<LPR, kFusedWaves>(slab, wave * 64 + kTripRows, S, second_trip);
+  }
   auto rotate_part = [&](const float* vec, float* part_row) {
     float a0 = 0.f, a1 = 0.f;
 #pragma unroll
@@ -157,7 +192,9 @@ fused_decode_kernel(
   if constexpr (APPEND) {
     // row S-1 of the unit's cache: rotated key (columns < d to the low-rank slab, the rest to
     // the residual slab) by threads 128..255, value by threads 256..383
-    const size_t row = (size_t)unit * S_cap + (size_t)(S - 1);
+    size_t row;
+    if constexpr (PAGED) row = (size_t)slab.pool_row(S - 1);
+    else row = (size_t)unit * S_cap + (size_t)(S - 1);
     if (tid >= kD && tid < 2 * kD) {
       const int j = tid - kD;
       float sum = 0.f;
@@ -172,9 +209,9 @@ fused_decode_kernel(
   __syncthreads();
   if constexpr (APPEND && kPipelined) {
     // the loads put in flight before the rotation may have read row S-1 before it was written
-    if (S - 1 < kTripRows)
-      score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64, S, first_trip);
-    score_load_trip<LPR, kFusedWaves>(slab, slab_row_bytes, wave * 64 + kTripRows, S, second_trip);
+    if (PAGED || S - 1 < kTripRows)
+      score_load_trip<LPR, kFusedWaves>(slab, wave * 64, S, first_trip);
+    score_load_trip<LPR, kFusedWaves>(slab, wave * 64 + kTripRows, S, second_trip);
   }
 
   LOKI_STAMP(1);
@@ -185,10 +222,9 @@ fused_decode_kernel(
     for (int e = 0; e < EPC; ++e) qr[0][e] = cact ? s_qhat[0][cs * EPC + e] : 0.f;
     auto to_lds = [&](int row, const float (&sc)[1]) { s_score[row] = sc[0]; };
     if constexpr (kPipelined)
-      score_rows_pipelined<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, qr, 0, S, first_trip,
-                                                   second_trip, to_lds);
+      score_rows_pipelined<T, LPR, 1, kFusedWaves>(slab, qr, 0, S, first_trip, second_trip, to_lds);
     else
-      score_rows<T, LPR, 1, kFusedWaves>(slab, slab_row_bytes, cact, qr, 0, S, to_lds);
+      score_rows<T, LPR, 1, kFusedWaves>(slab, cact, qr, 0, S, to_lds);
   }
   __syncthreads();
   LOKI_STAMP(2);
@@ -199,7 +235,8 @@ fused_decode_kernel(
     for (int i = k + tid; i < k_max; i += kFusedThreads) gidx[i] = -1;  // a sequence keeping fewer rows
   block_select_topk_resident<kFusedThreads, KPT>(s_score, S, k, per_thread, s_sel,
                                                        [&](int rank, int pos, float score) {
-    s_idx[rank] = pos;
+    if constexpr (PAGED) s_idx[rank] = (int32_t)slab.pool_row(pos);  // the attention stage reads pool rows
+    else s_idx[rank] = pos;
     s_a[rank] = score;
     if (gidx) gidx[rank] = pos;
   });
@@ -211,7 +248,7 @@ fused_decode_kernel(
   float qr[1][EPC];
 #pragma unroll
   for (int e = 0; e < EPC; ++e) qr[0][e] = s_qhat[0][c * EPC + e];
-  const RowAddr ra = make_row_addr<T, REUSE_LO>(klo, khi, v, (size_t)unit, S_cap, d, c);
+  const RowAddr ra = make_row_addr<T, REUSE_LO>(klo, khi, v, PAGED ? (size_t)0 : (size_t)unit, S_cap, d, c);
   AttendAcc<T, 1> acc;
   acc.init();
   attend_rows<T, 1, kFusedWaves * RPW, true, REUSE_LO>(acc, qr, ra, s_idx, s_a, wave * RPW + rg, 0,
@@ -239,6 +276,7 @@ size_t fused_dynamic_lds(const Shape& s) {
 bool fused_eligible(const Shape& s) {
   // several new tokens per sequence: a block would read rows appended by other blocks of the launch
   if (s.rg.queries > 1) return false;
+  if (s.pg.table != nullptr && s.pg.pages_per_seq > kFusedMaxS / 256) return false;  // page list in LDS
   return s.G == 1 && s.S <= kFusedMaxS && s.k <= kFusedMaxK;
 }
 
@@ -249,11 +287,11 @@ bool fused_preferred(const Shape& s) {
   return units >= 192 || s.S <= 2048;
 }
 
-template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND>
+template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND, bool PAGED>
 static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, void* klo, void* khi,
                                  void* v, void* out, int32_t* out_idx, hipStream_t st) {
   using ST = typename T::store_t;
-  auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT, APPEND>;
+  auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT, APPEND, PAGED>;
   const size_t lds = fused_dynamic_lds(s);
   static bool attr_set = false;  // benign race: every caller sets the same value
   if (!attr_set) {
@@ -266,16 +304,20 @@ static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, 
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(kFusedThreads), lds, st,
                      static_cast<const ST*>(klo), static_cast<const ST*>(khi),
                      static_cast<const ST*>(v), static_cast<const ST*>(q), P, static_cast<ST*>(out),
-                     out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k, s.rg, s.ap);
+                     out_idx, s.Hkv, s.S, s.S_cap, s.d, s.k, s.rg, s.ap, s.pg);
   return hipGetLastError();
 }
 
 template <typename T, int LPR, bool REUSE_LO, int KPT>
 static hipError_t launch_fused_a(const Shape& s, const void* q, const float* P, void* klo, void* khi,
                                  void* v, void* out, int32_t* out_idx, hipStream_t st) {
-  if (s.ap.k_new != nullptr)
-    return launch_fused_k<T, LPR, REUSE_LO, KPT, true>(s, q, P, klo, khi, v, out, out_idx, st);
-  return launch_fused_k<T, LPR, REUSE_LO, KPT, false>(s, q, P, klo, khi, v, out, out_idx, st);
+  const bool paged = s.pg.table != nullptr;
+  if (s.ap.k_new != nullptr) {
+    if (paged) return launch_fused_k<T, LPR, REUSE_LO, KPT, true, true>(s, q, P, klo, khi, v, out, out_idx, st);
+    return launch_fused_k<T, LPR, REUSE_LO, KPT, true, false>(s, q, P, klo, khi, v, out, out_idx, st);
+  }
+  if (paged) return launch_fused_k<T, LPR, REUSE_LO, KPT, false, true>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_k<T, LPR, REUSE_LO, KPT, false, false>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <typename T, int LPR, bool REUSE_LO>

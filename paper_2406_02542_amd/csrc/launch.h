@@ -24,6 +24,16 @@ struct Append {
   const void* v_new = nullptr;  // [B, Hkv, 128]
 };
 
+// A paged cache (table null: the contiguous layout [B, Hkv, S_cap, width]).  The three slabs
+// are pools [n_pages, Hkv, page_rows, width]; row s of sequence b lives in physical page
+// table[b * pages_per_seq + s / page_rows] at row s % page_rows, the same page for klo, khi, v.
+struct Paging {
+  const int32_t* table = nullptr;  // device [B, pages_per_seq]
+  int lg_rows = 0;                 // log2(page_rows); page_rows is a power of two >= 256
+  int pages_per_seq = 0;
+  int n_pages = 0;                 // physical pages in the pools: table entries are clamped to it
+};
+
 struct Shape {
   int B, Hq, Hkv, G;  // G = Hq / Hkv
   int S, S_cap;       // S, k: the largest of the batch when `rg` gives per-sequence values
@@ -32,6 +42,7 @@ struct Shape {
   int elem_bytes;   // 4 or 2
   Ragged rg;
   Append ap;
+  Paging pg;
 };
 
 // Grid-shaping decisions; pure functions of the shape so that workspace sizing (host only)

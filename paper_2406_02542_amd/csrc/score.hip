@@ -25,7 +25,8 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
                                                    typename T::store_t* __restrict__ klo,
                                                    typename T::store_t* __restrict__ khi,
                                                    typename T::store_t* __restrict__ v, int S_max,
-                                                   int S_cap, int d, Ragged rg, Append ap) {
+                                                   int S_cap, int d, Ragged rg, Append ap,
+                                                   Paging pg) {
   using ST = typename T::store_t;
   constexpr int NV = G + (APPEND ? 1 : 0);
   __shared__ __align__(16) float s_q[NV][kD];
@@ -45,7 +46,8 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
   size_t row = 0;
   if constexpr (APPEND) {
     if (tid < kD) s_q[G][tid] = T::load1(static_cast<const ST*>(ap.k_new) + (size_t)unit * kD + tid);
-    row = (size_t)cache_unit(rg, unit, Hkv) * S_cap + (size_t)(seq_rows(rg, unit / Hkv, S_max) - 1);
+    row = (size_t)cache_row(pg, unit / Hkv / max(rg.queries, 1), h, Hkv, S_cap,
+                            seq_rows(rg, unit / Hkv, S_max) - 1);
     if (blockIdx.y == 0 && tid >= kD)  // the value row is copied once per unit
       v[row * kD + (tid - kD)] = static_cast<const ST*>(ap.v_new)[(size_t)unit * kD + (tid - kD)];
   }
@@ -83,7 +85,7 @@ template <typename T, int LPR, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_kernel(
     const typename T::store_t* __restrict__ klo, const float* __restrict__ qhat,
     float* __restrict__ scores, int Hkv, int S_max, int S_cap, int d, int rows_per_block,
-    Ragged rg) {
+    Ragged rg, Paging pg) {
   constexpr int EPC = T::EPC;
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
@@ -103,11 +105,14 @@ __global__ __launch_bounds__(256) void score_kernel(
       qr[g][e] = cact ? qhat[(size_t)(head0 + g) * kD + c * EPC + e] : 0.f;
 
   const size_t row_bytes = (size_t)d * T::kBytes;
-  const char* base = reinterpret_cast<const char*>(klo) + (size_t)cache_unit(rg, unit, Hkv) * S_cap * row_bytes +
-                     (size_t)(cact ? c : 0) * 16;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
-  score_rows<T, LPR, G, 4>(base, row_bytes, cact, qr, row0, row_end,
+  // the block's rows are consecutive in memory (a paged cache: the host keeps a block inside a page)
+  const long long row_shift =
+      cache_row(pg, unit / Hkv / max(rg.queries, 1), unit % Hkv, Hkv, S_cap, row0) - row0;
+  const char* base = reinterpret_cast<const char*>(klo) + row_shift * (long long)row_bytes +
+                     (size_t)(cact ? c : 0) * 16;
+  score_rows<T, LPR, G, 4>(ContiguousRows{base, row_bytes}, cact, qr, row0, row_end,
                            [&](int row, const float (&sc)[G]) {
                              if constexpr (GROUP_MAX) {
                                float m = sc[0];
@@ -161,7 +166,7 @@ __device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (
 template <int NCH, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_mfma_kernel(
     const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
-    int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg) {
+    int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg, Paging pg) {
   constexpr int d = 8 * NCH;
   const int S = seq_rows(rg, (int)blockIdx.y / Hkv, S_max);  // the score buffer keeps the stride S_max
   if ((int)blockIdx.x * rows_per_block >= S) return;
@@ -193,10 +198,13 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   // where this lane's chunk of load j sits inside a step
   const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
   const size_t row_bytes = (size_t)d * 2;
-  const char* base = reinterpret_cast<const char*>(klo) + (size_t)cache_unit(rg, unit, Hkv) * S_cap * row_bytes +
-                     (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
+  // the block's rows are consecutive in memory (a paged cache: the host keeps a block inside a page)
+  const long long row_shift =
+      cache_row(pg, unit / Hkv / max(rg.queries, 1), unit % Hkv, Hkv, S_cap, row0) - row0;
+  const char* base = reinterpret_cast<const char*>(klo) + row_shift * (long long)row_bytes +
+                     (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const bool vec_ok = (S_max & 3) == 0;
 
   for (int t0 = row0 + wave * RPS; t0 < row_end; t0 += 4 * RPS * UN) {
@@ -264,10 +272,10 @@ static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const voi
   dim3 grid((s.S + rpb - 1) / rpb, s.B * s.Hkv);
   if (select_mode == 1) {
     hipLaunchKernelGGL((score_mfma_kernel<NCH, G, true>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg);
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
   } else {
     hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg);
+                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
   }
   return hipGetLastError();
 }
@@ -310,10 +318,10 @@ static hipError_t launch_score_g(const Shape& s, int select_mode, const void* q,
   const bool gm = (select_mode == 1) && (G > 1);
   if (gm) {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, (G > 1)>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg);
   } else {
     hipLaunchKernelGGL((score_kernel<T, LPR, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg);
+                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg);
   }
   return hipGetLastError();
 }
@@ -357,7 +365,7 @@ static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, f
 #define LOKI_QROT(GV)                                                                            \
   hipLaunchKernelGGL((qrot_kernel<T, GV, APPEND>), grid, block, 0, st, static_cast<const ST*>(q), P, \
                      qhat, s.Hkv, static_cast<ST*>(klo), static_cast<ST*>(khi), static_cast<ST*>(v), \
-                     s.S, s.S_cap, s.d, s.rg, s.ap);                                             \
+                     s.S, s.S_cap, s.d, s.rg, s.ap, s.pg);                                       \
   break
   switch (s.G) {
     case 1: LOKI_QROT(1);

@@ -13,12 +13,22 @@ namespace loki {
 constexpr int kRotParts = 8;                 // q P is summed as 8 partial sums of 16 terms each,
 constexpr int kRotPartLen = kD / kRotParts;  // in a fixed order, whichever kernel computes it
 
+// Where this lane's 16-byte chunk of slab row `row` lives: rows one after the other from `base`
+// (this lane's chunk of row 0).  A paged cache supplies its own functor of the same shape.
+struct ContiguousRows {
+  const char* base;
+  size_t row_bytes;
+  __device__ __forceinline__ const char* operator()(int row) const {
+    return base + (size_t)row * row_bytes;
+  }
+};
+
 // Scores rows [row0, row_end) of one unit's low-rank slab with the block's WAVES waves.
-// qr is this lane's slice of qhat (zero for lanes past the slab row's last chunk); `base`
-// points at this lane's 16-byte chunk of slab row 0.  emit(row, scores[G]) is called once
+// qr is this lane's slice of qhat (zero for lanes past the slab row's last chunk); `rows`
+// maps a row to this lane's 16-byte chunk of it.  emit(row, scores[G]) is called once
 // per row by the lane that ends up owning it.
-template <typename T, int LPR, int G, int WAVES, typename Emit>
-__device__ __forceinline__ void score_rows(const char* base, size_t row_bytes, bool cact,
+template <typename T, int LPR, int G, int WAVES, typename Rows, typename Emit>
+__device__ __forceinline__ void score_rows(const Rows& rows, bool cact,
                                            const float (&qr)[G][T::EPC], int row0, int row_end,
                                            Emit emit) {
   constexpr int EPC = T::EPC;
@@ -38,8 +48,7 @@ __device__ __forceinline__ void score_rows(const char* base, size_t row_bytes, b
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
           const int row = tile0 + tt * WAVES * 64 + (it0 + u) * RPI + rsub;
-          raw[tt][u] = (cact && row < row_end) ? load16(base + (size_t)row * row_bytes)
-                                               : make_uint4(0, 0, 0, 0);
+          raw[tt][u] = (cact && row < row_end) ? load16(rows(row)) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
       for (int tt = 0; tt < TPI; ++tt)
@@ -78,9 +87,9 @@ struct ScoreTrip {
   uint4 raw[TPI][LPR];
 };
 
-template <int LPR, int WAVES>
-__device__ __forceinline__ void score_load_trip(const char* base, size_t row_bytes, int tile0,
-                                                int row_end, ScoreTrip<LPR>& t) {
+template <int LPR, int WAVES, typename Rows>
+__device__ __forceinline__ void score_load_trip(const Rows& rows, int tile0, int row_end,
+                                                ScoreTrip<LPR>& t) {
   constexpr int RPI = 64 / LPR;
   const int rsub = (threadIdx.x & 63) / LPR;
 #pragma unroll
@@ -88,7 +97,7 @@ __device__ __forceinline__ void score_load_trip(const char* base, size_t row_byt
 #pragma unroll
     for (int u = 0; u < LPR; ++u) {
       const int row = min(tile0 + tt * WAVES * 64 + u * RPI + rsub, row_end - 1);
-      t.raw[tt][u] = load16(base + (size_t)row * row_bytes);
+      t.raw[tt][u] = load16(rows(row));
     }
 }
 
@@ -129,8 +138,8 @@ __device__ __forceinline__ void score_trip(const ScoreTrip<LPR>& cur, const floa
 // turns (the loop body handles two trips), so two trips' loads stay in flight while a trip is
 // scored and no buffer is ever copied; the loads past the last trip are clamped re-reads of
 // the last row.
-template <typename T, int LPR, int G, int WAVES, typename Emit>
-__device__ __forceinline__ void score_rows_pipelined(const char* base, size_t row_bytes,
+template <typename T, int LPR, int G, int WAVES, typename Rows, typename Emit>
+__device__ __forceinline__ void score_rows_pipelined(const Rows& rows,
                                                      const float (&qr)[G][T::EPC], int row0,
                                                      int row_end, ScoreTrip<LPR>& t0,
                                                      ScoreTrip<LPR>& t1, Emit emit) {
@@ -138,9 +147,9 @@ __device__ __forceinline__ void score_rows_pipelined(const char* base, size_t ro
   const int wave = threadIdx.x >> 6;
   for (int tile0 = row0 + wave * 64; tile0 < row_end; tile0 += 2 * kStride) {
     score_trip<T, LPR, G, WAVES>(t0, qr, tile0, row_end, emit);
-    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 2 * kStride, row_end, t0);
+    score_load_trip<LPR, WAVES>(rows, tile0 + 2 * kStride, row_end, t0);
     score_trip<T, LPR, G, WAVES>(t1, qr, tile0 + kStride, row_end, emit);
-    score_load_trip<LPR, WAVES>(base, row_bytes, tile0 + 3 * kStride, row_end, t1);
+    score_load_trip<LPR, WAVES>(rows, tile0 + 3 * kStride, row_end, t1);
   }
 }
 

@@ -40,8 +40,9 @@ def test_layout_struct_matches_header():
 
 
 def test_step_args_struct_matches_header():
-    assert [f[0] for f in api.StepArgs._fields_] == ["seq_lens", "ks", "k_new", "v_new", "queries_per_seq"]
-    assert ctypes.sizeof(api.StepArgs) == 4 * 8 + 8  # four pointers, one int32, padding
+    assert [f[0] for f in api.StepArgs._fields_] == ["seq_lens", "ks", "k_new", "v_new", "queries_per_seq",
+                                                     "page_rows", "page_table", "pages_per_seq", "n_pages"]
+    assert ctypes.sizeof(api.StepArgs) == 4 * 8 + 2 * 4 + 8 + 2 * 4
 
 
 def test_cache_and_workspace_sizes():

@@ -394,3 +394,95 @@ def test_step_with_several_new_tokens_per_sequence(G, dtype, mode):
                 max_err = max(max_err, err)
                 assert err <= tol, f"entry {e} hq {hq}: {err:.3e}"
     say(f"   max_err {max_err:.3e}")
+
+
+# -------------------------------------------------------------------------- paged cache --
+@pytest.mark.parametrize("G,dtype,mode,page_rows,m,path", [
+    (1, "bf16", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 1024, 1, api.PATH_SPLIT),
+    (4, "bf16", 1, 256, 1, api.PATH_SPLIT), (8, "bf16", 1, 512, 1, api.PATH_SPLIT),
+    (2, "f32", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 256, 2, api.PATH_SPLIT),
+    (1, "bf16", 0, 256, 1, api.PATH_FUSED), (1, "bf16", 0, 2048, 1, api.PATH_FUSED),
+    (1, "f32", 0, 512, 1, api.PATH_FUSED)])
+def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path):
+    """The same rows scattered over randomly ordered physical pages (with unused pages in
+    between) give bit-identical outputs, index lists and appended rows, on either kernel
+    sequence: the page table changes where a row lives, not what is computed.  The contiguous
+    reference is itself checked against the oracle by the tests above."""
+    B = 3
+    w = synth.Workload(f"paged_g{G}", B, 2 * G, 2, 128, 3000, dtype, 32, 500, seed=15000 + G)
+    x = synth.make_inputs(w)
+    wq = w.replace(B=B * m)
+    st = synth.make_step_inputs(wq, x["P"])
+    q = to_dev(synth.make_inputs(wq.replace(S=8))["q"], dtype)
+    rows = np.array([3000, 800, 1537])
+    lens = np.array([rows[b] - (m - 1 - j) for b in range(B) for j in range(m)], np.int32)
+    ks = np.maximum(1, (w.k * lens.astype(np.int64)) // w.S).astype(np.int32)
+    tdt = TORCH_DT[dtype]
+    pages_per_seq = (w.S + page_rows - 1) // page_rows
+    S_cap = pages_per_seq * page_rows
+    lay = api.make_layout(B, w.Hq, w.Hkv, 128, w.d, S_cap, tdt)
+    klo, khi, v = api.alloc_cache(lay)
+    klo.fill_(3e4); khi.fill_(3e4); v.fill_(-3e4)
+    kh, vv = to_dev(x["khat"], dtype), to_dev(x["v"], dtype)
+    for b in range(B):
+        n = int(rows[b]) - m
+        klo[b, :, :n] = kh[b, :, :n, :w.d]; khi[b, :, :n] = kh[b, :, :n, w.d:]; v[b, :, :n] = vv[b, :, :n]
+    # pools: every logical page gets a random physical page; a third of the pool stays unused
+    n_pages = B * pages_per_seq * 3 // 2 + 1
+    perm = np.random.default_rng(5).permutation(n_pages)[:B * pages_per_seq].astype(np.int32)
+    table = torch.from_numpy(perm.reshape(B, pages_per_seq)).cuda()
+
+    def to_pool(c):  # [B, Hkv, S_cap, W] -> [n_pages, Hkv, page_rows, W]
+        pool = torch.full((n_pages, w.Hkv, page_rows, c.shape[-1]), 7.0, dtype=tdt, device="cuda")
+        pool[table.view(-1).long()] = c.view(B, w.Hkv, pages_per_seq, page_rows, -1).permute(0, 2, 1, 3, 4).reshape(
+            B * pages_per_seq, w.Hkv, page_rows, -1)
+        return pool
+
+    def from_pool(pool):
+        return pool[table.view(-1).long()].view(B, pages_per_seq, w.Hkv, page_rows, -1).permute(0, 2, 1, 3, 4).reshape(
+            B, w.Hkv, S_cap, -1)
+
+    pklo, pkhi, pv = to_pool(klo), to_pool(khi), to_pool(v)
+    lay_ws = api.make_layout(B * m, w.Hq, w.Hkv, 128, w.d, S_cap, tdt)
+    ws = api.alloc_workspace(lay_ws, w.S, w.d, w.k, mode)
+    hsel = w.Hq if mode == 0 or G == 1 else w.Hkv
+    P = torch.from_numpy(x["P"]).cuda()
+    common = dict(seq_lens=torch.from_numpy(lens).cuda(), ks=torch.from_numpy(ks).cuda(),
+                  k_new=to_dev(st["k_new"], dtype), v_new=to_dev(st["v_new"], dtype), queries_per_seq=m)
+    out_c = torch.full((B * m, w.Hq, 128), float("nan"), dtype=tdt, device="cuda")
+    idx_c = torch.full((B * m, hsel, w.k), -7, dtype=torch.int32, device="cuda")
+    api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path, ws, out_c, idx_c, **common)
+    out_p = torch.full_like(out_c, float("nan"))
+    idx_p = torch.full_like(idx_c, -7)
+    api.loki_decode_step(lay, q, P, pklo, pkhi, pv, w.S, w.d, w.k, mode | path, ws, out_p, idx_p,
+                         page_table=table, page_rows=page_rows, n_pages=n_pages, **common)
+    torch.cuda.synchronize()
+    say(f"paged G {G} {dtype} mode {mode} page_rows {page_rows} m {m}: n_pages {n_pages}")
+    assert torch.isfinite(out_c.float()).all()
+    assert torch.equal(out_p, out_c)
+    assert torch.equal(idx_p, idx_c)
+    assert torch.equal(from_pool(pklo), klo) and torch.equal(from_pool(pkhi), khi) and torch.equal(from_pool(pv), v)
+    unused = np.setdiff1d(np.arange(n_pages), perm)
+    assert torch.all(pklo[torch.from_numpy(unused).cuda().long()] == 7.0)
+
+
+def test_paged_cache_rejects_bad_geometry():
+    lay = api.make_layout(1, 2, 2, 128, 32, 1024, torch.bfloat16)
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    pool_lo, pool_hi, pool_v = z(4, 2, 256, 32), z(4, 2, 256, 96), z(4, 2, 256, 128)
+    q, out, P = z(1, 2, 128), z(1, 2, 128), torch.zeros((2, 128, 128), device="cuda")
+    ws = api.alloc_workspace(lay, 1024, 32, 64, 0)
+    table = torch.zeros((1, 4), dtype=torch.int32, device="cuda")
+    for kw, status in ((dict(page_rows=200, n_pages=4), 1),      # not a power of two
+                       (dict(page_rows=128, n_pages=4), 1),      # below the scoring block granularity
+                       (dict(page_rows=256, n_pages=0), 1)):
+        with pytest.raises((api.LokiError, ValueError)) as e:
+            api.loki_decode_step(lay, q, P, pool_lo, pool_hi, pool_v, 1024, 32, 64, 0, ws, out,
+                                 page_table=table, **kw)
+        if isinstance(e.value, api.LokiError):
+            assert e.value.status == status
+    short = torch.zeros((1, 3), dtype=torch.int32, device="cuda")  # 3 pages x 256 rows < S
+    with pytest.raises(api.LokiError) as e:
+        api.loki_decode_step(lay, q, P, pool_lo, pool_hi, pool_v, 1024, 32, 64, 0, ws, out,
+                             page_table=short, page_rows=256, n_pages=4)
+    assert e.value.status == 1

@@ -115,6 +115,17 @@ int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* 
                      void* khi, int pos, int n_new, void* stream);
 
 /*
+ * loki_rotate_keys into a paged cache (see loki_decode_step for the page table's meaning):
+ * klo and khi are the pools [n_pages, Hkv, page_rows, d | D - d]; rows pos .. pos + n_new - 1
+ * of every sequence go to the pages page_table[b, row / page_rows] names;
+ * pages_per_seq * page_rows >= pos + n_new, which also has to fit layout->S_cap.  V is not
+ * transformed and is written by the caller.
+ */
+int loki_rotate_keys_paged(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                           void* khi, const int32_t* page_table, int page_rows, int pages_per_seq,
+                           int n_pages, int pos, int n_new, void* stream);
+
+/*
  * Algorithm 1 lines 3 and 5-9 for every (b, query head): the decode step.
  *   q    [B, Hq, D]   queries in the model's basis (storage type)
  *   P    [Hkv, D, D]  fp32

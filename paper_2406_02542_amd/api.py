@@ -60,6 +60,8 @@ def lib() -> ctypes.CDLL:
     L.loki_workspace_bytes.argtypes = [LP, i32, i32, i32, i32, ctypes.POINTER(sz)]
     L.loki_rotate_keys.restype = i32
     L.loki_rotate_keys.argtypes = [LP, vp, vp, vp, vp, i32, i32, vp]
+    L.loki_rotate_keys_paged.restype = i32
+    L.loki_rotate_keys_paged.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     L.loki_decode_attn.restype = i32
     L.loki_decode_attn.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
     L.loki_decode_step.restype = i32
@@ -183,6 +185,23 @@ def loki_rotate_keys(layout: Layout, k_new: torch.Tensor, P: torch.Tensor, klo: 
         _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
         _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
         pos, n_new, _stream_ptr(stream)), "loki_rotate_keys")
+
+
+def loki_rotate_keys_paged(layout: Layout, k_new: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                           khi: Optional[torch.Tensor], page_table: torch.Tensor, page_rows: int,
+                           n_pages: int, pos: int, n_new: int, stream=None) -> None:
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    pool_rows = n_pages * layout.Hkv * page_rows
+    _check(lib().loki_rotate_keys_paged(
+        ctypes.byref(layout),
+        _ptr(k_new, "k_new", dt, rows * n_new * layout.D),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, pool_rows * layout.d_split),
+        _ptr(khi, "khi", dt, pool_rows * (layout.D - layout.d_split)),
+        _ptr(page_table, "page_table", torch.int32, layout.B),
+        page_rows, page_table.numel() // layout.B, n_pages, pos, n_new,
+        _stream_ptr(stream)), "loki_rotate_keys_paged")
 
 
 def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,

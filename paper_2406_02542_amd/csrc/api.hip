@@ -218,8 +218,24 @@ int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int sel
   return LOKI_OK;
 }
 
-int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* P, void* klo,
-                     void* khi, int pos, int n_new, void* stream) {
+static int paging_from_args(const int32_t* page_table, int page_rows, int pages_per_seq, int n_pages,
+                            int Hkv, long long rows_needed, Paging* pg) {
+  int lg = 0;
+  while (lg < 31 && (1 << lg) < page_rows) ++lg;
+  if (page_rows < 1 || (1 << lg) != page_rows) return LOKI_ERR_INVALID_ARG;
+  if (lg < 8 || lg > 24 || pages_per_seq < 1 || n_pages < 1) return LOKI_ERR_INVALID_ARG;
+  if ((long long)pages_per_seq * page_rows < rows_needed) return LOKI_ERR_INVALID_ARG;
+  if ((long long)n_pages * Hkv * page_rows > 0x7fffffffLL) return LOKI_ERR_UNSUPPORTED;
+  if (reinterpret_cast<uintptr_t>(page_table) & 3u) return LOKI_ERR_ALIGNMENT;
+  pg->table = page_table;
+  pg->lg_rows = lg;
+  pg->pages_per_seq = pages_per_seq;
+  pg->n_pages = n_pages;
+  return LOKI_OK;
+}
+
+static int rotate_impl(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                       void* khi, int pos, int n_new, const Paging* pg, void* stream) {
   Shape s;
   const int rc = check_layout(layout, &s);
   if (rc != LOKI_OK) return rc;
@@ -228,12 +244,30 @@ int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* 
   if (pos < 0 || n_new < 1 || (long long)pos + n_new > s.S_cap) return LOKI_ERR_INVALID_ARG;
   if (!aligned16(k_new) || !aligned16(P) || !aligned16(klo) || !aligned16(khi))
     return LOKI_ERR_ALIGNMENT;
+  if (pg) s.pg = *pg;
   hipStream_t st = static_cast<hipStream_t>(stream);
   StageTimer tm(st);
   tm.begin("rotate_keys");
   const hipError_t e = launch_rotate(s, k_new, P, klo, khi, pos, n_new, st);
   tm.end();
   return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+}
+
+int loki_rotate_keys(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                     void* khi, int pos, int n_new, void* stream) {
+  return rotate_impl(layout, k_new, P, klo, khi, pos, n_new, nullptr, stream);
+}
+
+int loki_rotate_keys_paged(const loki_layout* layout, const void* k_new, const float* P, void* klo,
+                           void* khi, const int32_t* page_table, int page_rows, int pages_per_seq,
+                           int n_pages, int pos, int n_new, void* stream) {
+  if (!layout || !page_table) return LOKI_ERR_INVALID_ARG;
+  if (pos < 0 || n_new < 1) return LOKI_ERR_INVALID_ARG;
+  Paging pg;
+  const int rc = paging_from_args(page_table, page_rows, pages_per_seq, n_pages, layout->Hkv,
+                                  (long long)pos + n_new, &pg);
+  if (rc != LOKI_OK) return rc;
+  return rotate_impl(layout, k_new, P, klo, khi, pos, n_new, &pg, stream);
 }
 
 // The decode step behind loki_decode_attn (no per-sequence sizes, no append) and
@@ -270,14 +304,6 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   if ((reinterpret_cast<uintptr_t>(rg.seq_lens) & 3u) || (reinterpret_cast<uintptr_t>(rg.ks) & 3u))
     return LOKI_ERR_ALIGNMENT;
   if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
-  if (pg.table != nullptr) {
-    const int page_rows = 1 << pg.lg_rows;
-    if (pg.lg_rows < 8 || pg.lg_rows > 24 || pg.pages_per_seq < 1 || pg.n_pages < 1)
-      return LOKI_ERR_INVALID_ARG;
-    if ((long long)pg.pages_per_seq * page_rows < S) return LOKI_ERR_INVALID_ARG;
-    if ((long long)pg.n_pages * s.Hkv * page_rows > 0x7fffffffLL) return LOKI_ERR_UNSUPPORTED;
-    if (reinterpret_cast<uintptr_t>(pg.table) & 3u) return LOKI_ERR_ALIGNMENT;
-  }
   s.S = S;
   s.k = k;
   s.rg = rg;
@@ -343,13 +369,10 @@ int loki_decode_step(const loki_layout* layout, const void* q, const float* P, v
   Append ap;
   Paging pg;
   if (args && args->page_table) {
-    int lg = 0;
-    while (lg < 31 && (1 << lg) < args->page_rows) ++lg;
-    if (args->page_rows < 1 || (1 << lg) != args->page_rows) return LOKI_ERR_INVALID_ARG;
-    pg.table = args->page_table;
-    pg.lg_rows = lg;
-    pg.pages_per_seq = args->pages_per_seq;
-    pg.n_pages = args->n_pages;
+    if (!layout) return LOKI_ERR_INVALID_ARG;
+    const int rc = paging_from_args(args->page_table, args->page_rows, args->pages_per_seq,
+                                    args->n_pages, layout->Hkv, S_max, &pg);
+    if (rc != LOKI_OK) return rc;
   }
   if (args) {
     rg.seq_lens = args->seq_lens;

@@ -19,7 +19,7 @@ template <typename T>
 __global__ __launch_bounds__(kRotThreads) void rotate_kernel(
     const typename T::store_t* __restrict__ k_new, const float* __restrict__ P,
     typename T::store_t* __restrict__ klo, typename T::store_t* __restrict__ khi, int Hkv,
-    int S_cap, int d, int pos, int n_new, int n_items, int items_per_block) {
+    int S_cap, int d, int pos, int n_new, int n_items, int items_per_block, Paging pg) {
   using ST = typename T::store_t;
   __shared__ float s_P[kD * kD];        // [128][128]
   __shared__ float s_K[kRotTile * kD];  // [kRotTile][128]
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kRotThreads) void rotate_kernel(
       const int it = t0 + rbase + r;
       if (it < item1) {
         const int b = it / n_new, rr = it % n_new;
-        const size_t row = (size_t)(b * Hkv + h) * S_cap + pos + rr;
+        const size_t row = (size_t)cache_row(pg, b, h, Hkv, S_cap, pos + rr);
         if (j < d)
           T::store1(klo + row * d + j, acc[r]);
         else
@@ -95,10 +95,13 @@ constexpr int kRotMfmaWaves = kRotMfmaThreads / 64;
 constexpr int kRotMfmaItems = 2048;  // rows per block: 16 tiles per wave
 constexpr int kRotMfmaTPW = 2;        // tiles a wave multiplies per operand fetch
 
+// PAGED: the output rows go through the page table (a separate instantiation, so that the
+// contiguous kernel's store addresses stay plain arithmetic).
+template <bool PAGED>
 __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
     const uint16_t* __restrict__ k_new, const float* __restrict__ P, uint16_t* __restrict__ klo,
     uint16_t* __restrict__ khi, int Hkv, int S_cap, int d, int pos, int n_new, int n_items,
-    int items_per_block) {
+    int items_per_block, Paging pg) {
   __shared__ uint4 s_B[3][4][8][64];  // [term][32-column step of K][16-column block of Khat][lane]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: row bases stay scalar
@@ -172,7 +175,8 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
         const int itb = min(t0, item1 - 1);
         int b, r;
         split_item(itb, min(it, item1 - 1) - itb, b, r);
-        row[u][ii] = (size_t)(b * Hkv + h) * S_cap + pos + r;
+        if constexpr (PAGED) row[u][ii] = (size_t)cache_row(pg, b, h, Hkv, S_cap, pos + r);
+        else row[u][ii] = (size_t)(b * Hkv + h) * S_cap + pos + r;
       }
     // The operands in LDS never change, but they must be re-read for every trip: hoisted out of
     // the loop, all 96 of them would live in registers and spill.  An offset the compiler
@@ -250,6 +254,7 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
 
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,
                          int pos, int n_new, hipStream_t st) {
+  const bool paged = s.pg.table != nullptr;
   const long long n_items_ll = (long long)s.B * n_new;
   if (n_items_ll > 0x7fffffffLL) return hipErrorInvalidValue;
   const int n_items = (int)n_items_ll;
@@ -261,19 +266,26 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
     int ipb_m = kRotMfmaItems;
     if (n_items < ipb_m) ipb_m = ((n_items + 15) / 16) * 16;
     dim3 grid_m((n_items + ipb_m - 1) / ipb_m, s.Hkv);
-    hipLaunchKernelGGL(rotate_mfma_kernel, grid_m, dim3(kRotMfmaThreads), 0, st,
-                       static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
-                       static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb_m);
+    if (paged)
+      hipLaunchKernelGGL(rotate_mfma_kernel<true>, grid_m, dim3(kRotMfmaThreads), 0, st,
+                         static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
+                         static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb_m,
+                         s.pg);
+    else
+      hipLaunchKernelGGL(rotate_mfma_kernel<false>, grid_m, dim3(kRotMfmaThreads), 0, st,
+                         static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
+                         static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb_m,
+                         s.pg);
     return hipGetLastError();
   }
   if (s.dtype == 0) {
     hipLaunchKernelGGL(rotate_kernel<F32>, grid, dim3(kRotThreads), lds, st,
                        static_cast<const float*>(k_new), P, static_cast<float*>(klo),
-                       static_cast<float*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb);
+                       static_cast<float*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb, s.pg);
   } else {
     hipLaunchKernelGGL(rotate_kernel<BF16>, grid, dim3(kRotThreads), lds, st,
                        static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
-                       static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb);
+                       static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb, s.pg);
   }
   return hipGetLastError();
 }

@@ -486,3 +486,38 @@ def test_paged_cache_rejects_bad_geometry():
         api.loki_decode_step(lay, q, P, pool_lo, pool_hi, pool_v, 1024, 32, 64, 0, ws, out,
                              page_table=short, page_rows=256, n_pages=4)
     assert e.value.status == 1
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_paged_key_rotation_equals_contiguous(dtype):
+    """loki_rotate_keys_paged writes bit for bit what loki_rotate_keys writes, at the rows the
+    page table names; pages it does not name stay untouched."""
+    B, Hkv, page_rows, pps = 3, 2, 256, 5
+    S_cap = pps * page_rows
+    w = synth.Workload("paged_rot", B, Hkv, Hkv, 128, 1100, dtype, 32, 8, seed=16000)
+    P = synth.make_P(w)
+    K = synth.make_unrotated_keys(w, P)
+    tdt = TORCH_DT[dtype]
+    lay = api.make_layout(B, Hkv, Hkv, 128, 32, S_cap, tdt)
+    klo, khi, _ = api.alloc_cache(lay)
+    klo.fill_(5.0); khi.fill_(5.0)
+    n_pages = B * pps + 4
+    perm = np.random.default_rng(6).permutation(n_pages)[:B * pps].astype(np.int32)
+    table = torch.from_numpy(perm.reshape(B, pps)).cuda()
+    pklo = torch.full((n_pages, Hkv, page_rows, 32), 5.0, dtype=tdt, device="cuda")
+    pkhi = torch.full((n_pages, Hkv, page_rows, 96), 5.0, dtype=tdt, device="cuda")
+    Pd = torch.from_numpy(P).cuda()
+    for lo, n_new in ((0, 1000), (1000, 1), (1001, 99)):  # prefill at position 7, then appends
+        chunk = to_dev(K[:, :, lo:lo + n_new], dtype)
+        api.loki_rotate_keys(lay, chunk, Pd, klo, khi, 7 + lo, n_new)
+        api.loki_rotate_keys_paged(lay, chunk, Pd, pklo, pkhi, table, page_rows, n_pages, 7 + lo, n_new)
+    torch.cuda.synchronize()
+
+    def from_pool(pool):
+        return pool[table.view(-1).long()].view(B, pps, Hkv, page_rows, -1).permute(0, 2, 1, 3, 4).reshape(
+            B, Hkv, S_cap, -1)
+
+    assert torch.equal(from_pool(pklo), klo) and torch.equal(from_pool(pkhi), khi)
+    assert not torch.all(klo == 5.0)
+    unused = torch.from_numpy(np.setdiff1d(np.arange(n_pages), perm)).cuda().long()
+    assert torch.all(pklo[unused] == 5.0) and torch.all(pkhi[unused] == 5.0)

@@ -263,8 +263,7 @@ def make_step_inputs(w: Workload, P: np.ndarray, ragged: bool = True, min_frac: 
         lens[0] = w.S
         if w.B > 1:
             lens[1] = lo
-    kf = w.k / w.S
-    ks = np.maximum(1, np.floor(kf * lens.astype(np.float64))).astype(np.int32)
+    ks = np.maximum(1, (w.k * lens.astype(np.int64)) // w.S)  # floor(k_f * seq_len) in integers
     ks = np.minimum(ks, np.minimum(lens, w.k)).astype(np.int32)
     scale = np.sqrt(spectrum(w.D, w.tau) ** 2 + w.noise_var)
     c = _rng(w.seed, _T_KNEW).standard_normal((w.B, w.Hkv, w.D)) * scale[None, None, :]

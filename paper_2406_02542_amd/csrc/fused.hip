@@ -283,8 +283,10 @@ bool fused_eligible(const Shape& s) {
 bool fused_preferred(const Shape& s) {
   if (!fused_eligible(s)) return false;
   const int units = s.B * s.Hkv;
-  // enough blocks to occupy most CUs, or so little work per unit that launch count dominates
-  return units >= 192 || s.S <= 2048;
+  // measured on the Llama-2-shaped layer (S = 4096 and 8192): equal at 32 units, the single
+  // launch ahead from 64 units on (25 vs 27 us) and by a third at 128 and more; below that only
+  // when there is so little work per unit that the launch count dominates
+  return units >= 48 || s.S <= 2048;
 }
 
 template <typename T, int LPR, bool REUSE_LO, int KPT, bool APPEND, bool PAGED>

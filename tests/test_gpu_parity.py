@@ -135,6 +135,15 @@ def test_long_sequences(S, k, G):
         say(f"mode {mode} {check_loki(case, mode)}")
 
 
+@pytest.mark.parametrize("S", [1100000, 1100001])
+def test_sequence_beyond_the_chunked_select(S):
+    """More than 64 chunks of 16384 rows: one block per head streams the scores four times
+    (select_stream_kernel), with and without 16-byte-aligned score rows."""
+    w, x = _case(f"huge_{S}", 1, 1, 1, S, "bf16", 16, 5000, seed=3900 + S % 7)
+    say(f"case {w}")
+    say(f"{check_loki(DeviceCase(w, x), 0)}")
+
+
 def test_long_sequence_with_massive_ties():
     """S = 40000 with an all-zero cache and with only 7 distinct key rows: the threshold bin
     overflows every candidate buffer, the plain digit passes must take over."""

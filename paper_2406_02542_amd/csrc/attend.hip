@@ -241,6 +241,7 @@ static hipError_t launch_pca_t(const Shape& s, int nsplit, int rpb, const float*
 
 hipError_t launch_pca_attend(const Shape& s, int nsplit, const float* qhat, const void* klo,
                              const void* v, float* partial, void* out, hipStream_t st) {
+  if (attend_mfma_applies(s, s.G)) return launch_pca_mfma(s, nsplit, qhat, klo, v, partial, out, st);
   const int rpb = div_up(s.S, nsplit);
   return s.dtype == 0 ? launch_pca_t<F32>(s, nsplit, rpb, qhat, klo, v, partial, out, st)
                       : launch_pca_t<BF16>(s, nsplit, rpb, qhat, klo, v, partial, out, st);

@@ -34,7 +34,11 @@ constexpr int kAmRows = 32;        // rows per wave step
 constexpr int kAmPitch = 264;      // bytes per V row in LDS: 256 + 8 keeps column reads conflict-free
 
 // QT = number of bf16 terms q enters with (1: q is bf16; 2: q is fp32)
-template <int NH, bool GATHER>
+// KSTEPS / LO_ONLY (with GATHER = false): the logits use only the first d columns, held by k_a
+// with row pitch d (Appendix E, Algorithm 2): KSTEPS = ceil(d / 32) of the four 32-column
+// steps of the first product are issued, and columns past d (a partial last step) meet a zero
+// in the B operand, so whatever valid chunk their lanes load does not count.
+template <int NH, bool GATHER, int KSTEPS = 4, bool LO_ONLY = false>
 __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void attend_mfma_kernel(
     const void* __restrict__ k_a,   // GATHER: klo [units, S_cap, d]; dense: K [units, S_cap, 128]
     const void* __restrict__ k_b,   // GATHER: khi [units, S_cap, 128-d]; dense: unused
@@ -45,7 +49,8 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     uint16_t* __restrict__ out,     // [B*Hq, 128] bf16 when nsplit == 1
     int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg,
     Paging pg) {
-  constexpr int QT = GATHER ? 2 : 1;
+  constexpr bool kRotated = GATHER || LO_ONLY;  // the query is the fp32 rotated one
+  constexpr int QT = kRotated ? 2 : 1;
   __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmRows * kAmPitch];  // 8448 B per wave
   __shared__ int32_t s_idx[GATHER ? kMaxGatherChunk : 1];
   __shared__ MergeSmem<kAmWaves, NH> s_merge;
@@ -79,16 +84,17 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
   const size_t addr_unit = paged ? (size_t)0 : (size_t)cache_unit(rg, kv_unit, Hkv);
 
   // B operand of the first product: q of head r16, columns 32*step + 8*kgrp .. +7
-  am_bf16x8_t bq[4][QT];
+  am_bf16x8_t bq[KSTEPS][QT];
 #pragma unroll
-  for (int step = 0; step < 4; ++step) {
+  for (int step = 0; step < KSTEPS; ++step) {
     const int col = 32 * step + 8 * kgrp;
-    if constexpr (GATHER) {
+    if constexpr (kRotated) {
+      const bool col_ok = head_ok && (!LO_ONLY || col < d);
       const float* qh = static_cast<const float*>(qv) + (head0 + (head_ok ? r16 : 0)) * kD + col;
       uint32_t w[QT][4];
 #pragma unroll
       for (int e2 = 0; e2 < 4; ++e2) {
-        float rest0 = head_ok ? qh[2 * e2] : 0.f, rest1 = head_ok ? qh[2 * e2 + 1] : 0.f;
+        float rest0 = col_ok ? qh[2 * e2] : 0.f, rest1 = col_ok ? qh[2 * e2 + 1] : 0.f;
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
           const uint32_t pk = BF16::round2(rest0, rest1);
@@ -109,16 +115,16 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
   }
 
   // where this lane's 16-byte chunks of a K row live: chunk 4*step + kgrp of the logical row
-  const int nlo = (GATHER ? d : kD) / 8;  // chunks held by k_a
-  const char* kptr[4];
-  size_t kpitch[4];
+  const int nlo = (kRotated ? d : kD) / 8;  // chunks held by k_a
+  const char* kptr[KSTEPS];
+  size_t kpitch[KSTEPS];
 #pragma unroll
-  for (int step = 0; step < 4; ++step) {
+  for (int step = 0; step < KSTEPS; ++step) {
     const int c = 4 * step + kgrp;
     const bool in_lo = c < nlo;
-    kpitch[step] = in_lo ? (size_t)(GATHER ? d : kD) * 2 : (size_t)(kD - d) * 2;
-    const char* base = in_lo ? static_cast<const char*>(k_a) + (size_t)c * 16
-                             : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
+    kpitch[step] = (in_lo || LO_ONLY) ? (size_t)(kRotated ? d : kD) * 2 : (size_t)(kD - d) * 2;
+    const char* base = (in_lo || LO_ONLY) ? static_cast<const char*>(k_a) + (size_t)(in_lo ? c : 0) * 16
+                                          : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
     kptr[step] = base + addr_unit * S_cap * kpitch[step];
   }
   const char* vptr = static_cast<const char*>(v) + addr_unit * S_cap * (kD * 2) + (size_t)kgrp * 16;
@@ -131,14 +137,14 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
 
   for (int base = r0 + wave * kAmRows; base < r1; base += kAmWaves * kAmRows) {
     // ---- loads: two 16-row tiles of K (A operands) and of V (to LDS) -------------------------
-    uint4 kraw[2][4], vraw[2][4];
+    uint4 kraw[2][KSTEPS], vraw[2][4];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int r = min(base + 16 * t + r16, r1 - 1);  // rows past the end re-read the last one
       const int row = GATHER ? s_idx[r - r0] : r;
 #pragma unroll
       for (int step = 0; step < 4; ++step) {
-        kraw[t][step] = load16(kptr[step] + (size_t)row * kpitch[step]);
+        if (step < KSTEPS) kraw[t][step] = load16(kptr[step] + (size_t)row * kpitch[step]);
         vraw[t][step] = load16(vptr + (size_t)row * (kD * 2) + step * 64);
       }
     }
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
 #pragma unroll
       for (int qt = QT - 1; qt >= 0; --qt)
 #pragma unroll
-        for (int step = 0; step < 4; ++step)
+        for (int step = 0; step < KSTEPS; ++step)
           s_acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
               __builtin_bit_cast(am_bf16x8_t, kraw[t][step]), bq[step][qt], s_acc[t], 0, 0, 0);
     }
@@ -285,6 +291,36 @@ static hipError_t launch_attend_mfma_nh(int NH, int blocks_y, int nsplit, int rp
       return hipErrorInvalidValue;
   }
   return hipGetLastError();
+}
+
+template <int NH>
+static hipError_t launch_pca_mfma_nh(const Shape& s, int nsplit, int rpb, const float* qhat,
+                                     const void* klo, const void* v, float* partial, void* out,
+                                     hipStream_t st) {
+  const dim3 grid(nsplit, s.B * s.Hkv), block(kAmThreads);
+  uint16_t* o16 = static_cast<uint16_t*>(out);
+#define LOKI_PCA_MFMA(KS)                                                                          \
+  hipLaunchKernelGGL((attend_mfma_kernel<NH, false, KS, true>), grid, block, 0, st, klo, nullptr, v, \
+                     qhat, nullptr, partial, o16, s.S_cap, s.d, s.S, rpb, nsplit, s.Hkv, s.S, s.rg,  \
+                     Paging{});                                                                    \
+  break
+  switch ((s.d + 31) / 32) {
+    case 1: LOKI_PCA_MFMA(1);
+    case 2: LOKI_PCA_MFMA(2);
+    case 3: LOKI_PCA_MFMA(3);
+    case 4: LOKI_PCA_MFMA(4);
+    default: return hipErrorInvalidValue;
+  }
+#undef LOKI_PCA_MFMA
+  return hipGetLastError();
+}
+
+hipError_t launch_pca_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
+                           const void* v, float* partial, void* out, hipStream_t st) {
+  const int rpb = (s.S + nsplit - 1) / nsplit;
+  if (s.G == 8) return launch_pca_mfma_nh<8>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+  if (s.G == 4) return launch_pca_mfma_nh<4>(s, nsplit, rpb, qhat, klo, v, partial, out, st);
+  return hipErrorInvalidValue;
 }
 
 bool attend_mfma_applies(const Shape& s, int heads_per_block) {

@@ -87,6 +87,8 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
 bool attend_mfma_applies(const Shape& s, int heads_per_block);
 hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const void* k_full,
                              const void* v, float* partial, void* out, hipStream_t st);
+hipError_t launch_pca_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
+                           const void* v, float* partial, void* out, hipStream_t st);
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
                               const void* khi, const void* v, const int32_t* sel_idx, float* partial,
                               void* out, hipStream_t st);

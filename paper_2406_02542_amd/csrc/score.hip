@@ -163,13 +163,16 @@ __device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (
 }
 
 // NCH = 16-byte chunks per slab row (d = 8 * NCH).
-template <int NCH, int G, bool GROUP_MAX>
+// TILE: several new tokens per sequence (rg.queries = m > 1).  The m G query heads that read one
+// KV head's slab form the 16 columns of the B operand, 16 / G tokens per block (blockIdx.z picks
+// the tile of tokens, blockIdx.y the sequence and KV head), so the slab is read once per tile
+// instead of once per token: [m G, d] x [d, S] as one contraction.  Token j only has scores for
+// the rows of its own causal length; the block covers the longest length of its tile.
+template <int NCH, int G, bool GROUP_MAX, bool TILE>
 __global__ __launch_bounds__(256) void score_mfma_kernel(
     const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
     int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg, Paging pg) {
   constexpr int d = 8 * NCH;
-  const int S = seq_rows(rg, (int)blockIdx.y / Hkv, S_max);  // the score buffer keeps the stride S_max
-  if ((int)blockIdx.x * rows_per_block >= S) return;
   constexpr int RB = NCH <= 4 ? 4 / NCH : 1;   // 16-row blocks one load instruction covers
   constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
   constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
@@ -177,11 +180,39 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   constexpr int UN = 8 / NL;                   // steps per loop trip: 8 loads in flight per lane
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int unit = blockIdx.y;
-  const int head0 = unit * G;
-
   const int kgrp = lane >> 4, r16 = lane & 15;
-  const bool head_ok = r16 < G;
+
+  // column r16 of the tile: which query head it is, where its scores go, how many rows it sees
+  int S;            // rows the block scores up to (uniform)
+  int S_lane;       // rows head r16 has scores for
+  bool head_ok;
+  size_t head;      // row of qhat
+  size_t score_row; // row of the score buffer
+  int cache_b, hkv;
+  if constexpr (TILE) {
+    constexpr int QPT = 16 / G;  // tokens per tile
+    const int m = rg.queries;
+    const int bs = (int)blockIdx.y / Hkv, j0 = (int)blockIdx.z * QPT;
+    hkv = (int)blockIdx.y % Hkv;
+    cache_b = bs;
+    const int j = j0 + r16 / G;
+    head_ok = j < m;
+    const int entry = bs * m + min(j, m - 1);
+    head = ((size_t)entry * Hkv + hkv) * G + r16 % G;
+    score_row = GROUP_MAX ? (size_t)entry * Hkv + hkv : head;
+    S_lane = seq_rows(rg, entry, S_max);
+    S = 0;
+    for (int jj = j0; jj < min(j0 + QPT, m); ++jj) S = max(S, seq_rows(rg, bs * m + jj, S_max));
+  } else {
+    const int unit = blockIdx.y;
+    hkv = unit % Hkv;
+    cache_b = unit / Hkv;
+    head_ok = r16 < G;
+    head = (size_t)unit * G + (head_ok ? r16 : 0);
+    score_row = GROUP_MAX ? (size_t)unit : head;
+    S = S_lane = seq_rows(rg, cache_b, S_max);  // the score buffer keeps the stride S_max
+  }
+  if ((int)blockIdx.x * rows_per_block >= S) return;
 
   // B operands: qhat of head r16, the 8 columns this lane's k-group stands for
   bf16x8_t bq[NB][3];
@@ -191,7 +222,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
     const bool active = head_ok && (NCH <= 4 ? (kgrp / NCH == n) : true);
     float x[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = qhat[(size_t)(head0 + (head_ok ? r16 : 0)) * kD + kbase + e];
+    for (int e = 0; e < 8; ++e) x[e] = qhat[head * kD + kbase + e];
     split_bf16x8(x, active, bq[n]);
   }
 
@@ -201,8 +232,8 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
   // the block's rows are consecutive in memory (a paged cache: the host keeps a block inside a page)
-  const long long row_shift =
-      cache_row(pg, unit / Hkv / max(rg.queries, 1), unit % Hkv, Hkv, S_cap, row0) - row0;
+  const long long row_shift = cache_row(pg, cache_b, hkv, Hkv, S_cap, row0) - row0;
+  const int lane_end = min(row_end, S_lane);
   const char* base = reinterpret_cast<const char*>(klo) + row_shift * (long long)row_bytes +
                      (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const bool vec_ok = (S_max & 3) == 0;
@@ -242,22 +273,20 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
         const int rowbase = trow + 16 * rb + 4 * kgrp;
         float v[4] = {acc[0], acc[1], acc[2], acc[3]};
         bool writer = head_ok;
-        float* dst;
         if constexpr (GROUP_MAX) {
+          // the G heads of one token sit in G consecutive lanes
 #pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<16>(head_ok ? v[i] : -3.0e38f);
-          writer = r16 == 0;
-          dst = scores + (size_t)unit * S_max + rowbase;
-        } else {
-          dst = scores + (size_t)(head0 + (head_ok ? r16 : 0)) * S_max + rowbase;
+          for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<G>(head_ok ? v[i] : -3.0e38f);
+          writer = head_ok && (r16 % G == 0);
         }
-        if (writer && rowbase < row_end) {
-          if (vec_ok && rowbase + 3 < row_end) {
+        float* dst = scores + score_row * S_max + rowbase;
+        if (writer && rowbase < lane_end) {
+          if (vec_ok && rowbase + 3 < lane_end) {
             *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
           } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (rowbase + i < row_end) dst[i] = v[i];
+              if (rowbase + i < lane_end) dst[i] = v[i];
           }
         }
       }
@@ -265,46 +294,64 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   }
 }
 
-template <int NCH, int G>
-static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const void* q, const float* P,
-                                      const void* klo, float* scores, float* qhat, hipStream_t st) {
-  const int rpb = score_rows_per_block(s);
-  dim3 grid((s.S + rpb - 1) / rpb, s.B * s.Hkv);
-  if (select_mode == 1) {
-    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, true>), grid, dim3(256), 0, st,
+// tokens of one sequence that share a score block (TILE), and the blocks along z that takes
+static int score_tile_tokens(const Shape& s) { return 16 / s.G; }
+
+template <int NCH, int G, bool TILE>
+static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const void* klo, float* scores,
+                                      const float* qhat, hipStream_t st) {
+  const int m = TILE ? s.rg.queries : 1;
+  const int nz = TILE ? (m + score_tile_tokens(s) - 1) / score_tile_tokens(s) : 1;
+  Shape blocks = s;  // the grid's y*z extent stands in for the batch when the row block is sized
+  blocks.B = s.B / m * nz;
+  const int rpb = score_rows_per_block(blocks);
+  dim3 grid((s.S + rpb - 1) / rpb, s.B / m * s.Hkv, nz);
+  if (select_mode == 1 && G > 1) {
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, (G > 1), TILE>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
   } else {
-    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false>), grid, dim3(256), 0, st,
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false, TILE>), grid, dim3(256), 0, st,
                        static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
   }
   return hipGetLastError();
 }
 
 template <int NCH>
-static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const void* q, const float* P,
-                                      const void* klo, float* scores, float* qhat, hipStream_t st) {
+static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const void* klo, float* scores,
+                                      const float* qhat, hipStream_t st) {
+  if (s.rg.queries > 1) {
+    switch (s.G) {
+      case 1: return launch_score_mfma_g<NCH, 1, true>(s, select_mode, klo, scores, qhat, st);
+      case 2: return launch_score_mfma_g<NCH, 2, true>(s, select_mode, klo, scores, qhat, st);
+      case 4: return launch_score_mfma_g<NCH, 4, true>(s, select_mode, klo, scores, qhat, st);
+      case 8: return launch_score_mfma_g<NCH, 8, true>(s, select_mode, klo, scores, qhat, st);
+      default: return hipErrorInvalidValue;
+    }
+  }
   switch (s.G) {
-    case 2: return launch_score_mfma_g<NCH, 2>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 4: return launch_score_mfma_g<NCH, 4>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 8: return launch_score_mfma_g<NCH, 8>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 2: return launch_score_mfma_g<NCH, 2, false>(s, select_mode, klo, scores, qhat, st);
+    case 4: return launch_score_mfma_g<NCH, 4, false>(s, select_mode, klo, scores, qhat, st);
+    case 8: return launch_score_mfma_g<NCH, 8, false>(s, select_mode, klo, scores, qhat, st);
     default: return hipErrorInvalidValue;
   }
 }
 
-// bf16 cache, 2..8 query heads per KV head and a power-of-two number of chunks per slab row
+// bf16 cache, a power-of-two number of chunks per slab row, and at least two query heads that
+// share a slab: 2..8 per KV head, or several new tokens per sequence
 static bool score_mfma_applies(const Shape& s) {
   const int nch = s.d / 8;
-  return s.dtype == 1 && s.G >= 2 && s.G <= 8 && s.d % 8 == 0 && (nch & (nch - 1)) == 0;
+  const bool shared = (s.G >= 2 || s.rg.queries > 1) && s.G <= 8;
+  return s.dtype == 1 && shared && s.d % 8 == 0 && (nch & (nch - 1)) == 0;
 }
 
-static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* q, const float* P,
-                                    const void* klo, float* scores, float* qhat, hipStream_t st) {
+static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* klo, float* scores,
+                                    const float* qhat, hipStream_t st) {
   switch (s.d / 8) {
-    case 1: return launch_score_mfma_n<1>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 2: return launch_score_mfma_n<2>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 4: return launch_score_mfma_n<4>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 8: return launch_score_mfma_n<8>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 16: return launch_score_mfma_n<16>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 1: return launch_score_mfma_n<1>(s, select_mode, klo, scores, qhat, st);
+    case 2: return launch_score_mfma_n<2>(s, select_mode, klo, scores, qhat, st);
+    case 4: return launch_score_mfma_n<4>(s, select_mode, klo, scores, qhat, st);
+    case 8: return launch_score_mfma_n<8>(s, select_mode, klo, scores, qhat, st);
+    case 16: return launch_score_mfma_n<16>(s, select_mode, klo, scores, qhat, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -389,7 +436,7 @@ hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qha
 
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, hipStream_t st) {
-  if (score_mfma_applies(s)) return launch_score_mfma(s, select_mode, q, P, klo, scores, qhat, st);
+  if (score_mfma_applies(s)) return launch_score_mfma(s, select_mode, klo, scores, qhat, st);
   return s.dtype == 0 ? launch_score_t<F32>(s, select_mode, q, P, klo, scores, qhat, st)
                       : launch_score_t<BF16>(s, select_mode, q, P, klo, scores, qhat, st);
 }

@@ -244,7 +244,8 @@ def test_dense_step_ragged(G, dtype):
 # ---------------------------------------------------------------- PCAAttn (Algorithm 2) --
 @pytest.mark.parametrize("G,dtype,d,S", [(1, "f32", 32, 1500), (1, "bf16", 32, 4096), (2, "bf16", 16, 3001),
                                          (4, "bf16", 64, 5000), (8, "bf16", 32, 2000), (4, "f32", 128, 700),
-                                         (1, "bf16", 128, 1000)])
+                                         (1, "bf16", 128, 1000), (8, "bf16", 48, 2500), (4, "bf16", 8, 1300),
+                                         (4, "bf16", 104, 900), (8, "bf16", 128, 700)])
 def test_pca_attn(G, dtype, d, S):
     """softmax(qhat[:d] Klo^T / sqrt(D)) V over all rows; the residual slab is never passed."""
     w = synth.Workload(f"pca_g{G}", 3, 2 * G, 2, 128, S, dtype, d, 8, seed=9990 + G)
@@ -317,12 +318,16 @@ def test_decode_step_replays_from_a_captured_graph(G, mode):
 
 
 # ------------------------------------------------------- several new tokens per sequence --
-@pytest.mark.parametrize("G,dtype,mode", [(1, "bf16", 0), (4, "bf16", 0), (4, "bf16", 1), (2, "f32", 0)])
-def test_step_with_several_new_tokens_per_sequence(G, dtype, mode):
-    """queries_per_seq = 3 (chunked / speculative decoding): token j of a sequence is appended
+@pytest.mark.parametrize("G,dtype,mode,m", [(1, "bf16", 0, 3), (4, "bf16", 0, 3), (4, "bf16", 1, 3),
+                                            (2, "f32", 0, 3), (4, "bf16", 0, 5), (8, "bf16", 1, 3),
+                                            (1, "bf16", 0, 17), (2, "bf16", 1, 9), (8, "bf16", 0, 2)])
+def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m):
+    """queries_per_seq = m (chunked / speculative decoding): token j of a sequence is appended
     at its own row and attends up to and including it; entries of one sequence share its
-    cache.  Same protocol as the single-token cases."""
-    m, B = 3, 3
+    cache.  Same protocol as the single-token cases.  On a bf16 cache the m G query heads of
+    a KV head are scored as tiles of 16 columns: the cases cover a partly filled tile, two
+    tiles, and a last tile with one token."""
+    B = 3
     w = synth.Workload(f"multi_g{G}", B, 2 * G, 2, 128, 2500, dtype, 32, 400, seed=14000 + G)
     wq = w.replace(B=B * m)
     x = synth.make_inputs(w)
@@ -401,6 +406,7 @@ def test_step_with_several_new_tokens_per_sequence(G, dtype, mode):
     (1, "bf16", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 1024, 1, api.PATH_SPLIT),
     (4, "bf16", 1, 256, 1, api.PATH_SPLIT), (8, "bf16", 1, 512, 1, api.PATH_SPLIT),
     (2, "f32", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 256, 2, api.PATH_SPLIT),
+    (4, "bf16", 1, 512, 5, api.PATH_SPLIT), (1, "bf16", 0, 256, 3, api.PATH_SPLIT),
     (1, "bf16", 0, 256, 1, api.PATH_FUSED), (1, "bf16", 0, 2048, 1, api.PATH_FUSED),
     (1, "f32", 0, 512, 1, api.PATH_FUSED)])
 def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path):

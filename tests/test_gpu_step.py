@@ -401,6 +401,68 @@ def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m):
     say(f"   max_err {max_err:.3e}")
 
 
+@pytest.mark.parametrize("Hq,Hkv,mode,m", [(32, 8, 0, 4), (32, 8, 1, 4), (32, 8, 1, 3), (32, 32, 0, 4)])
+def test_multi_token_step_equals_single_token_steps_at_full_size(Hq, Hkv, mode, m):
+    """At a size the oracle cannot walk (16 sequences, S = 8192, k = 1024): one step with
+    queries_per_seq = m gives what m single-token steps one after the other give (those are
+    the steps the oracle covers above).  With grouped heads both forms score a column with the
+    same matrix-core arithmetic, so the index lists must be identical; with one head per KV
+    head the single-token form scores in fp32 vector order, and lists may differ by swaps at
+    the threshold.  Outputs agree to bf16 rounding (the two forms split the k rows over a
+    different number of blocks)."""
+    Bs, S, d, k, G = 16, 8192, 32, 1024, Hq // Hkv
+    tdt = torch.bfloat16
+    g = torch.Generator(device="cuda").manual_seed(77 + Hq + mode + m)
+    rnd = lambda *shape, scale=1.0: (scale * torch.randn(shape, device="cuda", generator=g)).to(tdt)
+    klo0, khi0, v0 = rnd(Bs, Hkv, S, d, scale=2.0), rnd(Bs, Hkv, S, 128 - d, scale=0.5), rnd(Bs, Hkv, S, 128)
+    q, k_new, v_new = rnd(Bs, m, Hq, 128), rnd(Bs, m, Hkv, 128), rnd(Bs, m, Hkv, 128)
+    Pm = torch.linalg.qr(torch.randn((Hkv, 128, 128), device="cuda", generator=g))[0].contiguous()
+    rows = torch.randint(S // 3, S + 1, (Bs,), device="cuda", generator=g, dtype=torch.int32)
+    rows[0] = S
+    lens = (rows[:, None] - (m - 1 - torch.arange(m, device="cuda", dtype=torch.int32))[None, :]).contiguous()
+    ks = torch.clamp((k * lens.long()) // S, min=1).to(torch.int32).contiguous()
+    say(f"Hq {Hq} Hkv {Hkv} mode {mode} m {m} rows {rows.tolist()}")
+    lay = api.make_layout(Bs, Hq, Hkv, 128, d, S, tdt)
+    laym = api.make_layout(Bs * m, Hq, Hkv, 128, d, S, tdt)
+    ws = api.alloc_workspace(laym, S, d, k, mode)
+    hsel = Hq if mode == 0 or G == 1 else Hkv
+    sel = mode | api.PATH_SPLIT
+
+    ca = [t.clone() for t in (klo0, khi0, v0)]
+    out_a = torch.full((Bs, m, Hq, 128), float("nan"), dtype=tdt, device="cuda")
+    idx_a = torch.full((Bs, m, hsel, k), -7, dtype=torch.int32, device="cuda")
+    api.loki_decode_step(lay, q.view(Bs * m, Hq, 128), Pm, *ca, S, d, k, sel, ws, out_a.view(Bs * m, Hq, 128),
+                         idx_a.view(Bs * m, hsel, k), seq_lens=lens.view(-1), ks=ks.view(-1),
+                         k_new=k_new.view(Bs * m, Hkv, 128), v_new=v_new.view(Bs * m, Hkv, 128), queries_per_seq=m)
+    cb = [t.clone() for t in (klo0, khi0, v0)]
+    out_b, idx_b = torch.empty_like(out_a), torch.empty_like(idx_a)
+    for j in range(m):
+        o = torch.full((Bs, Hq, 128), float("nan"), dtype=tdt, device="cuda")
+        ix = torch.full((Bs, hsel, k), -7, dtype=torch.int32, device="cuda")
+        api.loki_decode_step(lay, q[:, j].contiguous(), Pm, *cb, S, d, k, sel, ws, o, ix,
+                             seq_lens=lens[:, j].contiguous(), ks=ks[:, j].contiguous(),
+                             k_new=k_new[:, j].contiguous(), v_new=v_new[:, j].contiguous())
+        out_b[:, j], idx_b[:, j] = o, ix
+    torch.cuda.synchronize()
+    for a, b in zip(ca, cb):
+        assert torch.equal(a, b)  # the appended rows
+    assert torch.isfinite(out_a.float()).all()
+    if G > 1:
+        assert torch.equal(idx_a, idx_b)
+    else:
+        ia, ib = idx_a.cpu().numpy(), idx_b.cpu().numpy()
+        worst = 0
+        for e in np.ndindex(ia.shape[:3]):
+            la, lb = set(ia[e][ia[e] >= 0].tolist()), set(ib[e][ib[e] >= 0].tolist())
+            assert len(la) == len(lb)
+            worst = max(worst, len(la - lb))
+        say(f"   most rows swapped in one list: {worst}")
+        assert worst <= 2
+    err = float((out_a.float() - out_b.float()).abs().max())
+    say(f"   max |out difference| {err:.3e}")
+    assert err <= OUT_TOL["bf16"]
+
+
 # -------------------------------------------------------------------------- paged cache --
 @pytest.mark.parametrize("G,dtype,mode,page_rows,m,path", [
     (1, "bf16", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 1024, 1, api.PATH_SPLIT),

@@ -238,19 +238,23 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
                      (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
   const bool vec_ok = (S_max & 3) == 0;
 
-  for (int t0 = row0 + wave * RPS; t0 < row_end; t0 += 4 * RPS * UN) {
-    uint4 raw[UN][NL];
+  // Two register buffers of UN/2 steps each, refilled right after they are consumed, so that a
+  // wave always has loads in flight while it computes.  Loads past the block's end re-read its
+  // last row (no branch around a load; their scores are never stored).
+  constexpr int UH = UN / 2;             // steps per buffer
+  constexpr int kTrip = 4 * RPS * UH;    // rows the block advances per buffer
+  auto load_trip = [&](uint4 (&raw)[UH][NL], int t0) {
 #pragma unroll
-    for (int u = 0; u < UN; ++u)
+    for (int u = 0; u < UH; ++u)
 #pragma unroll
       for (int j = 0; j < NL; ++j) {
-        const int trow = t0 + u * 4 * RPS;
-        raw[u][j] = (trow + row_in_step < row_end)
-                        ? load16(base + (size_t)trow * row_bytes + (size_t)j * 64)
-                        : make_uint4(0, 0, 0, 0);
+        const int r = min(t0 + u * 4 * RPS + row_in_step, row_end - 1) - row_in_step;
+        raw[u][j] = load16(base + (long long)r * (long long)row_bytes + (size_t)j * 64);
       }
+  };
+  auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
+    for (int u = 0; u < UH; ++u) {
       const int trow = t0 + u * 4 * RPS;
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
@@ -291,6 +295,16 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
         }
       }
     }
+  };
+  uint4 buf0[UH][NL], buf1[UH][NL];
+  const int t_first = row0 + wave * RPS;
+  load_trip(buf0, t_first);
+  load_trip(buf1, t_first + kTrip);
+  for (int t0 = t_first; t0 < row_end; t0 += 2 * kTrip) {
+    score_trip(buf0, t0);
+    load_trip(buf0, t0 + 2 * kTrip);
+    score_trip(buf1, t0 + kTrip);
+    load_trip(buf1, t0 + 3 * kTrip);
   }
 }
 

@@ -92,8 +92,10 @@ typedef float rot_f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kRotMfmaThreads = 512;
 constexpr int kRotMfmaWaves = kRotMfmaThreads / 64;
-constexpr int kRotMfmaItems = 2048;  // rows per block: 16 tiles per wave
+constexpr int kRotMfmaMinItems = 1024;  // rows per block, at least and at most
+constexpr int kRotMfmaMaxItems = 8192;
 constexpr int kRotMfmaTPW = 2;        // tiles a wave multiplies per operand fetch
+constexpr int kRotTerms = 3;          // bf16 terms P enters with (3: every product exact)
 
 // PAGED: the output rows go through the page table (a separate instantiation, so that the
 // contiguous kernel's store addresses stay plain arithmetic).
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
     const uint16_t* __restrict__ k_new, const float* __restrict__ P, uint16_t* __restrict__ klo,
     uint16_t* __restrict__ khi, int Hkv, int S_cap, int d, int pos, int n_new, int n_items,
     int items_per_block, Paging pg) {
-  __shared__ uint4 s_B[3][4][8][64];  // [term][32-column step of K][16-column block of Khat][lane]
+  __shared__ uint4 s_B[kRotTerms][4][8][64];  // [term][32-column step of K][16-column block of Khat][lane]
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: row bases stay scalar
   const int kgrp = lane >> 4, r16 = lane & 15;
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
     float rest = pv[n];
     uint16_t* base = reinterpret_cast<uint16_t*>(&s_B[0][i / 32][col / 16][((i % 32) / 8) * 16 + col % 16]) + (i % 8);
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
+    for (int t = 0; t < kRotTerms; ++t) {
       const uint16_t hb = BF16::round(rest);
       rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
       base[(size_t)t * (sizeof(s_B[0]) / 2)] = hb;
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
 #pragma unroll
         for (int half = 0; half < 2; ++half) acc[u][half] = rot_f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int t = 2; t >= 0; --t)  // smallest terms first
+      for (int t = kRotTerms - 1; t >= 0; --t)  // smallest terms first
 #pragma unroll
         for (int step = 0; step < 4; ++step) {
           const rot_bf16x8_t b0 =
@@ -263,7 +265,13 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
   dim3 grid((n_items + ipb - 1) / ipb, s.Hkv);
   const size_t lds = 0;  // LDS is declared statically in the kernels
   if (s.dtype == 1) {
-    int ipb_m = kRotMfmaItems;
+    // One block per CU where the rows allow it: a block's set-up (P_h split into LDS) and its
+    // tail are paid once per block, and on the benchmark prefill 8192 rows per block (one round
+    // of blocks) took 289 us against 348 us with 2048 (four rounds).
+    constexpr int kTripRows = 16 * kRotMfmaTPW * kRotMfmaWaves;
+    long long want = (n_items_ll * s.Hkv + kNumCU - 1) / kNumCU;
+    want = (want + kTripRows - 1) / kTripRows * kTripRows;
+    int ipb_m = (int)(want < kRotMfmaMinItems ? kRotMfmaMinItems : want > kRotMfmaMaxItems ? kRotMfmaMaxItems : want);
     if (n_items < ipb_m) ipb_m = ((n_items + 15) / 16) * 16;
     dim3 grid_m((n_items + ipb_m - 1) / ipb_m, s.Hkv);
     if (paged)

@@ -321,6 +321,28 @@ def main():
 
         t_paged = timed(paged_step, args.steps, args.warmup)
         del pools
+
+        # several new tokens per sequence (chunked / speculative decoding): the same number of
+        # batch entries, as m = 4 consecutive tokens of B / 4 sequences (the first B / 4 caches)
+        multi = None
+        m_tok = 4
+        if w.B % m_tok == 0 and w.B * w.Hq * 1 <= 65535:
+            bs = w.B // m_tok
+            lay_m = api.make_layout(bs, w.Hq, w.Hkv, w.D, w.d, caches[0][0].shape[2], tdt)
+            lens_m = torch.tensor([w.S - (m_tok - 1 - j) for _ in range(bs) for j in range(m_tok)],
+                                  dtype=torch.int32, device="cuda")
+            ks_m = torch.full((w.B,), w.k, dtype=torch.int32, device="cuda")
+
+            def multi_step(i):
+                klo, khi, v, _ = caches[i % len(caches)]
+                api.loki_decode_step(lay_m, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, out, None,
+                                     seq_lens=lens_m, ks=ks_m, k_new=k_new, v_new=v_new,
+                                     queries_per_seq=m_tok, stream=stream)
+
+            t_multi = timed(multi_step, args.steps, args.warmup)
+            multi = {"queries_per_seq": m_tok, "sequences": bs, "us": t_multi * 1e6,
+                     "us_per_token": t_multi * 1e6 / m_tok}
+            log(f"[bench] {m_tok} tokens per sequence on {bs} sequences: {t_multi * 1e6:.1f} us")
         t_app = timed(append_step, args.steps, args.warmup)
         t_sep = timed(separate_step, args.steps, args.warmup)
         t_rag = timed(ragged_step, args.steps, args.warmup)
@@ -334,6 +356,7 @@ def main():
                 "paged_cache": {"page_rows": page_rows, "pool_pages": n_pages,
                                 "append_folded_in_us": t_paged * 1e6},
                 "rotate_keys_then_value_copy_then_decode_us": t_sep * 1e6,
+                "several_tokens_per_sequence": multi,
                 "ragged": {"seq_lens_min_mean_max": [int(st_in["seq_lens"].min()),
                                                      float(st_in["seq_lens"].mean()),
                                                      int(st_in["seq_lens"].max())],

@@ -31,7 +31,7 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy
 # calibration; measured values and commands are in profiles/llama2_7b_fused_decode.md.
 MEASURED_TRAFFIC_BYTES = {
-    "llama2_7b:fused_decode": 194713.2 * 2048 + 128.0 * 1024,
+    "llama2_7b:fused_decode": 194697.7 * 2048 + 128.0 * 1024,
 }
 
 

@@ -4,8 +4,11 @@ that hold at any size (index validity, ordering) are checked on every unit."""
 import numpy as np
 import pytest
 
+import torch
+
+from oracle import loki_oracle as O
 from paper_2406_02542_amd import api, synth
-from tests.parity import DeviceCase, check_dense, check_loki
+from tests.parity import OUT_TOL, TORCH_DT, DeviceCase, check_dense, check_loki
 
 pytestmark = pytest.mark.gpu
 
@@ -57,6 +60,21 @@ def test_full_size_config(name, modes, n_units):
     out = case.run_dense()
     assert np.all(np.isfinite(out))
     say(f"{name} dense: {check_dense(case, units=units[:4], out_gpu=out)}")
+    # Appendix E, Algorithm 2 at the same size (grouped heads: the matrix-core kernel)
+    lay = case.layout
+    ws = torch.empty(api.loki_workspace_bytes(lay, w.S, w.d, 0, -2), dtype=torch.uint8, device="cuda")
+    outp = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")
+    api.loki_pca_attn(lay, case.q, case.P, case.klo, case.v, w.S, w.d, ws, outp)
+    torch.cuda.synchronize()
+    got = outp.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    ref = O.pca_attention_batch(x["q"], x["P"], x["khat"], x["v"], w.d, units=units[:4])
+    worst = 0.0
+    for b, h in units[:4]:
+        for hq in range(h * w.G, (h + 1) * w.G):
+            worst = max(worst, float(np.max(np.abs(got[b, hq] - ref[b, hq]))))
+    say(f"{name} PCAAttn: max_err {worst:.3e} over {4 * w.G} heads")
+    assert worst <= OUT_TOL[w.dtype]
 
 
 def test_full_size_large_share_sweep():

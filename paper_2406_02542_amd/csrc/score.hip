@@ -351,11 +351,15 @@ static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const voi
 }
 
 // bf16 cache, a power-of-two number of chunks per slab row, and at least two query heads that
-// share a slab: 2..8 per KV head, or several new tokens per sequence
+// share a slab: 2..8 per KV head, or several new tokens per sequence.  With rows of 16 or 32
+// bytes (d <= 16) a matrix instruction is spent on very few bytes and the vector kernel is the
+// faster one (d = 16, 4 heads per KV head, one selection per group, S = 131072: 33 against
+// 41 us; d = 8: 12 against 33 us), so grouped heads alone do not take this path there.
 static bool score_mfma_applies(const Shape& s) {
   const int nch = s.d / 8;
-  const bool shared = (s.G >= 2 || s.rg.queries > 1) && s.G <= 8;
-  return s.dtype == 1 && shared && s.d % 8 == 0 && (nch & (nch - 1)) == 0;
+  const bool tile = s.rg.queries > 1;
+  const bool shared = (s.G >= 2 || tile) && s.G <= 8;
+  return s.dtype == 1 && shared && s.d % 8 == 0 && (nch & (nch - 1)) == 0 && (nch > 2 || tile);
 }
 
 static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* klo, float* scores,

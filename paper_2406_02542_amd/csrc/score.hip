@@ -112,19 +112,28 @@ __global__ __launch_bounds__(256) void score_kernel(
       cache_row(pg, unit / Hkv / max(rg.queries, 1), unit % Hkv, Hkv, S_cap, row0) - row0;
   const char* base = reinterpret_cast<const char*>(klo) + row_shift * (long long)row_bytes +
                      (size_t)(cact ? c : 0) * 16;
-  score_rows<T, LPR, G, 4>(ContiguousRows{base, row_bytes}, cact, qr, row0, row_end,
-                           [&](int row, const float (&sc)[G]) {
-                             if constexpr (GROUP_MAX) {
-                               float m = sc[0];
+  auto emit = [&](int row, const float (&sc)[G]) {
+    if constexpr (GROUP_MAX) {
+      float m = sc[0];
 #pragma unroll
-                               for (int g = 1; g < G; ++g) m = fmaxf(m, sc[g]);
-                               scores[(size_t)unit * S_max + row] = m;
-                             } else {
+      for (int g = 1; g < G; ++g) m = fmaxf(m, sc[g]);
+      scores[(size_t)unit * S_max + row] = m;
+    } else {
 #pragma unroll
-                               for (int g = 0; g < G; ++g)
-                                 scores[(size_t)(head0 + g) * S_max + row] = sc[g];
-                             }
-                           });
+      for (int g = 0; g < G; ++g) scores[(size_t)(head0 + g) * S_max + row] = sc[g];
+    }
+  };
+  const ContiguousRows rows{base, row_bytes};
+  if constexpr (LPR <= 8) {
+    // two trips of eight loads per lane in flight, refilled as they are consumed
+    ScoreTrip<LPR> t0, t1;
+    const int tile0 = row0 + (tid >> 6) * 64;
+    score_load_trip<LPR, 4>(rows, tile0, row_end, t0);
+    score_load_trip<LPR, 4>(rows, tile0 + 4 * 64 * ScoreTrip<LPR>::TPI, row_end, t1);
+    score_rows_pipelined<T, LPR, G, 4>(rows, qr, row0, row_end, t0, t1, emit);
+  } else {
+    score_rows<T, LPR, G, 4>(rows, cact, qr, row0, row_end, emit);
+  }
 }
 
 // ---- matrix-core variant for grouped queries on a bf16 cache ----------------------------------

@@ -303,6 +303,24 @@ def rank_at(eigenvalues, v: float) -> int:
     return len(lam)
 
 
+def layer_rank_at(eigenvalues, v: float) -> float:
+    """Rank_l@v (Section 3.1, below Eq. 2): Rank_{l,h}@v averaged over the heads of a layer;
+    ``eigenvalues`` is [heads, D]."""
+    lam = np.asarray(eigenvalues, dtype=np.float64)
+    return float(np.mean([rank_at(lam[h], v) for h in range(lam.shape[0])]))
+
+
+def layer_width(eigenvalues, v: float, multiple: int = 1) -> int:
+    """Variable-width policy of Appendix B.2: a layer's d follows its explained variance.
+    Reading: d is Rank_l@v of the layer, taken up to the next whole number and then to the
+    next multiple of the cache layout's granularity, at most D."""
+    lam = np.asarray(eigenvalues, dtype=np.float64)
+    D = lam.shape[-1]
+    d = int(math.ceil(layer_rank_at(lam, v)))
+    d = -(-d // multiple) * multiple
+    return min(d, D)
+
+
 def jaccard(a, b) -> float:
     """|A n B| / |A u B| of two index sets (Section 6.3 compares the selection of Loki with
     that of exact top-k this way); negative entries are padding."""

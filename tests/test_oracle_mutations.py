@@ -34,6 +34,7 @@ BATTERY = [
     pins.test_group_mode_selects_on_group_max,
     pins.test_bf16_rounding_matches_torch,
     pins.test_rank_at_closed_form,
+    pins.test_layer_rank_and_width_closed_forms,
     pins.test_cost_model_prints_2p6x,
     pins.test_step_without_options_is_the_batch_function,
     pins.test_step_ragged_ignores_rows_past_each_sequence_and_pads_indices,
@@ -92,6 +93,9 @@ MUTATIONS = {
     # helpers
     "bf16 truncation instead of rounding": ("to_bf16", lambda x: (np.asarray(x, np.float64).astype(np.float32).view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32).astype(np.float64)),
     "rank_at off by one": ("rank_at", lambda ev, v: max(1, _real_rank_at(ev, v) - 1)),
+    "layer rank is the largest head's instead of the mean": ("layer_rank_at", lambda ev, v: float(max(_real_rank_at(e, v) for e in np.asarray(ev, float)))),
+    "layer width rounds down to the multiple": ("layer_width", lambda ev, v, multiple=1: min(int(math.ceil(O.layer_rank_at(ev, v))) // multiple * multiple, np.asarray(ev).shape[-1])),
+    "layer width rounds the mean to nearest": ("layer_width", lambda ev, v, multiple=1: min(-(-int(math.floor(O.layer_rank_at(ev, v))) // multiple) * multiple, np.asarray(ev).shape[-1])),
     "PCAAttn scaled by sqrt(d)": ("pca_attention", lambda q, P, Khat, V, d: O.softmax(O.approx_scores(O.rotate_query(q, P), Khat, d) / math.sqrt(d)) @ np.asarray(V, float)),
     "PCAAttn over the d LAST columns": ("pca_attention", lambda q, P, Khat, V, d: O.softmax((np.asarray(Khat, float)[:, -d:] @ O.rotate_query(q, P)[-d:]) / math.sqrt(len(q))) @ np.asarray(V, float)),
     "Jaccard over the smaller set": ("jaccard", lambda a, b: len(set(a) & set(b)) / max(1, min(len(set(a)), len(set(b))))),

@@ -324,6 +324,35 @@ def test_rank_at_closed_form():
     assert O.rank_at([2.0, 3.0, 5.0], 100) == 3
 
 
+def test_layer_rank_and_width_closed_forms():
+    """Rank_l@v is the head average of Eq. 2 (Section 3.1); the width policy of Appendix B.2
+    takes it up to a whole multiple of the layout's granularity.  Heads with geometric
+    spectra of different ratios have closed-form ranks; a flat spectrum needs ceil(v D / 100)
+    components."""
+    D = 128
+    ratios = (0.80, 0.90, 0.95, 0.97)
+    lam = np.stack([r ** np.arange(D) for r in ratios])
+    for v in (50, 65, 80):
+        ranks = [math.ceil(math.log(1 - v / 100.0 * (1 - r ** D)) / math.log(r) - 1e-12) for r in ratios]
+        assert O.layer_rank_at(lam, v) == pytest.approx(sum(ranks) / 4.0, abs=1e-12)
+        whole = math.ceil(sum(ranks) / 4.0)
+        assert O.layer_width(lam, v, 1) == whole
+        assert O.layer_width(lam, v, 8) == (whole + 7) // 8 * 8
+        assert O.layer_width(lam, v, 8) % 8 == 0 and O.layer_width(lam, v, 8) - whole < 8
+    flat = np.ones((3, D))
+    assert O.layer_rank_at(flat, 50) == 64 and O.layer_rank_at(flat, 80) == math.ceil(0.8 * D)
+    assert O.layer_width(flat, 80, 8) == 104 and O.layer_width(flat, 80, 4) == 104
+    assert O.layer_width(flat, 99.9, 8) == D          # never beyond D
+    # one head is the plain Eq. 2; the order of heads does not matter; a mean of 20.5 goes to 21
+    assert O.layer_rank_at(lam[1:2], 65) == O.rank_at(lam[1], 65)
+    assert O.layer_rank_at(lam[::-1], 65) == O.layer_rank_at(lam, 65)
+    two = np.zeros((2, D))
+    two[0, :20] = 1.0
+    two[1, :21] = 1.0
+    assert O.layer_rank_at(two, 100) == 20.5
+    assert O.layer_width(two, 100, 1) == 21 and O.layer_width(two, 100, 8) == 24
+
+
 def test_score_error_statistics():
     """For q ~ N(0, I): E[(a_full - a_approx)^2] = sum_{j >= d} (sigma_j^2 + nu)
     on the synthetic keys (their columns in the rotated basis are independent)."""

@@ -266,6 +266,19 @@ int loki_rank_at(const float* eigenvalues, int n_heads, int D, float v_percent, 
                  void* stream);
 
 /*
+ * Section 3.1 (Rank_l@v: Rank_{l,h}@v of Eq. 2 averaged over the heads of a layer) and
+ * Appendix B.2 (a layer's slab width set from its explained variance).  eigenvalues is
+ * device fp32 [n_heads, D], decreasing per head.  mean_rank (device fp32 [1], may be NULL)
+ * receives Rank_l@v; d_out (device int32 [1]) receives the width: Rank_l@v taken up to the
+ * next whole number, then up to the next multiple of `multiple` (the layout's granularity:
+ * 8 for bf16 caches, 4 for fp32; D % multiple == 0), at most D.  0 < v_percent <= 100.
+ * The value is what loki_layout.d_split of that layer's cache would be set to; the caller
+ * reads it back.  Errors as for loki_rank_at.
+ */
+int loki_layer_width(const float* eigenvalues, int n_heads, int D, float v_percent, int multiple,
+                     float* mean_rank, int32_t* d_out, void* stream);
+
+/*
  * Section 6.3 (agreement of two selections, Figure 6 left): Jaccard similarity
  * |A n B| / |A u B| of n_lists pairs of ascending index lists (device int32
  * [n_lists, k], entries < 0 are padding at the end); out is device fp32 [n_lists].

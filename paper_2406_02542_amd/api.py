@@ -76,6 +76,8 @@ def lib() -> ctypes.CDLL:
     L.loki_pca_fit.argtypes = [LP, vp, ctypes.c_longlong, vp, vp, vp, sz, vp]
     L.loki_rank_at.restype = i32
     L.loki_rank_at.argtypes = [vp, i32, i32, ctypes.c_float, vp, vp]
+    L.loki_layer_width.restype = i32
+    L.loki_layer_width.argtypes = [vp, i32, i32, ctypes.c_float, i32, vp, vp, vp]
     L.loki_index_jaccard.restype = i32
     L.loki_index_jaccard.argtypes = [vp, vp, i32, i32, vp, vp]
     L.dense_decode_attn.restype = i32
@@ -351,6 +353,15 @@ def loki_rank_at(eigenvalues: torch.Tensor, v_percent: float, ranks: torch.Tenso
     n, D = eigenvalues.shape
     _check(lib().loki_rank_at(_ptr(eigenvalues, "eigenvalues", torch.float32, n * D), n, D, v_percent,
                               _ptr(ranks, "ranks", torch.int32, n), _stream_ptr(stream)), "loki_rank_at")
+
+
+def loki_layer_width(eigenvalues: torch.Tensor, v_percent: float, multiple: int,
+                     mean_rank: Optional[torch.Tensor], d_out: torch.Tensor, stream=None) -> None:
+    n, D = eigenvalues.shape
+    _check(lib().loki_layer_width(_ptr(eigenvalues, "eigenvalues", torch.float32, n * D), n, D, v_percent,
+                                  multiple, _ptr(mean_rank, "mean_rank", torch.float32, 1),
+                                  _ptr(d_out, "d_out", torch.int32, 1), _stream_ptr(stream)),
+           "loki_layer_width")
 
 
 def loki_index_jaccard(idx_a: torch.Tensor, idx_b: torch.Tensor, out: torch.Tensor, stream=None) -> None:

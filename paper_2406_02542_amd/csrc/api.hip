@@ -513,6 +513,17 @@ int loki_rank_at(const float* eigenvalues, int n_heads, int D, float v_percent, 
   return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
 }
 
+int loki_layer_width(const float* eigenvalues, int n_heads, int D, float v_percent, int multiple,
+                     float* mean_rank, int32_t* d_out, void* stream) {
+  if (!eigenvalues || !d_out || n_heads < 1 || D < 1) return LOKI_ERR_INVALID_ARG;
+  if (!(v_percent > 0.f) || v_percent > 100.f) return LOKI_ERR_INVALID_ARG;
+  if (multiple < 1 || multiple > D || D % multiple != 0) return LOKI_ERR_INVALID_ARG;
+  if ((long long)n_heads * D > 0x7fffffffLL / 2) return LOKI_ERR_UNSUPPORTED;  // rank sum in int32
+  const hipError_t e = launch_layer_width(eigenvalues, n_heads, D, v_percent, multiple, mean_rank,
+                                          d_out, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+}
+
 int loki_index_jaccard(const int32_t* idx_a, const int32_t* idx_b, int n_lists, int k, float* out,
                        void* stream) {
   if (!idx_a || !idx_b || !out || n_lists < 1 || k < 1) return LOKI_ERR_INVALID_ARG;

@@ -14,7 +14,7 @@
 //                                     round-robin order, eigenvectors accumulated in L2-resident
 //                                     global memory; eigenpairs sorted by decreasing eigenvalue,
 //                                     every component's largest entry made positive
-//   rank_at_kernel, jaccard_kernel    small reductions
+//   rank_at_kernel, layer_width_kernel, jaccard_kernel    small reductions
 #include "common.h"
 
 namespace loki {
@@ -283,22 +283,46 @@ __global__ __launch_bounds__(kJacThreads) void jacobi_kernel(const double* __res
 }
 
 // Eq. 2: the smallest d whose leading normalised eigenvalues sum to at least v percent.
-__global__ __launch_bounds__(64) void rank_at_kernel(const float* __restrict__ eigenvalues, int Dn,
-                                                     float v_percent, int32_t* __restrict__ ranks) {
-  if (threadIdx.x != 0) return;
-  const float* lam = eigenvalues + (size_t)blockIdx.x * Dn;
+__device__ inline int rank_at_of(const float* __restrict__ lam, int Dn, float v_percent) {
   double total = 0.0;
   for (int i = 0; i < Dn; ++i) total += (double)lam[i];
   double run = 0.0;
-  int r = Dn;
   for (int i = 0; i < Dn; ++i) {
     run += (double)lam[i];
-    if (run / total >= (double)v_percent / 100.0) {
-      r = i + 1;
-      break;
-    }
+    if (run / total >= (double)v_percent / 100.0) return i + 1;
   }
-  ranks[blockIdx.x] = r;
+  return Dn;
+}
+
+__global__ __launch_bounds__(64) void rank_at_kernel(const float* __restrict__ eigenvalues, int Dn,
+                                                     float v_percent, int32_t* __restrict__ ranks) {
+  if (threadIdx.x != 0) return;
+  ranks[blockIdx.x] = rank_at_of(eigenvalues + (size_t)blockIdx.x * Dn, Dn, v_percent);
+}
+
+// Rank_l@v of a layer (the head average of Eq. 2, Section 3.1) and the slab width that the
+// variable-width policy of Appendix B.2 derives from it: the average taken up to a whole
+// number, then to a multiple of the layout's granularity, at most D.  One block; the ranks are
+// integers, so their sum is exact whatever the order.
+__global__ __launch_bounds__(256) void layer_width_kernel(const float* __restrict__ eigenvalues,
+                                                          int n_heads, int Dn, float v_percent,
+                                                          int multiple, float* __restrict__ mean_rank,
+                                                          int32_t* __restrict__ d_out) {
+  __shared__ int s_sum;
+  if (threadIdx.x == 0) s_sum = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int h = threadIdx.x; h < n_heads; h += 256)
+    mine += rank_at_of(eigenvalues + (size_t)h * Dn, Dn, v_percent);
+  if (mine) atomicAdd(&s_sum, mine);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int sum = s_sum;
+    if (mean_rank) *mean_rank = (float)((double)sum / (double)n_heads);
+    int d = (sum + n_heads - 1) / n_heads;             // ceil of the average
+    d = (d + multiple - 1) / multiple * multiple;
+    *d_out = d < Dn ? d : Dn;
+  }
 }
 
 // |A n B| / |A u B| of two ascending index lists of length k each (entries < 0 are padding).
@@ -395,6 +419,13 @@ hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, lon
 hipError_t launch_rank_at(const float* eigenvalues, int n, int Dn, float v_percent, int32_t* ranks,
                           hipStream_t st) {
   hipLaunchKernelGGL(rank_at_kernel, dim3(n), dim3(64), 0, st, eigenvalues, Dn, v_percent, ranks);
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_width(const float* eigenvalues, int n, int Dn, float v_percent, int multiple,
+                              float* mean_rank, int32_t* d_out, hipStream_t st) {
+  hipLaunchKernelGGL(layer_width_kernel, dim3(1), dim3(256), 0, st, eigenvalues, n, Dn, v_percent,
+                     multiple, mean_rank, d_out);
   return hipGetLastError();
 }
 

@@ -108,6 +108,8 @@ hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, lon
                             float* eigenvalues, void* workspace, hipStream_t st);
 hipError_t launch_rank_at(const float* eigenvalues, int n, int Dn, float v_percent, int32_t* ranks,
                           hipStream_t st);
+hipError_t launch_layer_width(const float* eigenvalues, int n, int Dn, float v_percent, int multiple,
+                              float* mean_rank, int32_t* d_out, hipStream_t st);
 hipError_t launch_jaccard(const int32_t* a, const int32_t* b, int n_lists, int k, float* out,
                           hipStream_t st);
 hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void* klo, void* khi,

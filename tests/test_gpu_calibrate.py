@@ -116,6 +116,33 @@ def test_rank_at_matches_oracle():
             assert g == wv or (v == 100.0 and abs(g - wv) <= 1), (v, got, want)
 
 
+def test_layer_width_matches_oracle():
+    """Rank_l@v and the width policy of Appendix B.2 on spectra of 3 to 300 heads."""
+    rng = np.random.default_rng(8)
+    for n_heads, taus in ((3, (4.0, 30.0, 90.0)), (32, None), (300, None)):
+        if taus is None:
+            taus = rng.uniform(3.0, 120.0, n_heads)
+        spectra = np.stack([np.sort(rng.random(128))[::-1] * np.exp(-np.arange(128) / t) for t in taus])
+        lam = torch.from_numpy(spectra.astype(np.float32)).cuda()
+        lam64 = lam.cpu().numpy().astype(np.float64)
+        for v in (50.0, 65.0, 80.0, 90.0):
+            for multiple in (1, 4, 8):
+                mean = torch.full((1,), -1.0, device="cuda")
+                d = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+                api.loki_layer_width(lam, v, multiple, mean, d)
+                torch.cuda.synchronize()
+                assert abs(mean.item() - O.layer_rank_at(lam64, v)) <= 1e-4
+                assert d.item() == O.layer_width(lam64, v, multiple), (n_heads, v, multiple)
+    d = torch.zeros(1, dtype=torch.int32, device="cuda")
+    api.loki_layer_width(lam, 80.0, 8, None, d)     # the mean is optional
+    torch.cuda.synchronize()
+    assert d.item() == O.layer_width(lam64, 80.0, 8)
+    with pytest.raises(RuntimeError):
+        api.loki_layer_width(lam, 80.0, 5, None, d)  # 128 is not a multiple of 5
+    with pytest.raises(RuntimeError):
+        api.loki_layer_width(lam, 0.0, 8, None, d)
+
+
 def test_index_jaccard_matches_oracle():
     rng = np.random.default_rng(4)
     n, k, S = 37, 500, 4000

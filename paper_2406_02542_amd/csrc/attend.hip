@@ -27,7 +27,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     const float* __restrict__ sel_score,   // REUSE_LO: [blocks_y, n] approximate scores of sel_idx
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     void* __restrict__ out,         // [B*Hq, 128] storage type when nsplit == 1
-    int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag, Paging pg) {
+    int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag, Paging pg,
+    int xcd_group_blocks) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;           // lanes per row: 16 (bf16) or 32 (fp32)
@@ -39,7 +40,25 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int c = lane % LPRV, rg = lane / LPRV;
-  const int head0 = blockIdx.y * NH;              // first query head, flattened over batch
+  // Which (split, head) this block is.  Blocks go to the 8 XCDs round-robin in launch order
+  // and each XCD has its own L2.  Query heads that read the same KV head of the same sequence
+  // (the G heads of a group when every head selects for itself, and the tokens of one
+  // sequence when a step brings several) pick largely the same rows, so their blocks are
+  // renumbered to land on one XCD, next to each other in time.  xcd_group_blocks = blocks of
+  // one such set (0: launch order as is; the host asks for it only when the number of sets
+  // is a multiple of 8).
+  int bx = blockIdx.x, by = blockIdx.y;
+  if (xcd_group_blocks > 0) {
+    const int v = by * nsplit + bx;
+    const int xcd = v & 7, j = v >> 3;
+    const int set = (j / xcd_group_blocks) * 8 + xcd, m = j % xcd_group_blocks;
+    const int member = m / nsplit;                 // (token, head of the group)
+    const int Hkv = Hq / Gq, tokens = max(rag.queries, 1);
+    const int seq = set / Hkv, hkv = set % Hkv;
+    by = ((seq * tokens + member / Gq) * Hkv + hkv) * Gq + member % Gq;
+    bx = m % nsplit;
+  }
+  const int head0 = by * NH;              // first query head, flattened over batch
   const int bidx = head0 / Hq;
   const int kv_unit = bidx * (Hq / Gq) + (head0 % Hq) / Gq;
 
@@ -48,18 +67,18 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   // the neutral partial (max -big, sum 0).
   const int n = GATHER ? seq_keep(rag, bidx, n_max, seq_rows(rag, bidx, S_max))
                        : seq_rows(rag, bidx, n_max);
-  const int r0 = blockIdx.x * rows_per_block;
+  const int r0 = bx * rows_per_block;
   const int r1 = min(n, r0 + rows_per_block);
 
   // a paged cache: the list in LDS holds rows of the pool and the slabs are addressed from their start
   const bool paged = GATHER && pg.table != nullptr;
   const int cache_b = bidx / max(rag.queries, 1);
   if constexpr (GATHER) {
-    const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
+    const int32_t* idx = sel_idx + (size_t)by * n_max;
     for (int i = tid; i < r1 - r0; i += kAttThreads) {
       const int pos = idx[r0 + i];
       s_idx[i] = paged ? (int32_t)cache_row(pg, cache_b, kv_unit % (Hq / Gq), Hq / Gq, S_cap, pos) : pos;
-      if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)blockIdx.y * n_max + r0 + i];
+      if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)by * n_max + r0 + i];
     }
     __syncthreads();
   }
@@ -97,7 +116,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     if (nsplit == 1) {
       T::store1(static_cast<ST*>(out) + head * kD + col, os / ls);
     } else {
-      float* pr = partial + (head * nsplit + blockIdx.x) * kPartialStride;
+      float* pr = partial + (head * nsplit + bx) * kPartialStride;
       pr[col] = os;
       if (col == 0) {
         pr[kD] = mn;
@@ -153,18 +172,19 @@ static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block,
                                    const void* k_b, const void* v, const void* qv,
                                    const int32_t* sel_idx, const float* sel_score, float* partial,
                                    void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
-                                   const Ragged& rg, const Paging& pg, hipStream_t st) {
+                                   const Ragged& rg, const Paging& pg, int xcd_group_blocks,
+                                   hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
   // (d = 128, Exact-TopK of Section 5: it is the whole logit and no key is read again)
   constexpr bool kCanReuse = GATHER && NH == 1;
   if (kCanReuse && sel_score != nullptr) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks);
   } else {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, false>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks);
   }
   return hipGetLastError();
 }
@@ -174,10 +194,12 @@ static hipError_t launch_attend_t(int NH, int blocks_y, int nsplit, int rows_per
                                   const void* k_a, const void* k_b, const void* v, const void* qv,
                                   const int32_t* sel_idx, const float* sel_score, float* partial,
                                   void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
-                                  const Ragged& rg, const Paging& pg, hipStream_t st) {
+                                  const Ragged& rg, const Paging& pg, int xcd_group_blocks,
+                                  hipStream_t st) {
 #define LOKI_ATT(NHV)                                                                          \
   return launch_attend_nh<T, NHV, GATHER>(blocks_y, nsplit, rows_per_block, k_a, k_b, v, qv,   \
-                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, st)
+                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, \
+                                          xcd_group_blocks, st)
   switch (NH) {
     case 1: LOKI_ATT(1);
     case 2: LOKI_ATT(2);
@@ -199,11 +221,16 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
   const int blocks_y = s.B * s.Hq / NH;
   const int rpb = div_up(s.k, nsplit);
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
+  // query heads that read the same cached KV head share most rows: keep their blocks on one
+  // XCD (see attend_kernel)
+  const int tokens = s.rg.queries > 1 ? s.rg.queries : 1;
+  const int sharers = tokens * s.G;
+  const int xcd = (NH == 1 && sharers > 1 && (s.B / tokens * s.Hkv) % 8 == 0) ? sharers * nsplit : 0;
   if (s.dtype == 0)
     return launch_attend_t<F32, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, st);
+                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, st);
   return launch_attend_t<BF16, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, st);
+                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, st);
 }
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
@@ -213,9 +240,9 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)
     return launch_attend_t<F32, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, st);
+                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, st);
+                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, st);
 }
 
 template <typename T, int NH>
@@ -223,7 +250,7 @@ static hipError_t launch_pca_nh(const Shape& s, int nsplit, int rpb, const float
                                 const void* v, float* partial, void* out, hipStream_t st) {
   hipLaunchKernelGGL((attend_kernel<T, NH, false, false, true>), dim3(nsplit, s.B * s.Hkv),
                      dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, out,
-                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{});
+                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{}, 0);
   return hipGetLastError();
 }
 

@@ -318,22 +318,23 @@ def test_decode_step_replays_from_a_captured_graph(G, mode):
 
 
 # ------------------------------------------------------- several new tokens per sequence --
-@pytest.mark.parametrize("G,dtype,mode,m", [(1, "bf16", 0, 3), (4, "bf16", 0, 3), (4, "bf16", 1, 3),
-                                            (2, "f32", 0, 3), (4, "bf16", 0, 5), (8, "bf16", 1, 3),
-                                            (1, "bf16", 0, 17), (2, "bf16", 1, 9), (8, "bf16", 0, 2)])
-def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m):
+@pytest.mark.parametrize("G,dtype,mode,m,B", [(1, "bf16", 0, 3, 3), (4, "bf16", 0, 3, 3), (4, "bf16", 1, 3, 3),
+                                              (2, "f32", 0, 3, 3), (4, "bf16", 0, 5, 3), (8, "bf16", 1, 3, 3),
+                                              (1, "bf16", 0, 17, 3), (2, "bf16", 1, 9, 3), (8, "bf16", 0, 2, 3),
+                                              (4, "bf16", 0, 3, 4), (2, "f32", 0, 2, 4), (1, "bf16", 0, 4, 4)])
+def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m, B):
     """queries_per_seq = m (chunked / speculative decoding): token j of a sequence is appended
     at its own row and attends up to and including it; entries of one sequence share its
     cache.  Same protocol as the single-token cases.  On a bf16 cache the m G query heads of
     a KV head are scored as tiles of 16 columns: the cases cover a partly filled tile, two
-    tiles, and a last tile with one token."""
-    B = 3
+    tiles, and a last tile with one token.  With 4 sequences (8 cached KV heads) the gather
+    renumbers its blocks per XCD."""
     w = synth.Workload(f"multi_g{G}", B, 2 * G, 2, 128, 2500, dtype, 32, 400, seed=14000 + G)
     wq = w.replace(B=B * m)
     x = synth.make_inputs(w)
     xq = synth.make_inputs(wq.replace(S=8))   # only its q is used
     st = synth.make_step_inputs(wq, x["P"])    # k_new, v_new for B m entries
-    rows = np.array([2500, 700, 1337])         # rows of each sequence after the chunk
+    rows = np.array([2500, 700, 1337, 2011][:B])   # rows of each sequence after the chunk
     lens = np.array([rows[b] - (m - 1 - j) for b in range(B) for j in range(m)], np.int32)
     ks = np.maximum(1, (w.k * lens.astype(np.int64)) // w.S).astype(np.int32)
     say(f"case {w} m {m} mode {mode} lens {lens.tolist()} ks {ks.tolist()}")

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
     void* __restrict__ out,         // [B*Hq, 128] storage type when nsplit == 1
     int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag, Paging pg,
-    int xcd_group_blocks) {
+    int xcd_group_blocks, int xcd_sets) {
   using ST = typename T::store_t;
   constexpr int EPC = T::EPC;
   constexpr int LPRV = kD / EPC;           // lanes per row: 16 (bf16) or 32 (fp32)
@@ -45,13 +45,14 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   // (the G heads of a group when every head selects for itself, and the tokens of one
   // sequence when a step brings several) pick largely the same rows, so their blocks are
   // renumbered to land on one XCD, next to each other in time.  xcd_group_blocks = blocks of
-  // one such set (0: launch order as is; the host asks for it only when the number of sets
-  // is a multiple of 8).
+  // one such set (0: launch order as is), xcd_sets = number of sets; the grid is rounded up to
+  // a multiple of 8 sets and the blocks of the sets that do not exist leave at once.
   int bx = blockIdx.x, by = blockIdx.y;
   if (xcd_group_blocks > 0) {
     const int v = by * nsplit + bx;
     const int xcd = v & 7, j = v >> 3;
     const int set = (j / xcd_group_blocks) * 8 + xcd, m = j % xcd_group_blocks;
+    if (set >= xcd_sets) return;  // uniform for the block, before any barrier
     const int member = m / nsplit;                 // (token, head of the group)
     const int Hkv = Hq / Gq, tokens = max(rag.queries, 1);
     const int seq = set / Hkv, hkv = set % Hkv;
@@ -173,18 +174,18 @@ static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block,
                                    const int32_t* sel_idx, const float* sel_score, float* partial,
                                    void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
                                    const Ragged& rg, const Paging& pg, int xcd_group_blocks,
-                                   hipStream_t st) {
+                                   int xcd_sets, hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
   // (d = 128, Exact-TopK of Section 5: it is the whole logit and no key is read again)
   constexpr bool kCanReuse = GATHER && NH == 1;
   if (kCanReuse && sel_score != nullptr) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
   } else {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, false>), dim3(nsplit, blocks_y),
                        dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks);
+                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
   }
   return hipGetLastError();
 }
@@ -195,11 +196,11 @@ static hipError_t launch_attend_t(int NH, int blocks_y, int nsplit, int rows_per
                                   const int32_t* sel_idx, const float* sel_score, float* partial,
                                   void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
                                   const Ragged& rg, const Paging& pg, int xcd_group_blocks,
-                                  hipStream_t st) {
+                                  int xcd_sets, hipStream_t st) {
 #define LOKI_ATT(NHV)                                                                          \
   return launch_attend_nh<T, NHV, GATHER>(blocks_y, nsplit, rows_per_block, k_a, k_b, v, qv,   \
                                           sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, \
-                                          xcd_group_blocks, st)
+                                          xcd_group_blocks, xcd_sets, st)
   switch (NH) {
     case 1: LOKI_ATT(1);
     case 2: LOKI_ATT(2);
@@ -218,19 +219,24 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
   const int NH = (select_mode == 1) ? s.G : 1;
   if (attend_mfma_applies(s, NH))
     return launch_gather_mfma(s, nsplit, qhat, klo, khi, v, sel_idx, partial, out, st);
-  const int blocks_y = s.B * s.Hq / NH;
+  int blocks_y = s.B * s.Hq / NH;
   const int rpb = div_up(s.k, nsplit);
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   // query heads that read the same cached KV head share most rows: keep their blocks on one
   // XCD (see attend_kernel)
   const int tokens = s.rg.queries > 1 ? s.rg.queries : 1;
   const int sharers = tokens * s.G;
-  const int xcd = (NH == 1 && sharers > 1 && (s.B / tokens * s.Hkv) % 8 == 0) ? sharers * nsplit : 0;
+  const int sets = s.B / tokens * s.Hkv;
+  int xcd = 0;
+  if (NH == 1 && sharers > 1 && (long long)div_up(sets, 8) * 8 * sharers <= 65535) {
+    xcd = sharers * nsplit;
+    blocks_y = div_up(sets, 8) * 8 * sharers;
+  }
   if (s.dtype == 0)
     return launch_attend_t<F32, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, st);
+                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
   return launch_attend_t<BF16, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, st);
+                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
 }
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
@@ -240,9 +246,9 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)
     return launch_attend_t<F32, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, st);
+                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, st);
+                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
 }
 
 template <typename T, int NH>
@@ -250,7 +256,7 @@ static hipError_t launch_pca_nh(const Shape& s, int nsplit, int rpb, const float
                                 const void* v, float* partial, void* out, hipStream_t st) {
   hipLaunchKernelGGL((attend_kernel<T, NH, false, false, true>), dim3(nsplit, s.B * s.Hkv),
                      dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, out,
-                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{}, 0);
+                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{}, 0, 0);
   return hipGetLastError();
 }
 

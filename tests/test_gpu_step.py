@@ -402,27 +402,25 @@ def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m, B):
     say(f"   max_err {max_err:.3e}")
 
 
-@pytest.mark.parametrize("Hq,Hkv,mode,m", [(32, 8, 0, 4), (32, 8, 1, 4), (32, 8, 1, 3), (32, 32, 0, 4)])
-def test_multi_token_step_equals_single_token_steps_at_full_size(Hq, Hkv, mode, m):
-    """At a size the oracle cannot walk (16 sequences, S = 8192, k = 1024): one step with
-    queries_per_seq = m gives what m single-token steps one after the other give (those are
-    the steps the oracle covers above).  With grouped heads both forms score a column with the
-    same matrix-core arithmetic, so the index lists must be identical; with one head per KV
-    head the single-token form scores in fp32 vector order, and lists may differ by swaps at
-    the threshold.  Outputs agree to bf16 rounding (the two forms split the k rows over a
-    different number of blocks)."""
-    Bs, S, d, k, G = 16, 8192, 32, 1024, Hq // Hkv
+def _multi_token_vs_single_token_steps(Bs, Hq, Hkv, S, d, k, mode, m, seed):
+    """One step with queries_per_seq = m against m single-token steps one after the other (the
+    form the oracle covers), on random bf16 caches.  Index lists must be identical when both
+    forms score with the same matrix-core arithmetic (grouped heads, d a power of two above
+    16); otherwise the two score kernels differ in accumulation order and a list may differ by
+    swaps at the threshold.  Outputs agree to the output tolerance (the two forms split the k
+    rows over a different number of blocks)."""
+    G = Hq // Hkv
     tdt = torch.bfloat16
-    g = torch.Generator(device="cuda").manual_seed(77 + Hq + mode + m)
+    g = torch.Generator(device="cuda").manual_seed(seed)
     rnd = lambda *shape, scale=1.0: (scale * torch.randn(shape, device="cuda", generator=g)).to(tdt)
     klo0, khi0, v0 = rnd(Bs, Hkv, S, d, scale=2.0), rnd(Bs, Hkv, S, 128 - d, scale=0.5), rnd(Bs, Hkv, S, 128)
     q, k_new, v_new = rnd(Bs, m, Hq, 128), rnd(Bs, m, Hkv, 128), rnd(Bs, m, Hkv, 128)
     Pm = torch.linalg.qr(torch.randn((Hkv, 128, 128), device="cuda", generator=g))[0].contiguous()
-    rows = torch.randint(S // 3, S + 1, (Bs,), device="cuda", generator=g, dtype=torch.int32)
+    rows = torch.randint(max(S // 3, m), S + 1, (Bs,), device="cuda", generator=g, dtype=torch.int32)
     rows[0] = S
     lens = (rows[:, None] - (m - 1 - torch.arange(m, device="cuda", dtype=torch.int32))[None, :]).contiguous()
     ks = torch.clamp((k * lens.long()) // S, min=1).to(torch.int32).contiguous()
-    say(f"Hq {Hq} Hkv {Hkv} mode {mode} m {m} rows {rows.tolist()}")
+    say(f"Bs {Bs} Hq {Hq} Hkv {Hkv} S {S} d {d} k {k} mode {mode} m {m} rows {rows.tolist()}")
     lay = api.make_layout(Bs, Hq, Hkv, 128, d, S, tdt)
     laym = api.make_layout(Bs * m, Hq, Hkv, 128, d, S, tdt)
     ws = api.alloc_workspace(laym, S, d, k, mode)
@@ -448,7 +446,8 @@ def test_multi_token_step_equals_single_token_steps_at_full_size(Hq, Hkv, mode, 
     for a, b in zip(ca, cb):
         assert torch.equal(a, b)  # the appended rows
     assert torch.isfinite(out_a.float()).all()
-    if G > 1:
+    same_arithmetic = G > 1 and d > 16 and (d & (d - 1)) == 0
+    if same_arithmetic:
         assert torch.equal(idx_a, idx_b)
     else:
         ia, ib = idx_a.cpu().numpy(), idx_b.cpu().numpy()
@@ -462,6 +461,29 @@ def test_multi_token_step_equals_single_token_steps_at_full_size(Hq, Hkv, mode, 
     err = float((out_a.float() - out_b.float()).abs().max())
     say(f"   max |out difference| {err:.3e}")
     assert err <= OUT_TOL["bf16"]
+
+
+@pytest.mark.parametrize("Hq,Hkv,mode,m", [(32, 8, 0, 4), (32, 8, 1, 4), (32, 8, 1, 3), (32, 32, 0, 4)])
+def test_multi_token_step_equals_single_token_steps_at_full_size(Hq, Hkv, mode, m):
+    """At a size the oracle cannot walk: 16 sequences, S = 8192, k = 1024."""
+    _multi_token_vs_single_token_steps(16, Hq, Hkv, 8192, 32, 1024, mode, m, 77 + Hq + mode + m)
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_multi_token_step_equals_single_token_steps_on_random_shapes(seed):
+    """Odd shapes: any number of sequences and KV heads (the XCD renumbering of the gather
+    pads the grid), 1 to 8 heads per KV head, 2 to 9 tokens (partly filled and several score
+    tiles), slab widths on both score kernels, either selection mode."""
+    rng = np.random.default_rng(5000 + seed)
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    Bs = int(rng.integers(1, 8))
+    m = int(rng.integers(2, 10))
+    S = int(rng.integers(300, 5000))
+    d = int(rng.choice([8, 16, 24, 32, 64]))
+    k = int(rng.integers(1, max(2, S // 3)))
+    mode = int(rng.integers(0, 2))
+    _multi_token_vs_single_token_steps(Bs, Hkv * G, Hkv, S, d, k, mode, m, 6000 + seed)
 
 
 # -------------------------------------------------------------------------- paged cache --

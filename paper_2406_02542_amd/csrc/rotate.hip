@@ -85,8 +85,8 @@ __global__ __launch_bounds__(kRotThreads) void rotate_kernel(
 // significant bits, so every product is exact and only the fp32 accumulation order differs
 // from the vector kernel) and parked in LDS already in operand layout, 96 KiB.  Every wave
 // owns whole 16-row tiles (each key row is read from HBM once), prefetches its next tile while
-// the 96 matrix instructions of the current one run, and packs pairs of neighbouring columns
-// so that results leave as 4-byte stores.
+// the 96 matrix instructions of the current one run, packs pairs of neighbouring columns into
+// a staging tile in LDS, and writes whole rows from there.
 typedef __bf16 rot_bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float rot_f32x4_t __attribute__((ext_vector_type(4)));
 
@@ -105,6 +105,9 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
     uint16_t* __restrict__ khi, int Hkv, int S_cap, int d, int pos, int n_new, int n_items,
     int items_per_block, Paging pg) {
   __shared__ uint4 s_B[kRotTerms][4][8][64];  // [term][32-column step of K][16-column block of Khat][lane]
+  // per wave: the rotated tiles of a trip, bf16, before they leave as whole rows (with three
+  // terms the two arrays fill the 160 KiB of a CU exactly)
+  __shared__ uint4 s_stage[kRotMfmaWaves][kRotMfmaTPW * 16 * 16];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: row bases stay scalar
   const int kgrp = lane >> 4, r16 = lane & 15;
@@ -162,24 +165,18 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
   constexpr int kStride = 16 * TPW * kRotMfmaWaves;  // rows the block covers per trip
 
   // One trip: TPW tiles starting at row t0; FULL = every row of them exists.
+  // Results go through the wave's staging tile so that every store instruction writes whole
+  // rows (16 bytes per lane, four rows per instruction); stored straight from the accumulator
+  // layout a row leaves in 32-byte pieces spread over the trip, which measured 10 % slower.
+  // A row of the tile is 256 bytes = 8 units of 32 bytes; unit c of row r sits at unit
+  // c ^ ((r >> 1) & 7), which keeps both the 4-byte writes (8 rows of equal parity x 8 words)
+  // and the 16-byte reads off each other's banks without padding.
+  typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+  unsigned char* stage = reinterpret_cast<unsigned char*>(&s_stage[wave][0]);
   auto trip = [&](int t0, const uint4 (&raw)[TPW][4], auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
-    // rows this lane stores per tile: items +4*kgrp + {0,1} (even column) or {2,3} (odd column)
+    // rows this lane holds per tile: +4*kgrp + {0,1} (even column) or {2,3} (odd column)
     const int i0 = (r16 & 1) * 2;
-    size_t row[TPW][2];
-    bool ok[TPW][2];
-#pragma unroll
-    for (int u = 0; u < TPW; ++u)
-#pragma unroll
-      for (int ii = 0; ii < 2; ++ii) {
-        const int it = t0 + 16 * u + 4 * kgrp + i0 + ii;
-        ok[u][ii] = FULL || it < item1;
-        const int itb = min(t0, item1 - 1);
-        int b, r;
-        split_item(itb, min(it, item1 - 1) - itb, b, r);
-        if constexpr (PAGED) row[u][ii] = (size_t)cache_row(pg, b, h, Hkv, S_cap, pos + r);
-        else row[u][ii] = (size_t)(b * Hkv + h) * S_cap + pos + r;
-      }
     // The operands in LDS never change, but they must be re-read for every trip: hoisted out of
     // the loop, all 96 of them would live in registers and spill.  An offset the compiler
     // cannot see through (always 0) keeps the reads inside the trip.
@@ -212,7 +209,6 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
       for (int u = 0; u < TPW; ++u)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-          const int colb = 16 * (nb + half) + (r16 & ~1);  // even column of the pair
           // neighbour lane (r16 ^ 1) holds the other column of the pair for the same rows
           float other[4];
 #pragma unroll
@@ -223,18 +219,34 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
             const float mine = (r16 & 1) ? acc[u][half][2 + ii] : acc[u][half][ii];
             const float lo_col = (r16 & 1) ? other[i] : mine;
             const float hi_col = (r16 & 1) ? mine : other[i];
-            const uint32_t packed = BF16::round2(lo_col, hi_col);
-            uint32_t* p32 =
-                (colb < d) ? reinterpret_cast<uint32_t*>(klo + row[u][ii] * d + colb)
-                           : reinterpret_cast<uint32_t*>(khi + row[u][ii] * (kD - d) + (colb - d));
-            if (FULL) {
-              *p32 = packed;
-            } else if (ok[u][ii]) {
-              *p32 = packed;
-            }
+            const int rt = 4 * kgrp + i;  // row of the tile
+            const int unit = (nb + half) ^ ((rt >> 1) & 7);
+            *reinterpret_cast<uint32_t*>(stage + (u * 16 + rt) * 256 + unit * 32 + (r16 & ~1) * 2) =
+                BF16::round2(lo_col, hi_col);
           }
         }
     }
+    __builtin_amdgcn_wave_barrier();
+    // whole rows out: lane l takes chunk l%16 (8 columns) of row l/16 + 4*pass
+    const int itb = min(t0, item1 - 1);
+#pragma unroll
+    for (int u = 0; u < TPW; ++u)
+#pragma unroll
+      for (int pass = 0; pass < 4; ++pass) {
+        const int rt = 4 * pass + kgrp, c = r16;
+        const int it = t0 + 16 * u + rt;
+        int b, r;
+        split_item(itb, min(it, item1 - 1) - itb, b, r);
+        size_t row;
+        if constexpr (PAGED) row = (size_t)cache_row(pg, b, h, Hkv, S_cap, pos + r);
+        else row = (size_t)(b * Hkv + h) * S_cap + pos + r;
+        const int unit = (c >> 1) ^ ((rt >> 1) & 7);
+        const u32x4_t val = *reinterpret_cast<const u32x4_t*>(stage + (u * 16 + rt) * 256 + unit * 32 + (c & 1) * 16);
+        const int col = 8 * c;
+        uint16_t* dst = (col < d) ? klo + row * d + col : khi + row * (kD - d) + (col - d);
+        if (FULL || it < item1) *reinterpret_cast<u32x4_t*>(dst) = val;
+      }
+    __builtin_amdgcn_wave_barrier();
   };
 
   uint4 nxt[TPW][4];

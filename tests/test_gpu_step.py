@@ -499,15 +499,40 @@ def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path)
     between) give bit-identical outputs, index lists and appended rows, on either kernel
     sequence: the page table changes where a row lives, not what is computed.  The contiguous
     reference is itself checked against the oracle by the tests above."""
-    B = 3
-    w = synth.Workload(f"paged_g{G}", B, 2 * G, 2, 128, 3000, dtype, 32, 500, seed=15000 + G)
+    w = synth.Workload(f"paged_g{G}", 3, 2 * G, 2, 128, 3000, dtype, 32, 500, seed=15000 + G)
+    _paged_vs_contiguous(w, mode, page_rows, m, path, [3000, 800, 1537])
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_paged_cache_equals_contiguous_cache_on_random_shapes(seed):
+    rng = np.random.default_rng(7000 + seed)
+    Hkv = int(rng.choice([1, 2, 3, 4]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    B = int(rng.integers(1, 6))
+    m = int(rng.choice([1, 1, 2, 3, 6]))
+    S = int(rng.integers(400, 5000))
+    d = int(rng.choice([8, 16, 32, 64]))
+    dtype = "bf16" if rng.random() < 0.75 else "f32"
+    k = int(rng.integers(1, max(2, min(S // 3, 2000))))
+    mode = int(rng.integers(0, 2))
+    page_rows = int(rng.choice([256, 512, 1024, 2048]))
+    fused_ok = G == 1 and m == 1 and (S + page_rows - 1) // page_rows <= 32
+    path = api.PATH_FUSED if (fused_ok and rng.random() < 0.5) else api.PATH_SPLIT
+    rows = [S] + [int(rng.integers(max(m, 2), S + 1)) for _ in range(B - 1)]
+    w = synth.Workload(f"paged_rnd{seed}", B, Hkv * G, Hkv, 128, S, dtype, d, k, seed=17000 + seed)
+    _paged_vs_contiguous(w, mode, page_rows, m, path, rows)
+
+
+def _paged_vs_contiguous(w, mode, page_rows, m, path, rows):
+    B, G, dtype = w.B, w.G, w.dtype
     x = synth.make_inputs(w)
     wq = w.replace(B=B * m)
     st = synth.make_step_inputs(wq, x["P"])
     q = to_dev(synth.make_inputs(wq.replace(S=8))["q"], dtype)
-    rows = np.array([3000, 800, 1537])
+    rows = np.array(rows)
     lens = np.array([rows[b] - (m - 1 - j) for b in range(B) for j in range(m)], np.int32)
     ks = np.maximum(1, (w.k * lens.astype(np.int64)) // w.S).astype(np.int32)
+    say(f"paged case {w} mode {mode} page_rows {page_rows} m {m} path {path:#x} rows {rows.tolist()}")
     tdt = TORCH_DT[dtype]
     pages_per_seq = (w.S + page_rows - 1) // page_rows
     S_cap = pages_per_seq * page_rows
@@ -548,7 +573,6 @@ def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path)
     api.loki_decode_step(lay, q, P, pklo, pkhi, pv, w.S, w.d, w.k, mode | path, ws, out_p, idx_p,
                          page_table=table, page_rows=page_rows, n_pages=n_pages, **common)
     torch.cuda.synchronize()
-    say(f"paged G {G} {dtype} mode {mode} page_rows {page_rows} m {m}: n_pages {n_pages}")
     assert torch.isfinite(out_c.float()).all()
     assert torch.equal(out_p, out_c)
     assert torch.equal(idx_p, idx_c)

@@ -76,8 +76,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
   const int cache_b = bidx / max(rag.queries, 1);
   if constexpr (GATHER) {
     const int32_t* idx = sel_idx + (size_t)by * n_max;
+    const int S_b = seq_rows(rag, bidx, S_max);
     for (int i = tid; i < r1 - r0; i += kAttThreads) {
-      const int pos = idx[r0 + i];
+      const int pos = min(max(idx[r0 + i], 0), S_b - 1);  // a bad list entry cannot leave the unit's rows
       s_idx[i] = paged ? (int32_t)cache_row(pg, cache_b, kv_unit % (Hq / Gq), Hq / Gq, S_cap, pos) : pos;
       if constexpr (REUSE_LO) s_a[i] = sel_score[(size_t)by * n_max + r0 + i];
     }

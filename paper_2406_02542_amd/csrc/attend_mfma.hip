@@ -75,8 +75,9 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
   if constexpr (GATHER) {
     const int32_t* idx = sel_idx + (size_t)blockIdx.y * n_max;
     const int cache_b = bidx / max(rg.queries, 1);
+    const int S_b = seq_rows(rg, bidx, S_max);
     for (int i = tid; i < r1 - r0; i += kAmThreads) {
-      const int pos = idx[r0 + i];
+      const int pos = min(max(idx[r0 + i], 0), S_b - 1);  // a bad list entry cannot leave the unit's rows
       s_idx[i] = paged ? (int32_t)cache_row(pg, cache_b, kv_unit % Hkv, Hkv, S_cap, pos) : pos;
     }
     __syncthreads();

@@ -272,10 +272,6 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
   const long long n_items_ll = (long long)s.B * n_new;
   if (n_items_ll > 0x7fffffffLL) return hipErrorInvalidValue;
   const int n_items = (int)n_items_ll;
-  int ipb = 512;
-  if (n_items < ipb) ipb = ((n_items + kRotTile - 1) / kRotTile) * kRotTile;
-  dim3 grid((n_items + ipb - 1) / ipb, s.Hkv);
-  const size_t lds = 0;  // LDS is declared statically in the kernels
   if (s.dtype == 1) {
     // One block per CU where the rows allow it: a block's set-up (P_h split into LDS) and its
     // tail are paid once per block, and on the benchmark prefill 8192 rows per block (one round
@@ -298,15 +294,13 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
                          s.pg);
     return hipGetLastError();
   }
-  if (s.dtype == 0) {
-    hipLaunchKernelGGL(rotate_kernel<F32>, grid, dim3(kRotThreads), lds, st,
-                       static_cast<const float*>(k_new), P, static_cast<float*>(klo),
-                       static_cast<float*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb, s.pg);
-  } else {
-    hipLaunchKernelGGL(rotate_kernel<BF16>, grid, dim3(kRotThreads), lds, st,
-                       static_cast<const uint16_t*>(k_new), P, static_cast<uint16_t*>(klo),
-                       static_cast<uint16_t*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb, s.pg);
-  }
+  // fp32 caches: the vector kernel (P_h in LDS as fp32)
+  int ipb = 512;
+  if (n_items < ipb) ipb = ((n_items + kRotTile - 1) / kRotTile) * kRotTile;
+  const dim3 grid((n_items + ipb - 1) / ipb, s.Hkv);
+  hipLaunchKernelGGL(rotate_kernel<F32>, grid, dim3(kRotThreads), 0, st,
+                     static_cast<const float*>(k_new), P, static_cast<float*>(klo),
+                     static_cast<float*>(khi), s.Hkv, s.S_cap, s.d, pos, n_new, n_items, ipb, s.pg);
   return hipGetLastError();
 }
 

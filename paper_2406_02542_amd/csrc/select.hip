@@ -266,6 +266,7 @@ __host__ __device__ inline int mb_meta_stride(int nc) { return 4 * nc + 8; }
 template <int kMbStreamThreads, typename F>
 __device__ __forceinline__ void mb_stream_keys(const float* __restrict__ a, int n, F f) {
   const int tid = threadIdx.x;
+  if (n <= 0) return;  // (a negative n would make the tail loop below re-read rows before `a`)
   if ((reinterpret_cast<uintptr_t>(a) & 15u) == 0) {
     const int n4 = n >> 2;  // whole 16-byte words
     const float4* a4 = reinterpret_cast<const float4*>(a);
@@ -303,7 +304,7 @@ __global__ __launch_bounds__(kMbStreamThreads) void mb_hist_kernel(const float* 
   __shared__ uint32_t s_hist[2048];
   const int tid = threadIdx.x, chunk = blockIdx.x, head = blockIdx.y;
   const int S = seq_rows(rg, head / heads_per_seq, S_max);
-  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);  // <= 0 past a short sequence's end
+  const int c0 = chunk * kMbChunk, n = max(min(S - c0, kMbChunk), 0);  // 0 past a short sequence's end
   for (int i = tid; i < 2048; i += kMbStreamThreads) s_hist[i] = 0u;
   __syncthreads();
   mb_stream_keys<kMbStreamThreads>(scores + (size_t)head * S_max + c0, n,
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(kMbStreamThreads) void mb_collect_kernel(const floa
   __shared__ uint32_t s_ncand, s_gt;
   const int tid = threadIdx.x, lane = tid & 63, chunk = blockIdx.x, head = blockIdx.y;
   const int S = seq_rows(rg, head / heads_per_seq, S_max);
-  const int c0 = chunk * kMbChunk, n = min(S - c0, kMbChunk);
+  const int c0 = chunk * kMbChunk, n = max(min(S - c0, kMbChunk), 0);  // 0 past a short sequence's end
   uint32_t* m = meta + (size_t)head * mb_meta_stride(nc);
   const uint32_t bin1 = m[4 * nc];
   const int cap = mb_cand_cap(nc);

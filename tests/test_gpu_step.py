@@ -24,13 +24,24 @@ def say(msg):
     print(msg, flush=True)
 
 
-def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=None, use_ks=True):
+def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=None, use_ks=True,
+                  boost_tail=0):
     x = synth.make_inputs(w)
     st = synth.make_step_inputs(w, x["P"], ragged=ragged)
     if lens is not None:
         st["seq_lens"] = np.asarray(lens, np.int32)
         st["ks"] = np.minimum(np.maximum(1, (w.k * st["seq_lens"].astype(np.int64)) // w.S),
                               np.minimum(st["seq_lens"], w.k)).astype(np.int32)
+    if boost_tail:
+        # the last `boost_tail` rows of every sequence point along the first query head's rotated
+        # query (low-rank columns), so they are certain to be selected by that head
+        for b in range(w.B):
+            n = int(st["seq_lens"][b])
+            for h in range(w.Hkv):
+                qhat = O.rotate_query(x["q"][b, h * w.G], x["P"][h])
+                row = np.zeros(w.D)
+                row[:w.d] = 8.0 * qhat[:w.d] / max(np.linalg.norm(qhat[:w.d]), 1e-9)
+                x["khat"][b, h, max(0, n - boost_tail):n] = O.to_storage(row, w.dtype)
     if ks is not None:
         st["ks"] = np.asarray(ks, np.int32)
     lens_np, ks_np = st["seq_lens"], st["ks"]
@@ -175,6 +186,16 @@ def test_step_long_sequences_multiblock_select(mode):
     the first chunk, one ending just past a chunk boundary."""
     w = synth.Workload("step_long", 3, 4, 1, 128, 40000, "bf16", 16, 2500, seed=9700)
     run_step_case(w, mode, True, True, lens=[40000, 9000, 16385 + 16384])
+
+
+@pytest.mark.parametrize("append", [False, True])
+@pytest.mark.parametrize("mode", [0, 1])
+def test_step_multiblock_select_short_sequences_not_multiple_of_four(mode, append):
+    """Sequences that end before the last chunk of the multi-block select and whose length is
+    not a multiple of four: the chunks past their end must count no row (they once re-read the
+    sequence's last rows, which moved the threshold and left ranks of the index list unwritten)."""
+    w = synth.Workload("step_long_odd", 4, 4, 1, 128, 40000, "bf16", 16, 2500, seed=9710)
+    run_step_case(w, mode, True, append, lens=[40000, 9001, 16387, 3], boost_tail=4)
 
 
 # ------------------------------------------------------------------- identities and errors --

@@ -53,7 +53,9 @@ typedef enum {
                                    Hq / Hkv not in {1, 2, 4, 8}, B * Hq > 65535           */
   LOKI_ERR_ALIGNMENT = 3,       /* a base pointer is not 16-byte aligned                  */
   LOKI_ERR_WORKSPACE = 4,       /* workspace smaller than loki_workspace_bytes reports    */
-  LOKI_ERR_HIP = 5              /* the HIP runtime reported an error at launch            */
+  LOKI_ERR_HIP = 5,             /* the HIP runtime reported an error at launch            */
+  LOKI_ERR_SCRATCH_LIMIT = 6    /* loki_decode_attn_static: the shape needs more workspace
+                                   than LOKI_STATIC_SCRATCH_BYTES                         */
 } loki_status;
 
 enum { LOKI_F32 = 0, LOKI_BF16 = 1 };
@@ -147,6 +149,28 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
                      const void* khi, const void* v, int S, int d, int k, int select_mode,
                      void* workspace, size_t workspace_bytes, void* out, int32_t* out_idx,
                      void* stream);
+
+/*
+ * loki_decode_attn for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * scores, index lists, rotated queries and split partials go to a buffer of
+ * LOKI_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy per GPU, held
+ * until the process ends); the call allocates and frees nothing.  Arguments and results as
+ * loki_decode_attn, without workspace / workspace_bytes.
+ *   - A shape whose loki_workspace_bytes(layout, S, d, k, select_mode) exceeds
+ *     LOKI_STATIC_SCRATCH_BYTES is refused with LOKI_ERR_SCRATCH_LIMIT; nothing is enqueued.
+ *   - The device the work runs on must be the calling thread's current device.  The first call
+ *     on a device looks the buffer's address up (hipGetSymbolAddress); make that call before
+ *     starting a graph capture.
+ *   - All calls on one GPU share that GPU's buffer, which keeps the previous call's contents
+ *     (no kernel relies on them; nothing has to be cleared).  Calls that may run at the same
+ *     time on one GPU (different streams) race on it: serialise them, or use loki_decode_attn
+ *     with separate workspaces.
+ */
+enum { LOKI_STATIC_SCRATCH_BYTES = 64 << 20 };
+int loki_decode_attn_static(const loki_layout* layout, const void* q, const float* P,
+                            const void* klo, const void* khi, const void* v, int S, int d, int k,
+                            int select_mode, void* out, int32_t* out_idx, void* stream);
 
 /*
  * Section 2, Eq. 1: full attention over all S rows, the baseline Loki is compared

@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
     L.loki_rotate_keys_paged.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp]
     L.loki_decode_attn.restype = i32
     L.loki_decode_attn.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, sz, vp, vp, vp]
+    L.loki_decode_attn_static.restype = i32
+    L.loki_decode_attn_static.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp]
     L.loki_decode_step.restype = i32
     L.loki_decode_step.argtypes = [LP, vp, vp, vp, vp, vp, i32, i32, i32, i32, vp, vp, sz, vp, vp, vp]
     L.dense_decode_step.restype = i32
@@ -226,6 +228,31 @@ def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
         _ptr(out, "out", dt, nq),
         _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k),
         _stream_ptr(stream)), "loki_decode_attn")
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def loki_decode_attn_static(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
+                            khi: Optional[torch.Tensor], v: torch.Tensor, S: int, d: int, k: int,
+                            select_mode: int, out: torch.Tensor,
+                            out_idx: Optional[torch.Tensor] = None, stream=None) -> None:
+    """loki_decode_attn on the library's built-in scratch buffer (no workspace argument)."""
+    dt = _torch_dtype(layout)
+    rows = layout.B * layout.Hkv
+    nq = layout.B * layout.Hq * layout.D
+    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
+    _check(lib().loki_decode_attn_static(
+        ctypes.byref(layout),
+        _ptr(q, "q", dt, nq),
+        _ptr(P, "P", torch.float32, layout.Hkv * layout.D * layout.D),
+        _ptr(klo, "klo", dt, rows * layout.S_cap * layout.d_split),
+        _ptr(khi, "khi", dt, rows * layout.S_cap * (layout.D - layout.d_split)),
+        _ptr(v, "v", dt, rows * layout.S_cap * layout.D),
+        S, d, k, select_mode,
+        _ptr(out, "out", dt, nq),
+        _ptr(out_idx, "out_idx", torch.int32, layout.B * hsel * k),
+        _stream_ptr(stream)), "loki_decode_attn_static")
 
 
 class StepArgs(ctypes.Structure):

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <new>
 
 #include "launch.h"
@@ -138,6 +139,29 @@ static int check_layout(const loki_layout* L, Shape* s) {
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
+// ---- built-in scratch for callers that cannot allocate (loki_decode_attn_static) -----------
+// Every GPU the library runs on holds its own copy of this array, at its own address, until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress: the
+// device address is looked up once per device (with that device current) and kept, and only
+// that address is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[LOKI_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+static int static_scratch_address(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return LOKI_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return LOKI_ERR_UNSUPPORTED;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+      return LOKI_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // every thread finds the same address
+  }
+  *out = ptr;
+  return LOKI_OK;
+}
+
 }  // namespace loki
 
 using namespace loki;
@@ -178,6 +202,7 @@ const char* loki_status_string(int status) {
     case LOKI_ERR_ALIGNMENT: return "pointer not sufficiently aligned";
     case LOKI_ERR_WORKSPACE: return "workspace too small";
     case LOKI_ERR_HIP: return "HIP runtime error";
+    case LOKI_ERR_SCRATCH_LIMIT: return "shape needs more than the built-in scratch buffer";
     default: return "unknown status";
   }
 }
@@ -359,6 +384,22 @@ int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, c
   return decode_impl(layout, q, P, const_cast<void*>(klo), const_cast<void*>(khi),
                      const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, Paging{},
                      workspace, workspace_bytes, out, out_idx, stream);
+}
+
+int loki_decode_attn_static(const loki_layout* layout, const void* q, const float* P,
+                            const void* klo, const void* khi, const void* v, int S, int d, int k,
+                            int select_mode, void* out, int32_t* out_idx, void* stream) {
+  size_t need = 0;
+  const int rc = loki_workspace_bytes(layout, S, d, k, select_mode, &need);
+  if (rc != LOKI_OK) return rc;
+  if (need > (size_t)LOKI_STATIC_SCRATCH_BYTES) return LOKI_ERR_SCRATCH_LIMIT;
+  void* ptr = nullptr;
+  const int ra = static_scratch_address(&ptr);
+  if (ra != LOKI_OK) return ra;
+  // nothing in the workspace has to start at zero: every kernel writes what the next one reads
+  return decode_impl(layout, q, P, const_cast<void*>(klo), const_cast<void*>(khi),
+                     const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, Paging{}, ptr,
+                     (size_t)LOKI_STATIC_SCRATCH_BYTES, out, out_idx, stream);
 }
 
 int loki_decode_step(const loki_layout* layout, const void* q, const float* P, void* klo, void* khi,

@@ -29,11 +29,26 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E
 
-# HBM bytes per launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy
-# calibration; measured values and commands are in profiles/llama2_7b_fused_decode.md.
-MEASURED_TRAFFIC_BYTES = {
-    "llama2_7b:fused_decode": 194697.7 * 2048 + 128.0 * 1024,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic.md")
+
+
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` on `workload` as recorded in profiles/hbm_traffic.md
+    (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by the plain-copy calibration; the file names the
+    commands and the commit of the kernel sources it was taken at).  Not measured by this run:
+    None when the table has no row for the pair."""
+    try:
+        rows = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None, None
+    for line in rows:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) >= 5 and cells[0] == workload and cells[1] == kernel:
+            try:
+                return float(cells[2]) + float(cells[3]), cells[4]
+            except ValueError:
+                return None, None
+    return None, None
 
 
 def log(msg):
@@ -79,6 +94,143 @@ def cpu_baseline(w, x, select_mode, budget_s=20.0):
             "sample": f"{done} (batch, KV head) unit evaluations of {w.name} "
                       f"({len(units)} units per step) in {dt:.1f} s, scaled to one step"}
 
+def _pct(samples, q):
+    return float(np.percentile(np.asarray(samples, dtype=np.float64), q))
+
+
+def event_timed_steps(torch, step_fn, steps, warmup, stream):
+    """Durations of `steps` back-to-back steps, each from one event on the launch stream to the
+    next, in microseconds, after `warmup` untimed steps (and at least 30 ms of them)."""
+    t_w = time.perf_counter()
+    i = 0
+    while i < warmup or time.perf_counter() - t_w < 0.03:
+        step_fn(i)
+        i += 1
+        if i % 50 == 0:
+            torch.cuda.synchronize()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record(stream)
+    for i in range(steps):
+        step_fn(i)
+        evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) / steps * 1e6
+    per_step = [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(steps)]
+    return per_step, wall_us
+
+
+def kernel_times(api, step_fn, steps):
+    """Mean HIP-event time of every kernel of a step, microseconds, in launch order (the
+    library's profile hook; every launch is read back before the next, so each bracket holds
+    one kernel on an otherwise idle device plus about 2.5 us of event overhead)."""
+    prof = api.Profile()
+    acc, order = {}, []
+    prof.attach()
+    try:
+        for i in range(steps):
+            step_fn(i)
+            for name, ms in prof.read():
+                if name not in acc:
+                    acc[name] = []
+                    order.append(name)
+                acc[name].append(ms)
+    finally:
+        api.Profile.detach()
+        prof.close()
+    return {n: float(np.mean(acc[n])) * 1e3 for n in order}
+
+
+def bench_configs(args, torch, api, synth):
+    """The `configs` array: every other workload of the benchmark list, both select modes where
+    query heads are grouped, and the nine (d, k) points of the large-model sweep.  Inputs come
+    from the same seeded generator as the parity tests; a workload's cache is generated once and
+    the low-rank / residual split is rebuilt on the device per d."""
+    cfgs = synth.paper_configs()
+    plan = [("tiny", [cfgs["tiny"]], (0,)),
+            ("llama3_8b_gqa", [cfgs["llama3_8b_gqa"]], (0, 1)),
+            ("long_gqa", [cfgs["long_gqa"]], (0, 1)),
+            ("large_share", synth.large_share_sweep(), (0, 1))]
+    stream = torch.cuda.current_stream()
+    steps = max(20, args.config_steps)
+    entries = []
+    for name, variants, modes in plan:
+        base = cfgs[name]
+        tdt = torch.float32 if base.dtype == "f32" else torch.bfloat16
+        t0 = time.perf_counter()
+        x = synth.make_inputs(base, threads=min(16, os.cpu_count() or 8))
+        kh = torch.from_numpy(x["khat"]).to("cuda").to(tdt)
+        vv = torch.from_numpy(x["v"]).to("cuda").to(tdt)
+        q = torch.from_numpy(x["q"]).to("cuda").to(tdt)
+        P = torch.from_numpy(x["P"]).to("cuda")
+        del x
+        cache_bytes = 2 * kh.numel() * kh.element_size()
+        copies = 2 if cache_bytes >= (1 << 30) else 4  # steps alternate between copies of the cache
+        kfs = [kh] + [kh.clone() for _ in range(copies - 1)]
+        vs = [vv] + [vv.clone() for _ in range(copies - 1)]
+        log(f"[bench] {name}: inputs + upload {time.perf_counter() - t0:.1f} s, {copies} cache copies")
+        out = torch.empty((base.B, base.Hq, base.D), dtype=tdt, device="cuda")
+        lay0 = api.make_layout(base.B, base.Hq, base.Hkv, base.D, base.d, base.S, tdt)
+        wsd = torch.empty(max(api.loki_workspace_bytes(lay0, base.S, 0, 0, -1), 256),
+                          dtype=torch.uint8, device="cuda")
+
+        def dense_step(i):
+            api.dense_decode_attn(lay0, q, kfs[i % copies], vs[i % copies], base.S, wsd, out, stream)
+
+        d_us, d_wall = event_timed_steps(torch, dense_step, steps, 10, stream)
+        dense_us = _pct(d_us, 50)
+        dense_bytes = base.B * base.Hkv * base.S * 2 * base.D * base.elem_bytes
+        for d in sorted({w.d for w in variants}):
+            lay = api.make_layout(base.B, base.Hq, base.Hkv, base.D, d, base.S, tdt)
+            klos = [kf[..., :d].contiguous() for kf in kfs]
+            khis = [kf[..., d:].contiguous() if d < base.D else None for kf in kfs]
+            for w in [w for w in variants if w.d == d]:
+                for mode in modes:
+                    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+
+                    def loki_step(i):
+                        c = i % copies
+                        api.loki_decode_attn(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode, ws,
+                                             out, None, stream)
+
+                    l_us, l_wall = event_timed_steps(torch, loki_step, steps, 10, stream)
+                    kern = kernel_times(api, loki_step, 30)
+                    med = _pct(l_us, 50)
+                    ab = algorithmic_bytes(w, mode)
+                    grouped_literal = (mode == 0 and w.G > 1)
+                    e = {"workload": name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "d": w.d,
+                         "k": w.k, "select_mode": mode, "units": w.B * w.Hkv, "steps": steps,
+                         "cache_copies": copies,
+                         "us_per_step": med, "us_p10": _pct(l_us, 10), "us_p90": _pct(l_us, 90),
+                         "us_mean": float(np.mean(l_us)), "us_wall_clock": l_wall,
+                         "tokens_heads_per_s": w.B * w.Hq / (med * 1e-6),
+                         "dense_us_per_step": dense_us, "dense_us_p10": _pct(d_us, 10),
+                         "dense_us_p90": _pct(d_us, 90),
+                         "dense_hbm_gbps": dense_bytes / dense_us / 1e3,
+                         "speedup_vs_dense": dense_us / med,
+                         "kernels_us": kern,
+                         "dominant_kernel": max(kern, key=lambda n: kern[n]) if kern else None}
+                    if grouped_literal:
+                        # every query head gathers its own k rows; heads of a group pick largely the
+                        # same rows and share them in cache, so this is a count of requested bytes,
+                        # not of bytes moved, and no fraction of the HBM peak is derived from it
+                        e.update({"requested_bytes": ab["step"],
+                                  "requested_gbps": ab["step"] / med / 1e3,
+                                  "algorithmic_bytes": None, "hbm_gbps": None, "frac_of_peak": None})
+                    else:
+                        e.update({"algorithmic_bytes": ab["step"], "hbm_gbps": ab["step"] / med / 1e3,
+                                  "frac_of_peak": ab["step"] / med / 1e3 / HBM_PEAK_GBPS})
+                    entries.append(e)
+                    log(f"[bench] {w.name} d={w.d} k={w.k} mode {mode}: {med:.1f} us "
+                        f"(p10 {e['us_p10']:.1f}, p90 {e['us_p90']:.1f}), dense {dense_us:.1f} us, "
+                        f"frac {e['frac_of_peak']}, kernels {kern}")
+                    del ws
+            del klos, khis
+        del kh, vv, kfs, vs, q, P, out, wsd
+        torch.cuda.empty_cache()
+    return entries
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -101,6 +253,12 @@ def main():
                     help="skip the calibration timing (loki_pca_fit on synthetic keys)")
     ap.add_argument("--no-step", action="store_true",
                     help="skip the loki_decode_step timings (append folded in; ragged batch)")
+    ap.add_argument("--configs", choices=["all", "none"], default=None,
+                    help="the other four workloads (both select modes, the nine (d, k) points of "
+                         "the large-model sweep) in the `configs` array of the JSON line; default: "
+                         "all when --workload is the benchmark workload, none otherwise")
+    ap.add_argument("--config-steps", type=int, default=200,
+                    help="event-timed steps per entry of the `configs` array")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 5 times (reference point for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -205,6 +363,11 @@ def main():
     log("[bench] timing loki")
     t_loki = timed(loki_step, args.steps, args.warmup)
     log(f"[bench] loki {t_loki * 1e6:.1f} us/step; per-kernel pass")
+    # distribution of step times: each step from one event on the launch stream to the next
+    dist_us, _ = event_timed_steps(torch, loki_step, max(200, args.steps), args.warmup, stream)
+    step_dist = {"steps": len(dist_us), "median_us": _pct(dist_us, 50), "p10_us": _pct(dist_us, 10),
+                 "p90_us": _pct(dist_us, 90), "mean_us": float(np.mean(dist_us)),
+                 "std_over_mean": float(np.std(dist_us) / np.mean(dist_us))}
 
     # the same steps replayed from a captured graph (one step per cache copy in the graph): the
     # library allocates nothing and records no memset, so its launches can be captured as they are
@@ -449,7 +612,9 @@ def main():
                    "frac_of_peak": step_bytes / sr_us / 1e3 / HBM_PEAK_GBPS}
     log(f"[bench] plain read of {step_bytes} bytes: {sr_us:.1f} us")
 
-    dominant = max((n for n in k_loki if n in ab), key=lambda n: k_loki[n])
+    # the longest kernel of the step, whether or not the method assigns it bytes (select, query
+    # rotation and merge kernels move none: their time is overhead on the step's roofline)
+    dominant = max(k_loki, key=lambda n: k_loki[n])
     kernel_us = k_loki[dominant]
     if len(k_loki) == 1:
         # The step is this one kernel: its average launch duration is the span between two
@@ -468,12 +633,14 @@ def main():
         kernel_us = ev0.elapsed_time(ev1) * 1e3 / args.steps
         log(f"[bench] {dominant}: {kernel_us:.1f} us per launch between events "
             f"({k_loki[dominant]:.1f} us isolated)")
-    achieved = ab[dominant] / (kernel_us * 1e-6) / 1e9
-    default_shape = (w == cfgs[args.workload])
-    traffic = MEASURED_TRAFFIC_BYTES.get(f"{w.name}:{dominant}") if default_shape else None
+    dom_bytes = ab.get(dominant, 0)
+    achieved = dom_bytes / (kernel_us * 1e-6) / 1e9
+    default_shape = (w == cfgs[args.workload]) and mode == 0
+    traffic, traffic_source = recorded_traffic(w.name, dominant) if default_shape else (None, None)
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBPS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "algorithmic_bytes": ab[dominant], "kernel_us": kernel_us,
+                "traffic_recorded_in": traffic_source,
+                "algorithmic_bytes": dom_bytes, "kernel_us": kernel_us,
                 "kernel_us_isolated": k_loki[dominant],
                 "stream_read": stream_read,
                 "frac_of_stream_read": achieved / stream_read["GB/s"]}
@@ -496,6 +663,7 @@ def main():
         "tokens_heads_per_s": w.B * w.Hq / t_loki,
         "step_hbm_gbps": ab["step"] / t_loki / 1e9,
         "step_hbm_frac": ab["step"] / t_loki / 1e9 / HBM_PEAK_GBPS,
+        "step_time_distribution": step_dist,
         "graph_replay_us_per_step": t_graph * 1e6,
         "kernels_us": k_loki,
         "dense_us_per_step": t_dense * 1e6 if t_dense else None,
@@ -513,6 +681,14 @@ def main():
         result["cpu_baseline"] = cpu_baseline(w, x, mode)
     else:
         result["cpu_baseline"] = None
+    want_configs = args.configs or ("all" if (args.workload == "llama2_7b" and default_shape) else "none")
+    if want_configs == "all":
+        # free the benchmark workload's tensors first: the other workloads hold up to 2 GiB caches
+        del caches, x
+        torch.cuda.empty_cache()
+        result["configs"] = bench_configs(args, torch, api, synth)
+    else:
+        result["configs"] = None
     print(json.dumps(result), flush=True)
 
 

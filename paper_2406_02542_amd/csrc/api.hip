@@ -344,12 +344,22 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   int32_t* idx = out_idx ? out_idx : w.sel_idx;
   StageTimer tm(st);
   hipError_t e;
-  if (path == LOKI_PATH_FUSED && !fused_eligible(s)) return LOKI_ERR_UNSUPPORTED;
-  if (path == LOKI_PATH_FUSED || (path == 0 && fused_preferred(s))) {
-    tm.begin("fused_decode");
-    e = launch_fused(s, q, P, klo, khi, v, out, out_idx, st);
-    tm.end();
-    return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+  if (s.G == 1) {
+    if (path == LOKI_PATH_FUSED && !fused_eligible(s)) return LOKI_ERR_UNSUPPORTED;
+    if (path == LOKI_PATH_FUSED || (path == 0 && fused_preferred(s))) {
+      tm.begin("fused_decode");
+      e = launch_fused(s, q, P, klo, khi, v, out, out_idx, st);
+      tm.end();
+      return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+    }
+  } else {
+    if (path == LOKI_PATH_FUSED && !fused_gqa_eligible(s, select_mode)) return LOKI_ERR_UNSUPPORTED;
+    if (path == LOKI_PATH_FUSED || (path == 0 && fused_gqa_preferred(s, select_mode))) {
+      tm.begin("fused_decode");
+      e = launch_fused_gqa(s, q, P, klo, khi, v, out, out_idx, st);
+      tm.end();
+      return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+    }
   }
   tm.begin("rotate_query");
   e = launch_qrot(s, q, P, w.qhat, klo, khi, v, st);

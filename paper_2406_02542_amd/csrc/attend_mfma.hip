@@ -19,19 +19,14 @@
 // as two bf16 terms (16 significant bits): unlike the ranking scores, these logits decide no
 // index, and a relative error of 2^-17 in them is far below the bf16 rounding of the output;
 // the third term would cost 16 registers and a third of the first product's matrix work.
-// Three waves per SIMD (168 registers) is the budget, so that three blocks share a CU (the
-// 8-head gather needs more registers and runs two).
-#include "attend_impl.h"
+// The tile loop (attend_mfma_impl.h) keeps the next step's loads in flight during the softmax
+// and the second product, which costs registers: two blocks share a CU.
+#include "attend_mfma_impl.h"
 
 namespace loki {
 
-typedef __bf16 am_bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float am_f32x4_t __attribute__((ext_vector_type(4)));
-
 constexpr int kAmThreads = 256;
 constexpr int kAmWaves = kAmThreads / 64;
-constexpr int kAmRows = 32;        // rows per wave step
-constexpr int kAmPitch = 264;      // bytes per V row in LDS: 256 + 8 keeps column reads conflict-free
 
 // QT = number of bf16 terms q enters with (1: q is bf16; 2: q is fp32)
 // KSTEPS / LO_ONLY (with GATHER = false): the logits use only the first d columns, held by k_a
@@ -39,7 +34,7 @@ constexpr int kAmPitch = 264;      // bytes per V row in LDS: 256 + 8 keeps colu
 // steps of the first product are issued, and columns past d (a partial last step) meet a zero
 // in the B operand, so whatever valid chunk their lanes load does not count.
 template <int NH, bool GATHER, int KSTEPS = 4, bool LO_ONLY = false>
-__global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void attend_mfma_kernel(
+__global__ __launch_bounds__(kAmThreads, 2) void attend_mfma_kernel(
     const void* __restrict__ k_a,   // GATHER: klo [units, S_cap, d]; dense: K [units, S_cap, 128]
     const void* __restrict__ k_b,   // GATHER: khi [units, S_cap, 128-d]; dense: unused
     const void* __restrict__ v,     // [units, S_cap, 128]
@@ -51,7 +46,7 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     Paging pg) {
   constexpr bool kRotated = GATHER || LO_ONLY;  // the query is the fp32 rotated one
   constexpr int QT = kRotated ? 2 : 1;
-  __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmRows * kAmPitch];  // 8448 B per wave
+  __shared__ __align__(16) unsigned char s_v[kAmWaves][kAmStageBytes];  // 8448 B per wave
   __shared__ int32_t s_idx[GATHER ? kMaxGatherChunk : 1];
   __shared__ MergeSmem<kAmWaves, NH> s_merge;
 
@@ -86,28 +81,13 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
 
   // B operand of the first product: q of head r16, columns 32*step + 8*kgrp .. +7
   am_bf16x8_t bq[KSTEPS][QT];
+  if constexpr (kRotated) {
+    am_query_operands<KSTEPS, QT>(static_cast<const float*>(qv) + (head0 + (head_ok ? r16 : 0)) * kD,
+                                  head_ok, LO_ONLY ? d : kD, bq);
+  } else {
 #pragma unroll
-  for (int step = 0; step < KSTEPS; ++step) {
-    const int col = 32 * step + 8 * kgrp;
-    if constexpr (kRotated) {
-      const bool col_ok = head_ok && (!LO_ONLY || col < d);
-      const float* qh = static_cast<const float*>(qv) + (head0 + (head_ok ? r16 : 0)) * kD + col;
-      uint32_t w[QT][4];
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        float rest0 = col_ok ? qh[2 * e2] : 0.f, rest1 = col_ok ? qh[2 * e2 + 1] : 0.f;
-#pragma unroll
-        for (int t = 0; t < QT; ++t) {
-          const uint32_t pk = BF16::round2(rest0, rest1);
-          rest0 -= __uint_as_float(pk << 16);            // exact in fp32
-          rest1 -= __uint_as_float(pk & 0xffff0000u);
-          w[t][e2] = pk;
-        }
-      }
-#pragma unroll
-      for (int t = 0; t < QT; ++t)
-        bq[step][t] = __builtin_bit_cast(am_bf16x8_t, make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]));
-    } else {
+    for (int step = 0; step < KSTEPS; ++step) {
+      const int col = 32 * step + 8 * kgrp;
       const uint16_t* qh = static_cast<const uint16_t*>(qv) + (head0 + (head_ok ? r16 : 0)) * kD + col;
       uint4 raw = load16(qh);
       if (!head_ok) raw = make_uint4(0, 0, 0, 0);
@@ -115,143 +95,11 @@ __global__ __launch_bounds__(kAmThreads, (NH == 8 && GATHER) ? 2 : 3) void atten
     }
   }
 
-  // where this lane's 16-byte chunks of a K row live: chunk 4*step + kgrp of the logical row
-  const int nlo = (kRotated ? d : kD) / 8;  // chunks held by k_a
-  const char* kptr[KSTEPS];
-  size_t kpitch[KSTEPS];
-#pragma unroll
-  for (int step = 0; step < KSTEPS; ++step) {
-    const int c = 4 * step + kgrp;
-    const bool in_lo = c < nlo;
-    kpitch[step] = (in_lo || LO_ONLY) ? (size_t)(kRotated ? d : kD) * 2 : (size_t)(kD - d) * 2;
-    const char* base = (in_lo || LO_ONLY) ? static_cast<const char*>(k_a) + (size_t)(in_lo ? c : 0) * 16
-                                          : static_cast<const char*>(k_b) + (size_t)(c - nlo) * 16;
-    kptr[step] = base + addr_unit * S_cap * kpitch[step];
-  }
-  const char* vptr = static_cast<const char*>(v) + addr_unit * S_cap * (kD * 2) + (size_t)kgrp * 16;
-  unsigned char* my_v = s_v[wave];
-
-  float m_run = kNegBig, l_run = 0.f;   // head r16, this lane's share of the rows
-  am_f32x4_t o[8];                      // o[cb][i]: column 16*cb + r16, head 4*kgrp + i
-#pragma unroll
-  for (int cb = 0; cb < 8; ++cb) o[cb] = am_f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  for (int base = r0 + wave * kAmRows; base < r1; base += kAmWaves * kAmRows) {
-    // ---- loads: two 16-row tiles of K (A operands) and of V (to LDS) -------------------------
-    uint4 kraw[2][KSTEPS], vraw[2][4];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int r = min(base + 16 * t + r16, r1 - 1);  // rows past the end re-read the last one
-      const int row = GATHER ? s_idx[r - r0] : r;
-#pragma unroll
-      for (int step = 0; step < 4; ++step) {
-        if (step < KSTEPS) kraw[t][step] = load16(kptr[step] + (size_t)row * kpitch[step]);
-        vraw[t][step] = load16(vptr + (size_t)row * (kD * 2) + step * 64);
-      }
-    }
-    // ---- S = K q^T: acc[t][i] = logit of row base + 16 t + 4 kgrp + i for head r16 -----------
-    am_f32x4_t s_acc[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      s_acc[t] = am_f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int qt = QT - 1; qt >= 0; --qt)
-#pragma unroll
-        for (int step = 0; step < KSTEPS; ++step)
-          s_acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
-              __builtin_bit_cast(am_bf16x8_t, kraw[t][step]), bq[step][qt], s_acc[t], 0, 0, 0);
-    }
-    // ---- V tiles to LDS, row-major with padded pitch ------------------------------------------
-    __builtin_amdgcn_wave_barrier();  // the previous step's column reads are done
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int step = 0; step < 4; ++step)
-      {  // the pitch keeps rows 8-byte aligned only: two 8-byte stores per chunk
-        unsigned char* dst = my_v + (16 * t + r16) * kAmPitch + (4 * step + kgrp) * 16;
-        *reinterpret_cast<uint2*>(dst) = make_uint2(vraw[t][step].x, vraw[t][step].y);
-        *reinterpret_cast<uint2*>(dst + 8) = make_uint2(vraw[t][step].z, vraw[t][step].w);
-      }
-    // ---- softmax scalars of head r16 -----------------------------------------------------------
-    float logit[2][4];
-    float smax = kNegBig;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool ok = base + 16 * t + 4 * kgrp + i < r1;
-        logit[t][i] = ok ? s_acc[t][i] * kSoftmaxScaleLog2 : kNegBig;
-        smax = fmaxf(smax, logit[t][i]);
-      }
-    smax = fmaxf(smax, __shfl_xor(smax, 16));
-    smax = fmaxf(smax, __shfl_xor(smax, 32));
-    const float m_new = fmaxf(m_run, smax);
-    const float corr = fast_exp2(m_run - m_new);
-    m_run = m_new;
-    float p[8], psum = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool ok = base + 16 * t + 4 * kgrp + i < r1;
-        p[4 * t + i] = ok ? fast_exp2(logit[t][i] - m_new) : 0.f;
-        psum += p[4 * t + i];
-      }
-    l_run = fmaf(l_run, corr, psum);
-    // A operand of the second product: P[head r16][k = 8 kgrp + e], two bf16 terms
-    uint32_t ph[4], pl[4];
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      ph[e2] = BF16::round2(p[2 * e2], p[2 * e2 + 1]);
-      pl[e2] = BF16::round2(p[2 * e2] - __uint_as_float(ph[e2] << 16),
-                            p[2 * e2 + 1] - __uint_as_float(ph[e2] & 0xffff0000u));
-    }
-    const am_bf16x8_t a_hi = __builtin_bit_cast(am_bf16x8_t, make_uint4(ph[0], ph[1], ph[2], ph[3]));
-    const am_bf16x8_t a_lo = __builtin_bit_cast(am_bf16x8_t, make_uint4(pl[0], pl[1], pl[2], pl[3]));
-    // ---- rescale the running output when some head's maximum moved ---------------------------
-    if (__ballot(corr != 1.0f) != 0ull) {
-      float c4[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) c4[i] = __shfl(corr, 4 * kgrp + i);  // lane of head 4 kgrp + i
-#pragma unroll
-      for (int cb = 0; cb < 8; ++cb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) o[cb][i] *= c4[i];
-    }
-    // ---- O += P V: B operand = V^T, rows (k index 8 kgrp + e) -> tile e/4, row 4 kgrp + e%4 ----
-    __builtin_amdgcn_wave_barrier();  // the V tiles above are written
-#pragma unroll
-    for (int cb = 0; cb < 8; ++cb) {
-      uint32_t w[4];
-#pragma unroll
-      for (int e2 = 0; e2 < 4; ++e2) {
-        const int e = 2 * e2;
-        const int rl0 = 16 * (e / 4) + 4 * kgrp + (e % 4);
-        const uint32_t x0 = *reinterpret_cast<const uint16_t*>(my_v + rl0 * kAmPitch + (16 * cb + r16) * 2);
-        const uint32_t x1 = *reinterpret_cast<const uint16_t*>(my_v + (rl0 + 1) * kAmPitch + (16 * cb + r16) * 2);
-        w[e2] = x0 | (x1 << 16);
-      }
-      const am_bf16x8_t bv = __builtin_bit_cast(am_bf16x8_t, make_uint4(w[0], w[1], w[2], w[3]));
-      o[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo, bv, o[cb], 0, 0, 0);
-      o[cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi, bv, o[cb], 0, 0, 0);
-    }
-  }
-
-  // ---- wave totals: sum l over the four k-groups; publish (m, l, o) per head ------------------
-  l_run += __shfl_xor(l_run, 16);
-  l_run += __shfl_xor(l_run, 32);
-  if (kgrp == 0 && head_ok) {
-    s_merge.m[wave][r16] = m_run;
-    s_merge.l[wave][r16] = l_run;
-  }
-#pragma unroll
-  for (int cb = 0; cb < 8; ++cb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int head = 4 * kgrp + i;
-      if (head < NH) s_merge.o[wave][head][16 * cb + r16] = o[cb][i];
-    }
-  __syncthreads();
+  const AmAddr<KSTEPS> ad = am_make_addr<KSTEPS, LO_ONLY>(k_a, k_b, v, addr_unit, S_cap, kRotated ? d : kD);
+  AmState st;
+  st.init();
+  am_attend_rows<GATHER, KSTEPS, QT, kAmWaves>(ad, bq, s_idx, r0, r1, s_v[wave], st);
+  am_publish<NH, kAmWaves>(st, s_merge);
 
   for (int i = tid; i < NH * kD; i += kAmThreads) {
     const int g = i / kD, col = i % kD;

@@ -1,0 +1,240 @@
+// The whole decode step of Loki (Algorithm 1 lines 3 and 5-9 of arXiv 2406.02542) for one
+// (batch, KV head) unit whose G > 1 query heads share ONE selection (one index set per KV head,
+// ranked by the maximum of the group's approximate scores), in ONE block, bf16 cache:
+//   rotate the G queries; score the low-rank slab on the matrix cores (score_mfma_impl.h) and
+//   keep the group maximum of every row in LDS; select the top-k in LDS (select_impl.h); attend
+//   over the selected rows for all G heads on the matrix cores (attend_mfma_impl.h).
+// No score, index list or partial result leaves the CU and there is no launch boundary, so the
+// select stage of one block overlaps the memory stages of the block it shares the CU with.
+// The stages use LDS one after the other: the rotation's partial sums, then the scores, then
+// the value tiles of the attention stage and finally the merge of the waves share one region.
+#include "attend_mfma_impl.h"
+#include "score_impl.h"
+#include "score_mfma_impl.h"
+#include "select_impl.h"
+
+namespace loki {
+
+constexpr int kGqaMaxK = kMaxGatherChunk;  // the index list lives in LDS
+
+// positions per thread in the select stage: ceil(S / threads) rounded up to a multiple of 4
+__host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
+  const int c = (S + threads - 1) / threads;
+  return (c + 3) & ~3;
+}
+
+template <int THREADS, int G>
+struct GqaLds {
+  static constexpr int kWaves = THREADS / 64;
+  static constexpr size_t kRotBytes = (size_t)G * (kRotParts + 1) * kD * sizeof(float);  // partial sums + q
+  static constexpr size_t kStageBytes = (size_t)kWaves * kAmStageBytes;
+  static constexpr size_t kMergeBytes = sizeof(MergeSmem<kWaves, G>);
+  __host__ __device__ static size_t region_bytes(int S) {
+    size_t b = (size_t)THREADS * gqa_keys_per_thread(S, THREADS) * sizeof(float);  // the scores
+    b = b > kRotBytes ? b : kRotBytes;
+    b = b > kStageBytes ? b : kStageBytes;
+    b = b > kMergeBytes ? b : kMergeBytes;
+    return (b + 15) & ~(size_t)15;
+  }
+  __host__ __device__ static size_t total_bytes(int S, int k) { return region_bytes(S) + (size_t)k * 4; }
+};
+
+// THREADS = 256: two blocks share a CU (S <= 8192); 512: one block per CU (S <= 16384).
+// NCH = 16-byte chunks per slab row (d = 8 NCH); KPT = keys a thread holds in the select stage.
+template <int THREADS, int NCH, int G, int KPT>
+__global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_kernel(
+    const uint16_t* __restrict__ klo, const uint16_t* __restrict__ khi, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ q, const float* __restrict__ P, uint16_t* __restrict__ out,
+    int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag) {
+  constexpr int kWaves = THREADS / 64;
+  constexpr int PPW = kRotParts / kWaves;  // parts of the rotation a wave owns
+  static_assert(PPW * kWaves == kRotParts, "the rotation's 8 parts divide over the waves");
+  constexpr int d = 8 * NCH;
+  using Lds = GqaLds<THREADS, G>;
+
+  extern __shared__ __align__(16) unsigned char dyn_smem[];
+  float* s_score = reinterpret_cast<float*>(dyn_smem);                     // scoring, select
+  float* s_q = reinterpret_cast<float*>(dyn_smem);                          // rotation: [G][128]
+  float* s_part = s_q + G * kD;                                             // rotation: [G][8][128]
+  unsigned char* s_stage = dyn_smem;                                        // attention: value tiles
+  MergeSmem<kWaves, G>& s_merge = *reinterpret_cast<MergeSmem<kWaves, G>*>(dyn_smem);  // merge
+  int32_t* s_idx = reinterpret_cast<int32_t*>(dyn_smem + Lds::region_bytes(S_max));  // [k_max]
+  __shared__ __align__(16) float s_qhat[G][kD];
+  __shared__ ResidentSelectSmem<THREADS> s_sel;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15;
+  const int unit = blockIdx.x;  // = b * Hkv + h
+  const int h = unit % Hkv;
+  const size_t head0 = (size_t)unit * G;
+  const int S = seq_rows(rag, unit / Hkv, S_max);
+  const int k = seq_keep(rag, unit / Hkv, k_max, S);
+  const int per_thread = gqa_keys_per_thread(S_max, THREADS);
+
+  resident_select_clear<THREADS>(s_sel);  // covered by the barriers of the next stages
+
+  // ---- qhat = q P_h for the G heads, with the association every path uses (8 parts of 16 terms,
+  // parts added in order): wave w owns parts w PPW .. w PPW + PPW - 1, lane l columns 2l, 2l+1 ----
+  {
+    float2 pv[PPW][kRotPartLen];
+    const float* Ph = P + (size_t)h * kD * kD + 2 * lane;
+#pragma unroll
+    for (int pp = 0; pp < PPW; ++pp)
+#pragma unroll
+      for (int ii = 0; ii < kRotPartLen; ++ii)
+        pv[pp][ii] = *reinterpret_cast<const float2*>(Ph + (size_t)((wave * PPW + pp) * kRotPartLen + ii) * kD);
+    for (int i = tid; i < G * kD; i += THREADS) s_q[i] = BF16::load1(q + head0 * kD + i);
+    __syncthreads();
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int pp = 0; pp < PPW; ++pp) {
+        const int part = wave * PPW + pp;
+        float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+        for (int i4 = 0; i4 < kRotPartLen; i4 += 4) {
+          const float4 qq = *reinterpret_cast<const float4*>(&s_q[g * kD + part * kRotPartLen + i4]);
+          a0 = fmaf(qq.x, pv[pp][i4 + 0].x, a0);
+          a1 = fmaf(qq.x, pv[pp][i4 + 0].y, a1);
+          a0 = fmaf(qq.y, pv[pp][i4 + 1].x, a0);
+          a1 = fmaf(qq.y, pv[pp][i4 + 1].y, a1);
+          a0 = fmaf(qq.z, pv[pp][i4 + 2].x, a0);
+          a1 = fmaf(qq.z, pv[pp][i4 + 2].y, a1);
+          a0 = fmaf(qq.w, pv[pp][i4 + 3].x, a0);
+          a1 = fmaf(qq.w, pv[pp][i4 + 3].y, a1);
+        }
+        *reinterpret_cast<float2*>(&s_part[(g * kRotParts + part) * kD + 2 * lane]) = make_float2(a0, a1);
+      }
+    __syncthreads();
+    for (int i = tid; i < G * kD; i += THREADS) {
+      const int g = i / kD, j = i % kD;
+      float sum = 0.f;
+#pragma unroll
+      for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[(g * kRotParts + pp) * kD + j];
+      s_qhat[g][j] = sum;
+    }
+    __syncthreads();  // s_qhat complete; the partial sums are dead, the region turns into the scores
+  }
+
+  // ---- approximate scores: group maximum of every row into LDS ----------------------------------
+  {
+    const bool head_ok = r16 < G;
+    bf16x8_t bq[ScoreMfmaGeom<NCH>::NB][3];
+    score_mfma_operands<NCH>(s_qhat[head_ok ? r16 : 0], head_ok, bq);
+    const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * (size_t)(d * 2);
+    score_mfma_rows<NCH, kWaves>(slab, 0, S, bq, [&](int rowbase, const f32x4_t& acc) {
+      float m4[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) m4[i] = group_allreduce_max<G>(head_ok ? acc[i] : -3.0e38f);
+      if (r16 == 0 && rowbase < S) {
+        if (rowbase + 3 < S) {
+          *reinterpret_cast<float4*>(&s_score[rowbase]) = make_float4(m4[0], m4[1], m4[2], m4[3]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (rowbase + i < S) s_score[rowbase + i] = m4[i];
+        }
+      }
+    });
+  }
+  __syncthreads();
+
+  // ---- top-k in LDS -----------------------------------------------------------------------------
+  int32_t* gidx = out_idx ? out_idx + (size_t)unit * k_max : nullptr;
+  if (gidx)
+    for (int i = k + tid; i < k_max; i += THREADS) gidx[i] = -1;  // a sequence keeping fewer rows
+  block_select_topk_resident<THREADS, KPT>(s_score, S, k, per_thread, s_sel,
+                                           [&](int rank, int pos, float) {
+                                             s_idx[rank] = pos;
+                                             if (gidx) gidx[rank] = pos;
+                                           });
+  __syncthreads();  // the index list is complete; the scores are dead, the region turns into value tiles
+
+  // ---- exact attention over the selected rows, all G heads ---------------------------------------
+  {
+    const bool head_ok = r16 < G;
+    am_bf16x8_t bq[4][2];
+    am_query_operands<4, 2>(s_qhat[head_ok ? r16 : 0], head_ok, kD, bq);
+    const AmAddr<4> ad = am_make_addr<4, false>(klo, khi, v, (size_t)unit, S_cap, d);
+    AmState st;
+    st.init();
+    am_attend_rows<true, 4, 2, kWaves>(ad, bq, s_idx, 0, k, s_stage + (size_t)wave * kAmStageBytes, st);
+    __syncthreads();  // every wave is done with its value tiles: the region turns into the merge
+    am_publish<G, kWaves>(st, s_merge);
+  }
+  for (int i = tid; i < G * kD; i += THREADS) {
+    const int g = i / kD, col = i % kD;
+    float mn, ls, os;
+    attend_merged<kWaves, G>(s_merge, g, col, mn, ls, os);
+    out[(head0 + g) * kD + col] = BF16::round(os / ls);
+  }
+}
+
+// ---- host side ---------------------------------------------------------------------------------
+bool fused_gqa_eligible(const Shape& s, int select_mode) {
+  if (s.dtype != 1 || select_mode != 1) return false;
+  if (s.G != 2 && s.G != 4 && s.G != 8) return false;
+  if (s.rg.queries > 1 || s.ap.k_new != nullptr || s.pg.table != nullptr) return false;
+  const int nch = s.d / 8;
+  if (s.d % 8 != 0 || (nch & (nch - 1)) != 0 || nch < 2 || s.d >= kD) return false;
+  return s.S <= 16384 && s.k <= kGqaMaxK;
+}
+
+bool fused_gqa_preferred(const Shape& s, int select_mode) {
+  if (!fused_gqa_eligible(s, select_mode)) return false;
+  // one block per unit: worth it when the units alone fill the chip
+  return s.B * s.Hkv >= kNumCU;
+}
+
+template <int THREADS, int NCH, int G, int KPT>
+static hipError_t launch_fused_gqa_k(const Shape& s, const void* q, const float* P, const void* klo,
+                                     const void* khi, const void* v, void* out, int32_t* out_idx,
+                                     hipStream_t st) {
+  auto kern = fused_gqa_kernel<THREADS, NCH, G, KPT>;
+  const size_t lds = GqaLds<THREADS, G>::total_bytes(s.S, s.k);
+  // the limit is a property of the function on the current device; setting it is cheap and
+  // keeps no state in the library
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(THREADS), lds, st,
+                     static_cast<const uint16_t*>(klo), static_cast<const uint16_t*>(khi),
+                     static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(q), P,
+                     static_cast<uint16_t*>(out), out_idx, s.Hkv, s.S, s.S_cap, s.k, s.rg);
+  return hipGetLastError();
+}
+
+template <int NCH, int G>
+static hipError_t launch_fused_gqa_g(const Shape& s, const void* q, const float* P, const void* klo,
+                                     const void* khi, const void* v, void* out, int32_t* out_idx,
+                                     hipStream_t st) {
+  if (s.S <= 256 * 16) return launch_fused_gqa_k<256, NCH, G, 16>(s, q, P, klo, khi, v, out, out_idx, st);
+  if (s.S <= 256 * 32) return launch_fused_gqa_k<256, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_gqa_k<512, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
+}
+
+template <int NCH>
+static hipError_t launch_fused_gqa_n(const Shape& s, const void* q, const float* P, const void* klo,
+                                     const void* khi, const void* v, void* out, int32_t* out_idx,
+                                     hipStream_t st) {
+  switch (s.G) {
+    case 2: return launch_fused_gqa_g<NCH, 2>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 4: return launch_fused_gqa_g<NCH, 4>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 8: return launch_fused_gqa_g<NCH, 8>(s, q, P, klo, khi, v, out, out_idx, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_fused_gqa(const Shape& s, const void* q, const float* P, const void* klo,
+                            const void* khi, const void* v, void* out, int32_t* out_idx,
+                            hipStream_t st) {
+  if (!fused_gqa_eligible(s, 1)) return hipErrorInvalidValue;
+  switch (s.d / 8) {
+    case 2: return launch_fused_gqa_n<2>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 4: return launch_fused_gqa_n<4>(s, q, P, klo, khi, v, out, out_idx, st);
+    case 8: return launch_fused_gqa_n<8>(s, q, P, klo, khi, v, out, out_idx, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace loki

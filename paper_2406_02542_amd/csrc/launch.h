@@ -102,6 +102,13 @@ bool fused_eligible(const Shape& s);
 bool fused_preferred(const Shape& s);
 hipError_t launch_fused(const Shape& s, const void* q, const float* P, void* klo, void* khi,
                         void* v, void* out, int32_t* out_idx, hipStream_t st);
+// Single-launch step for grouped query heads sharing one selection per KV head (fused_gqa.hip;
+// bf16 caches, select_mode = one selection per KV group).
+bool fused_gqa_eligible(const Shape& s, int select_mode);
+bool fused_gqa_preferred(const Shape& s, int select_mode);
+hipError_t launch_fused_gqa(const Shape& s, const void* q, const float* P, const void* klo,
+                            const void* khi, const void* v, void* out, int32_t* out_idx,
+                            hipStream_t st);
 // Calibration and diagnostics (calibrate.hip).
 size_t pca_workspace_bytes(int Hkv, long long N);
 hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, long long N, float* P,

@@ -7,6 +7,7 @@
 // block instead: see fused.hip.)  A score block needs no LDS and no barrier: its slice of qhat
 // goes straight to registers while the first slab loads are already in flight.
 #include "score_impl.h"
+#include "score_mfma_impl.h"
 
 namespace loki {
 
@@ -139,38 +140,10 @@ __global__ __launch_bounds__(256) void score_kernel(
 // ---- matrix-core variant for grouped queries on a bf16 cache ----------------------------------
 // With G > 1 query heads per KV head the scoring step is a small dense contraction per row tile,
 // scores[s, g] = sum_j Klo[s, j] qhat[g, j], and the per-byte vector work of the kernel above
-// grows with G until it, not HBM, sets the pace.  Here a wave's 1 KiB load is used directly as
-// the A operand of v_mfma_f32_16x16x32_bf16 (lane l supplies row l%16, columns 8*(l/16)..+7 —
-// exactly one 16-byte chunk of a slab row) and qhat^T, padded to 16 heads, is the B operand.
-// qhat is fp32: it enters as three bf16 terms (value, remainder, remainder of the remainder =
-// 24 significant bits), so the products are exact and a score differs from the fp32 vector
-// kernel only by accumulation order; the bf16 keys are exact.
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-__device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (&term)[3]) {
-  uint32_t w[3][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t part[3][2];
-#pragma unroll
-    for (int e = 0; e < 2; ++e) {
-      float rest = active ? x[2 * i + e] : 0.f;
-#pragma unroll
-      for (int t = 0; t < 3; ++t) {
-        const uint16_t hb = BF16::round(rest);
-        rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
-        part[t][e] = hb;
-      }
-    }
-#pragma unroll
-    for (int t = 0; t < 3; ++t) w[t][i] = part[t][0] | (part[t][1] << 16);
-  }
-#pragma unroll
-  for (int t = 0; t < 3; ++t)
-    term[t] = __builtin_bit_cast(bf16x8_t, make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]));
-}
-
+// grows with G until it, not HBM, sets the pace.  The tile loop is score_mfma_rows
+// (score_mfma_impl.h); this kernel decides which heads form the 16 columns and where their
+// scores go.
+//
 // NCH = 16-byte chunks per slab row (d = 8 * NCH).
 // TILE: several new tokens per sequence (rg.queries = m > 1).  The m G query heads that read one
 // KV head's slab form the 16 columns of the B operand, 16 / G tokens per block (blockIdx.z picks
@@ -181,15 +154,8 @@ template <int NCH, int G, bool GROUP_MAX, bool TILE>
 __global__ __launch_bounds__(256) void score_mfma_kernel(
     const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
     int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg, Paging pg) {
-  constexpr int d = 8 * NCH;
-  constexpr int RB = NCH <= 4 ? 4 / NCH : 1;   // 16-row blocks one load instruction covers
-  constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
-  constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
-  constexpr int RPS = 16 * RB;                 // rows per wave step
-  constexpr int UN = 8 / NL;                   // steps per loop trip: 8 loads in flight per lane
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int kgrp = lane >> 4, r16 = lane & 15;
+  const int lane = threadIdx.x & 63;
+  const int r16 = lane & 15;
 
   // column r16 of the tile: which query head it is, where its scores go, how many rows it sees
   int S;            // rows the block scores up to (uniform)
@@ -223,98 +189,36 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   }
   if ((int)blockIdx.x * rows_per_block >= S) return;
 
-  // B operands: qhat of head r16, the 8 columns this lane's k-group stands for
-  bf16x8_t bq[NB][3];
-#pragma unroll
-  for (int n = 0; n < NB; ++n) {
-    const int kbase = NCH <= 4 ? 8 * (kgrp % NCH) : 32 * n + 8 * kgrp;
-    const bool active = head_ok && (NCH <= 4 ? (kgrp / NCH == n) : true);
-    float x[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = qhat[head * kD + kbase + e];
-    split_bf16x8(x, active, bq[n]);
-  }
+  bf16x8_t bq[ScoreMfmaGeom<NCH>::NB][3];
+  score_mfma_operands<NCH>(qhat + head * kD, head_ok, bq);
 
-  // where this lane's chunk of load j sits inside a step
-  const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
-  const size_t row_bytes = (size_t)d * 2;
   const int row0 = blockIdx.x * rows_per_block;
   const int row_end = min(S, row0 + rows_per_block);
   // the block's rows are consecutive in memory (a paged cache: the host keeps a block inside a page)
   const long long row_shift = cache_row(pg, cache_b, hkv, Hkv, S_cap, row0) - row0;
   const int lane_end = min(row_end, S_lane);
-  const char* base = reinterpret_cast<const char*>(klo) + row_shift * (long long)row_bytes +
-                     (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+  const char* slab = reinterpret_cast<const char*>(klo) + row_shift * (long long)(NCH * 16);
   const bool vec_ok = (S_max & 3) == 0;
-
-  // Two register buffers of UN/2 steps each, refilled right after they are consumed, so that a
-  // wave always has loads in flight while it computes.  Loads past the block's end re-read its
-  // last row (no branch around a load; their scores are never stored).
-  constexpr int UH = UN / 2;             // steps per buffer
-  constexpr int kTrip = 4 * RPS * UH;    // rows the block advances per buffer
-  auto load_trip = [&](uint4 (&raw)[UH][NL], int t0) {
+  score_mfma_rows<NCH, 4>(slab, row0, row_end, bq, [&](int rowbase, const f32x4_t& acc) {
+    float v[4] = {acc[0], acc[1], acc[2], acc[3]};
+    bool writer = head_ok;
+    if constexpr (GROUP_MAX) {
+      // the G heads of one token sit in G consecutive lanes
 #pragma unroll
-    for (int u = 0; u < UH; ++u)
+      for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<G>(head_ok ? v[i] : -3.0e38f);
+      writer = head_ok && (r16 % G == 0);
+    }
+    float* dst = scores + score_row * S_max + rowbase;
+    if (writer && rowbase < lane_end) {
+      if (vec_ok && rowbase + 3 < lane_end) {
+        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      } else {
 #pragma unroll
-      for (int j = 0; j < NL; ++j) {
-        const int r = min(t0 + u * 4 * RPS + row_in_step, row_end - 1) - row_in_step;
-        raw[u][j] = load16(base + (long long)r * (long long)row_bytes + (size_t)j * 64);
-      }
-  };
-  auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
-#pragma unroll
-    for (int u = 0; u < UH; ++u) {
-      const int trow = t0 + u * 4 * RPS;
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
-        if constexpr (NCH <= 4) {
-          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][0]);
-#pragma unroll
-          for (int t = 2; t >= 0; --t)  // smallest terms first
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[rb][t], acc, 0, 0, 0);
-        } else {
-#pragma unroll
-          for (int j = 0; j < NL; ++j) {
-            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][j]);
-#pragma unroll
-            for (int t = 2; t >= 0; --t)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
-          }
-        }
-        // acc[i] = score of head r16 at row trow + 16*rb + 4*kgrp + i
-        const int rowbase = trow + 16 * rb + 4 * kgrp;
-        float v[4] = {acc[0], acc[1], acc[2], acc[3]};
-        bool writer = head_ok;
-        if constexpr (GROUP_MAX) {
-          // the G heads of one token sit in G consecutive lanes
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = group_allreduce_max<G>(head_ok ? v[i] : -3.0e38f);
-          writer = head_ok && (r16 % G == 0);
-        }
-        float* dst = scores + score_row * S_max + rowbase;
-        if (writer && rowbase < lane_end) {
-          if (vec_ok && rowbase + 3 < lane_end) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (rowbase + i < lane_end) dst[i] = v[i];
-          }
-        }
+        for (int i = 0; i < 4; ++i)
+          if (rowbase + i < lane_end) dst[i] = v[i];
       }
     }
-  };
-  uint4 buf0[UH][NL], buf1[UH][NL];
-  const int t_first = row0 + wave * RPS;
-  load_trip(buf0, t_first);
-  load_trip(buf1, t_first + kTrip);
-  for (int t0 = t_first; t0 < row_end; t0 += 2 * kTrip) {
-    score_trip(buf0, t0);
-    load_trip(buf0, t0 + 2 * kTrip);
-    score_trip(buf1, t0 + kTrip);
-    load_trip(buf1, t0 + 3 * kTrip);
-  }
+  });
 }
 
 // tokens of one sequence that share a score block (TILE), and the blocks along z that takes

@@ -1,0 +1,136 @@
+// Low-rank scoring of a run of slab rows on the matrix cores (Algorithm 1 line 5 of
+// arXiv 2406.02542 for several query heads that share one KV head's slab; bf16 cache):
+//   scores[s, g] = sum_{j<d} Klo[s, j] qhat[g, j]
+// A wave's 1 KiB load is directly the A operand of v_mfma_f32_16x16x32_bf16 (lane l supplies
+// row l%16, columns 8*(l/16)..+7 — exactly one 16-byte chunk of a slab row) and qhat^T, padded
+// to 16 heads, is the B operand.  qhat is fp32: it enters as three bf16 terms (value,
+// remainder, remainder of the remainder = 24 significant bits), so the products are exact and
+// a score differs from an fp32 vector dot product only by accumulation order; the bf16 keys
+// are exact.  Shared by the stand-alone score kernel and the single-launch grouped-query kernel.
+#pragma once
+
+#include "common.h"
+
+namespace loki {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ inline void split_bf16x8(const float (&x)[8], bool active, bf16x8_t (&term)[3]) {
+  uint32_t w[3][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t part[3][2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      float rest = active ? x[2 * i + e] : 0.f;
+#pragma unroll
+      for (int t = 0; t < 3; ++t) {
+        const uint16_t hb = BF16::round(rest);
+        rest -= __uint_as_float((uint32_t)hb << 16);  // exact in fp32
+        part[t][e] = hb;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) w[t][i] = part[t][0] | (part[t][1] << 16);
+  }
+#pragma unroll
+  for (int t = 0; t < 3; ++t)
+    term[t] = __builtin_bit_cast(bf16x8_t, make_uint4(w[t][0], w[t][1], w[t][2], w[t][3]));
+}
+
+// NCH = 16-byte chunks per slab row (d = 8 * NCH).
+template <int NCH>
+struct ScoreMfmaGeom {
+  static constexpr int RB = NCH <= 4 ? 4 / NCH : 1;   // 16-row blocks one load instruction covers
+  static constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
+  static constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
+  static constexpr int RPS = 16 * RB;                 // rows per wave step
+  static constexpr int UN = 8 / NL;                   // steps per loop trip: 8 loads in flight per lane
+};
+
+// The B operands of head `r16` (this lane's column of the tile): qh points at that head's 128
+// rotated-query values (global or LDS); lanes whose column holds no head pass active = false.
+template <int NCH>
+__device__ __forceinline__ void score_mfma_operands(const float* qh, bool active,
+                                                    bf16x8_t (&bq)[ScoreMfmaGeom<NCH>::NB][3]) {
+  const int kgrp = (threadIdx.x & 63) >> 4;
+#pragma unroll
+  for (int n = 0; n < ScoreMfmaGeom<NCH>::NB; ++n) {
+    const int kbase = NCH <= 4 ? 8 * (kgrp % NCH) : 32 * n + 8 * kgrp;
+    const bool act = active && (NCH <= 4 ? (kgrp / NCH == n) : true);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = qh[kbase + e];
+    split_bf16x8(x, act, bq[n]);
+  }
+}
+
+// Scores rows [row0, row_end) with the block's WAVES waves.  `slab` is the address row 0 would
+// have (rows are consecutive, 16 NCH bytes each); emit(rowbase, acc) is called by every lane
+// with acc[i] = score of head (lane % 16) at row rowbase + i, rowbase = ... + 4 (lane / 16);
+// rows at or past row_end carry the values of the last row and must not be used.
+// Two register buffers of UN/2 steps each, refilled right after they are consumed, so that a
+// wave always has loads in flight while it computes.  Loads past the end re-read the last row
+// (no branch around a load).
+template <int NCH, int WAVES, typename Emit>
+__device__ __forceinline__ void score_mfma_rows(const char* slab, int row0, int row_end,
+                                                const bf16x8_t (&bq)[ScoreMfmaGeom<NCH>::NB][3],
+                                                Emit emit) {
+  using Gm = ScoreMfmaGeom<NCH>;
+  constexpr int RB = Gm::RB, NL = Gm::NL, RPS = Gm::RPS, UN = Gm::UN;
+  constexpr int UH = UN / 2;                 // steps per buffer
+  constexpr int kTrip = WAVES * RPS * UH;    // rows the block advances per buffer
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kgrp = lane >> 4, r16 = lane & 15;
+  const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
+  constexpr size_t row_bytes = (size_t)NCH * 16;
+  const char* base = slab + (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+
+  auto load_trip = [&](uint4 (&raw)[UH][NL], int t0) {
+#pragma unroll
+    for (int u = 0; u < UH; ++u)
+#pragma unroll
+      for (int j = 0; j < NL; ++j) {
+        const int r = min(t0 + u * WAVES * RPS + row_in_step, row_end - 1) - row_in_step;
+        raw[u][j] = load16(base + (long long)r * (long long)row_bytes + (size_t)j * 64);
+      }
+  };
+  auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
+#pragma unroll
+    for (int u = 0; u < UH; ++u) {
+      const int trow = t0 + u * WAVES * RPS;
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (NCH <= 4) {
+          const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][0]);
+#pragma unroll
+          for (int t = 2; t >= 0; --t)  // smallest terms first
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[rb][t], acc, 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int j = 0; j < NL; ++j) {
+            const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][j]);
+#pragma unroll
+            for (int t = 2; t >= 0; --t)
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
+          }
+        }
+        emit(trow + 16 * rb + 4 * kgrp, acc);
+      }
+    }
+  };
+  uint4 buf0[UH][NL], buf1[UH][NL];
+  const int t_first = row0 + wave * RPS;
+  load_trip(buf0, t_first);
+  load_trip(buf1, t_first + kTrip);
+  for (int t0 = t_first; t0 < row_end; t0 += 2 * kTrip) {
+    score_trip(buf0, t0);
+    load_trip(buf0, t0 + 2 * kTrip);
+    score_trip(buf1, t0 + kTrip);
+    load_trip(buf1, t0 + 3 * kTrip);
+  }
+}
+
+}  // namespace loki

@@ -67,6 +67,12 @@ class DeviceCase:
         return out.float().cpu().numpy().astype(np.float64)
 
 
+def gqa_single_kernel_ok(w: synth.Workload, mode: int) -> bool:
+    """Shapes the single-launch grouped-query kernel takes (mirrors include/loki.h)."""
+    return (w.dtype == "bf16" and mode == 1 and w.G in (2, 4, 8) and w.d in (16, 32, 64)
+            and w.S <= 16384 and w.k <= 2048)
+
+
 def check_index_set(gpu_idx: np.ndarray, ora_idx: np.ndarray, scores: np.ndarray, S: int, k: int,
                     where: str) -> bool:
     """Validity + equality up to near-threshold swaps.  Returns True if sets are identical."""

@@ -93,6 +93,15 @@ def test_full_size_large_share_sweep():
                 _all_index_sets_valid(idx, base.S)
                 say(f"{case.w.name} mode {mode}: "
                     f"{check_loki(case, mode, units=units, out_gpu=out, idx_gpu=idx)}")
+                if mode == 1:
+                    # the library's choice above is the single-launch grouped-query kernel (512
+                    # units); pin the split path too and require the same index lists
+                    out2, idx2 = case.run_loki(mode, path=api.PATH_SPLIT)
+                    assert np.array_equal(idx, idx2)
+                    say(f"{case.w.name} mode 1 split path: "
+                        f"{check_loki(case, mode, units=units, out_gpu=out2, idx_gpu=idx2)}")
+                    out3, idx3 = case.run_loki(mode, path=api.PATH_FUSED)
+                    assert np.array_equal(idx, idx3) and np.array_equal(out, out3)
         if d == 16:
             say(f"dense: {check_dense(case, units=units[:2])}")
         del case

@@ -7,7 +7,8 @@ import torch
 
 from oracle import loki_oracle as O
 from paper_2406_02542_amd import api, synth
-from tests.parity import DeviceCase, OUT_TOL, TORCH_DT, check_dense, check_loki, to_dev
+from tests.parity import (DeviceCase, OUT_TOL, TORCH_DT, check_dense, check_loki, gqa_single_kernel_ok,
+                          to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +53,34 @@ def test_loki_matches_oracle(dtype, shape, mode):
     say(f"loki split {check_loki(case, mode, path=api.PATH_SPLIT)}")
     if Hq == Hkv:
         say(f"loki fused {check_loki(case, mode, path=api.PATH_FUSED)}")
+    elif gqa_single_kernel_ok(w, mode):
+        say(f"loki grouped single-kernel {check_loki(case, mode, path=api.PATH_FUSED)}")
+
+
+@pytest.mark.parametrize("shape", [
+    # (B, Hq, Hkv, S, d, k)
+    (2, 8, 2, 4096, 32, 1024),    # G=4: 16 keys per thread in the select stage
+    (1, 16, 2, 8192, 16, 2048),   # G=8: 32 keys per thread, largest index list
+    (1, 8, 1, 8190, 64, 511),     # G=8, two loads per row tile, ragged tail
+    (2, 4, 2, 16384, 32, 2048),   # G=2: the 512-thread form (one block per CU)
+    (1, 8, 2, 12001, 16, 1500),   # 512-thread form, odd length
+    (1, 4, 1, 5, 32, 3),          # fewer rows than one wave step
+    (1, 8, 1, 33, 64, 33),        # k = S
+])
+def test_grouped_single_kernel_matches_oracle_and_split_path(shape):
+    """One selection per KV group in one launch (grouped heads, bf16): against the oracle, and
+    the same index lists as the split path."""
+    B, Hq, Hkv, S, d, k = shape
+    w, x = _case(f"gq_{S}_{d}", B, Hq, Hkv, S, "bf16", d, k, seed=1500 + S + d + k)
+    say(f"case {w}")
+    assert gqa_single_kernel_ok(w, 1)
+    case = DeviceCase(w, x, S_cap=S + 11)
+    of, jf = case.run_loki(1, path=api.PATH_FUSED)
+    os_, js = case.run_loki(1, path=api.PATH_SPLIT)
+    say(f"single kernel {check_loki(case, 1, out_gpu=of, idx_gpu=jf)}")
+    say(f"split {check_loki(case, 1, out_gpu=os_, idx_gpu=js)}")
+    assert np.array_equal(jf, js)
+    assert np.max(np.abs(of - os_)) <= 8e-3
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -110,13 +139,14 @@ def test_edge_shapes_single_kernel_and_split_paths(dtype, S, d, k):
 
 def test_single_kernel_path_limits():
     """Pinning the one-kernel path outside its limits is refused, not silently rerouted."""
-    for (Hq, Hkv, S, k) in [(4, 2, 512, 64), (2, 2, 8193, 64), (2, 2, 8192, 2049)]:
+    for (Hq, Hkv, S, k, mode) in [(4, 2, 512, 64, 0), (2, 2, 8193, 64, 0), (2, 2, 8192, 2049, 0),
+                                  (4, 2, 16385, 64, 1), (4, 2, 4096, 2049, 1)]:
         w, x = _case("lim", 1, Hq, Hkv, S, "bf16", 32, k, seed=3600)
         case = DeviceCase(w, x)
         with pytest.raises(api.LokiError) as e:
-            case.run_loki(0, path=api.PATH_FUSED)
+            case.run_loki(mode, path=api.PATH_FUSED)
         assert e.value.status == 2
-        check_loki(case, 0)  # the default route still works
+        check_loki(case, mode)  # the default route still works
 
 
 @pytest.mark.parametrize("S,k,G", [

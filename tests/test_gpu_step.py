@@ -180,6 +180,14 @@ def test_step_gqa(mode, G, dtype):
     run_step_case(w, mode, True, True)
 
 
+@pytest.mark.parametrize("G,S,k", [(4, 5000, 1200), (8, 8192, 2048), (2, 12000, 700)])
+def test_step_gqa_single_kernel_ragged(G, S, k):
+    """Grouped heads, one selection per KV group, one launch: per-sequence lengths and k."""
+    w = synth.Workload(f"step_gq{G}", 4, 2 * G, 2, 128, S, "bf16", 32, k, seed=9650 + G)
+    run_step_case(w, 1, True, False, path=api.PATH_FUSED)
+    run_step_case(w, 1, True, False, path=api.PATH_FUSED, lens=[S, 1, 2, 257])
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_step_long_sequences_multiblock_select(mode):
     """S_max = 40000 (three chunks of the multi-block select): one full sequence, one inside

@@ -16,6 +16,17 @@
 namespace loki {
 
 constexpr int kGqaMaxK = kMaxGatherChunk;  // the index list lives in LDS
+// 16-byte slab loads a lane keeps in flight in the scoring stage (measured on the 64/8-head
+// shapes at S = 8192: 64-byte slab rows gain 6 % from 16 against 8, the other widths nothing)
+#ifndef LOKI_GQA_SCORE_DEPTH
+#define LOKI_GQA_SCORE_DEPTH(NCH) ((NCH) == 4 ? 16 : 8)
+#endif
+#ifndef LOKI_GQA_STAGGER_TICKS
+#define LOKI_GQA_STAGGER_TICKS 0
+#endif
+#ifndef LOKI_GQA_PRIO
+#define LOKI_GQA_PRIO 0
+#endif
 
 // positions per thread in the select stage: ceil(S / threads) rounded up to a multiple of 4
 __host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
@@ -53,7 +64,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   using Lds = GqaLds<THREADS, G>;
 
   extern __shared__ __align__(16) unsigned char dyn_smem[];
-  float* s_score = reinterpret_cast<float*>(dyn_smem);                     // scoring, select
+  uint32_t* s_key = reinterpret_cast<uint32_t*>(dyn_smem);                 // scoring, select: keys of the scores
   float* s_q = reinterpret_cast<float*>(dyn_smem);                          // rotation: [G][128]
   float* s_part = s_q + G * kD;                                             // rotation: [G][8][128]
   unsigned char* s_stage = dyn_smem;                                        // attention: value tiles
@@ -71,7 +82,19 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   const int k = seq_keep(rag, unit / Hkv, k_max, S);
   const int per_thread = gqa_keys_per_thread(S_max, THREADS);
 
+  if (LOKI_GQA_STAGGER_TICKS > 0 && gridDim.x >= 2 * kNumCU && blockIdx.x >= gridDim.x / 2) {
+    const unsigned long long t_start = wall_clock64();
+    while (wall_clock64() - t_start < (unsigned long long)LOKI_GQA_STAGGER_TICKS) __builtin_amdgcn_s_sleep(32);
+  }
+  if (LOKI_GQA_PRIO > 0 && blockIdx.x >= gridDim.x / 2) __builtin_amdgcn_s_setprio(LOKI_GQA_PRIO);
+  LOKI_STAMP(0);
   resident_select_clear<THREADS>(s_sel);  // covered by the barriers of the next stages
+
+  // the first slab loads need no query: they are in flight during the rotation
+  constexpr int kDepth = LOKI_GQA_SCORE_DEPTH(NCH);
+  const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * (size_t)(d * 2);
+  ScoreMfmaBufs<NCH, kDepth> sbufs;
+  score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
 
   // ---- qhat = q P_h for the G heads, with the association every path uses (8 parts of 16 terms,
   // parts added in order): wave w owns parts w PPW .. w PPW + PPW - 1, lane l columns 2l, 2l+1 ----
@@ -115,40 +138,117 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     }
     __syncthreads();  // s_qhat complete; the partial sums are dead, the region turns into the scores
   }
+  LOKI_STAMP(1);
 
-  // ---- approximate scores: group maximum of every row into LDS ----------------------------------
+  // ---- approximate scores: the key of every row's group maximum into LDS ----------------------
+  // qhat is the A operand and the row tile the B operand, so a lane holds one row and four heads:
+  // the maximum over the group is taken in registers (G = 8: one exchange between the lanes
+  // that hold heads 0-3 and 4-7).  The first counting pass of the selection rides along: the
+  // leading 11 bits of every row's key go into the histogram while the next rows' loads are in
+  // flight.
   {
     const bool head_ok = r16 < G;
+    const int kgrp = lane >> 4;
     bf16x8_t bq[ScoreMfmaGeom<NCH>::NB][3];
     score_mfma_operands<NCH>(s_qhat[head_ok ? r16 : 0], head_ok, bq);
-    const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * (size_t)(d * 2);
-    score_mfma_rows<NCH, kWaves>(slab, 0, S, bq, [&](int rowbase, const f32x4_t& acc) {
-      float m4[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) m4[i] = group_allreduce_max<G>(head_ok ? acc[i] : -3.0e38f);
-      if (r16 == 0 && rowbase < S) {
-        if (rowbase + 3 < S) {
-          *reinterpret_cast<float4*>(&s_score[rowbase]) = make_float4(m4[0], m4[1], m4[2], m4[3]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (rowbase + i < S) s_score[rowbase + i] = m4[i];
-        }
-      }
-    });
+    score_mfma_rows<NCH, kWaves, kDepth, true>(
+        slab, 0, S, bq, sbufs, [&](int rowbase, const f32x4_t& acc) {
+          float m = fmaxf(acc[0], acc[1]);
+          if constexpr (G >= 4) m = fmaxf(m, fmaxf(acc[2], acc[3]));
+          if constexpr (G == 8) {
+            // heads 4-7 sit in the next 16 lanes: v_permlane16_swap exchanges the odd 16-lane
+            // rows of one operand with the even rows of the other, so with the same value in
+            // both, row 0 ends up holding its own value and row 1's
+            typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+            const u32x2_t sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
+            m = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          }
+          const int row = rowbase + r16;
+          if (kgrp == 0 && row < S) {
+            const uint32_t key = float_to_key(m);
+            s_key[row] = key;
+            atomicAdd(&s_sel.hist[0][key >> 21], 1u);
+          }
+        });
   }
   __syncthreads();
+  LOKI_STAMP(2);
 
   // ---- top-k in LDS -----------------------------------------------------------------------------
   int32_t* gidx = out_idx ? out_idx + (size_t)unit * k_max : nullptr;
   if (gidx)
     for (int i = k + tid; i < k_max; i += THREADS) gidx[i] = -1;  // a sequence keeping fewer rows
-  block_select_topk_resident<THREADS, KPT>(s_score, S, k, per_thread, s_sel,
-                                           [&](int rank, int pos, float) {
-                                             s_idx[rank] = pos;
-                                             if (gidx) gidx[rank] = pos;
-                                           });
+  // The histogram of the leading 11 key bits is complete: find the bin that holds the k-th
+  // largest score.  Rows in higher bins are selected for certain (n_def of them); the rows
+  // inside the bin are the candidates among which the exact threshold is found.
+  resident_find_bin<THREADS>(s_sel, 0, (uint32_t)k);
+  const uint32_t bin1 = s_sel.out[0][0], rem1 = s_sel.out[0][1];
+  const uint32_t n_cand = s_sel.hist[0][bin1];
+  int n_def = k - (int)rem1;
+  constexpr int kCandCap = 4 * THREADS;  // candidates resolved from a compact list (else: all keys)
+  uint32_t* s_ckey = reinterpret_cast<uint32_t*>(dyn_smem);  // over the scores, once they are in registers
+  int32_t* s_cpos = reinterpret_cast<int32_t*>(s_ckey + kCandCap);
+  {
+    uint32_t key[KPT];
+    uint32_t valid_mask;
+    resident_load_keys<KPT>(s_key, S, per_thread, key, valid_mask);
+    LOKI_STAMP(11);
+    // (the barrier inside comes after every thread's key loads and before any list is written)
+    resident_partition<THREADS, KPT>(
+        key, valid_mask, per_thread, bin1, s_sel.wave[0], s_sel.wave[1],
+        [&](int rank, int pos) { s_idx[rank] = pos; },
+        [&](int rank, int pos, uint32_t kk) {
+          if (rank < kCandCap) {
+            s_ckey[rank] = kk;
+            s_cpos[rank] = pos;
+          }
+        });
+    for (int i = tid; i < 2048; i += THREADS) s_sel.hist[0][i] = 0u;  // everyone has read n_cand
+    __syncthreads();
+    LOKI_STAMP(13);
+    if (n_cand <= (uint32_t)kCandCap) {
+      // exact threshold among the candidates (they agree on the leading 11 bits: rank on the
+      // remaining 21, moved to the top of the word) and ordered emission of the rem1 best
+      uint32_t ck[4], vm = 0;
+      const int c0 = resident_pos0(4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool ok = (uint32_t)(c0 + e) < n_cand;
+        ck[e] = ok ? (s_ckey[c0 + e] << 11) : 0u;
+        vm |= (ok ? 1u : 0u) << e;
+      }
+      uint32_t Tp, need_eq;
+      resident_threshold<THREADS, 4>(ck, vm, rem1, s_sel, Tp, need_eq);
+      resident_compact<THREADS, 4>(ck, vm, 4, Tp, need_eq, 0u, 0u, s_sel.wave[0], s_sel.wave[1],
+                                   [&](int rank, int local, float) { s_idx[n_def + rank] = s_cpos[local]; });
+    } else {
+      // long runs of (nearly) equal scores: the plain selection over all keys, still in registers
+      uint32_t T, need_eq;
+      resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, s_sel, T, need_eq);
+      resident_compact<THREADS, KPT>(key, valid_mask, per_thread, T, need_eq, 0u, 0u, s_sel.wave[0],
+                                     s_sel.wave[1], [&](int rank, int pos, float) { s_idx[rank] = pos; });
+      n_def = k;
+    }
+  }
   __syncthreads();  // the index list is complete; the scores are dead, the region turns into value tiles
+  LOKI_STAMP(6);
+  if (gidx) {
+    // the list holds the certain rows (ascending) followed by the chosen candidates (ascending);
+    // the caller's copy is the merge of the two
+    const int n_chosen = k - n_def;
+    for (int i = tid; i < k; i += THREADS) {
+      const int pos = s_idx[i];
+      const bool certain = i < n_def;
+      const int32_t* other = certain ? s_idx + n_def : s_idx;
+      int lo = 0, hi = certain ? n_chosen : n_def;
+      while (lo < hi) {  // entries of the other run below pos
+        const int mid = (lo + hi) >> 1;
+        if (other[mid] < pos) lo = mid + 1;
+        else hi = mid;
+      }
+      gidx[(certain ? i : i - n_def) + lo] = pos;
+    }
+  }
 
   // ---- exact attention over the selected rows, all G heads ---------------------------------------
   {
@@ -160,6 +260,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     st.init();
     am_attend_rows<true, 4, 2, kWaves>(ad, bq, s_idx, 0, k, s_stage + (size_t)wave * kAmStageBytes, st);
     __syncthreads();  // every wave is done with its value tiles: the region turns into the merge
+    LOKI_STAMP(7);
     am_publish<G, kWaves>(st, s_merge);
   }
   for (int i = tid; i < G * kD; i += THREADS) {
@@ -168,7 +269,14 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     attend_merged<kWaves, G>(s_merge, g, col, mn, ls, os);
     out[(head0 + g) * kD + col] = BF16::round(os / ls);
   }
+  LOKI_STAMP(8);
 }
+
+#ifdef LOKI_PHASE_TIMING
+extern "C" int loki_debug_read_gqa_ts(unsigned long long* host_dst, size_t count) {
+  return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(loki::g_phase_ts), count * sizeof(unsigned long long));
+}
+#endif
 
 // ---- host side ---------------------------------------------------------------------------------
 bool fused_gqa_eligible(const Shape& s, int select_mode) {

@@ -199,7 +199,9 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   const int lane_end = min(row_end, S_lane);
   const char* slab = reinterpret_cast<const char*>(klo) + row_shift * (long long)(NCH * 16);
   const bool vec_ok = (S_max & 3) == 0;
-  score_mfma_rows<NCH, 4>(slab, row0, row_end, bq, [&](int rowbase, const f32x4_t& acc) {
+  ScoreMfmaBufs<NCH, 8> bufs;
+  score_mfma_prefetch<NCH, 4, 8>(slab, row0, row_end, bufs);
+  score_mfma_rows<NCH, 4, 8>(slab, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
     float v[4] = {acc[0], acc[1], acc[2], acc[3]};
     bool writer = head_ok;
     if constexpr (GROUP_MAX) {

@@ -46,7 +46,6 @@ struct ScoreMfmaGeom {
   static constexpr int NL = NCH <= 4 ? 1 : NCH / 4;   // load instructions per 16-row block
   static constexpr int NB = NCH <= 4 ? RB : NL;       // distinct B operands
   static constexpr int RPS = 16 * RB;                 // rows per wave step
-  static constexpr int UN = 8 / NL;                   // steps per loop trip: 8 loads in flight per lane
 };
 
 // The B operands of head `r16` (this lane's column of the tile): qh points at that head's 128
@@ -66,36 +65,84 @@ __device__ __forceinline__ void score_mfma_operands(const float* qh, bool active
   }
 }
 
-// Scores rows [row0, row_end) with the block's WAVES waves.  `slab` is the address row 0 would
-// have (rows are consecutive, 16 NCH bytes each); emit(rowbase, acc) is called by every lane
-// with acc[i] = score of head (lane % 16) at row rowbase + i, rowbase = ... + 4 (lane / 16);
-// rows at or past row_end carry the values of the last row and must not be used.
-// Two register buffers of UN/2 steps each, refilled right after they are consumed, so that a
-// wave always has loads in flight while it computes.  Loads past the end re-read the last row
+// The two register buffers of the tile loop (DEPTH / 2 16-byte loads per lane each).
+template <int NCH, int DEPTH>
+struct ScoreMfmaBufs {
+  static constexpr int NL = ScoreMfmaGeom<NCH>::NL;
+  static constexpr int UH = DEPTH / NL / 2;  // steps per buffer
+  uint4 b0[UH][NL], b1[UH][NL];
+};
+
+// Where this lane's chunk of step-row 0 lives, and its row inside a step.
+template <int NCH>
+struct ScoreMfmaLane {
+  const char* base;
+  int row_in_step;
+  __device__ __forceinline__ explicit ScoreMfmaLane(const char* slab) {
+    const int lane = threadIdx.x & 63;
+    const int kgrp = lane >> 4, r16 = lane & 15;
+    row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
+    base = slab + (size_t)row_in_step * (NCH * 16) + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+  }
+};
+
+// One buffer's loads for the steps starting at row t0; rows past the end re-read the last row
 // (no branch around a load).
-template <int NCH, int WAVES, typename Emit>
+template <int NCH, int WAVES, int UH>
+__device__ __forceinline__ void score_mfma_load(const ScoreMfmaLane<NCH>& ln, int t0, int row_end,
+                                                uint4 (&raw)[UH][ScoreMfmaGeom<NCH>::NL]) {
+  constexpr int RPS = ScoreMfmaGeom<NCH>::RPS, NL = ScoreMfmaGeom<NCH>::NL;
+#pragma unroll
+  for (int u = 0; u < UH; ++u)
+#pragma unroll
+    for (int j = 0; j < NL; ++j) {
+      const int r = min(t0 + u * WAVES * RPS + ln.row_in_step, row_end - 1) - ln.row_in_step;
+      raw[u][j] = load16(ln.base + (long long)r * (long long)(NCH * 16) + (size_t)j * 64);
+    }
+}
+
+// Puts the loads of the first two buffers in flight; needs no query, so a caller can issue it
+// ahead of the query rotation.  The scheduling barriers keep the two buffers' loads in issue
+// order (buffer 0 before buffer 1, here as in the loop): loads return in order, and the wait in
+// front of a buffer's first use can only leave the other buffer's loads in flight if they were
+// issued after it on every path into the loop.
+template <int NCH, int WAVES, int DEPTH>
+__device__ __forceinline__ void score_mfma_prefetch(const char* slab, int row0, int row_end,
+                                                    ScoreMfmaBufs<NCH, DEPTH>& bufs) {
+  constexpr int UH = ScoreMfmaBufs<NCH, DEPTH>::UH;
+  constexpr int kTrip = WAVES * ScoreMfmaGeom<NCH>::RPS * UH;
+  const ScoreMfmaLane<NCH> ln(slab);
+  const int t_first = row0 + (int)(threadIdx.x >> 6) * ScoreMfmaGeom<NCH>::RPS;
+  score_mfma_load<NCH, WAVES, UH>(ln, t_first, row_end, bufs.b0);
+  __builtin_amdgcn_sched_barrier(0);
+  score_mfma_load<NCH, WAVES, UH>(ln, t_first + kTrip, row_end, bufs.b1);
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// Scores rows [row0, row_end) with the block's WAVES waves; `bufs` holds the first two buffers
+// (score_mfma_prefetch with the same arguments).  `slab` is the address row 0 would have (rows
+// are consecutive, 16 NCH bytes each); emit(rowbase, acc) is called by every lane with acc[i] =
+// score of head (lane % 16) at row rowbase + i, rowbase = ... + 4 (lane / 16); rows at or past
+// row_end carry the values of the last row and must not be used.  A buffer is refilled right
+// after it is consumed, so that a wave always has loads in flight while it computes.
+// DEPTH = 16-byte loads a lane keeps in flight (both buffers together).
+// HEADS_IN_REGS: the two operands trade places (qhat is the A operand, the row tile the B
+// operand), so that the accumulator holds the scores of ONE row per lane and four heads per
+// lane in its registers: emit(rowbase, acc) then gets acc[i] = score of head 4 (lane / 16) + i at
+// row rowbase + lane % 16, rowbase a multiple of 16.  A maximum over the heads of a group is
+// then taken in registers instead of across lanes.
+template <int NCH, int WAVES, int DEPTH = 8, bool HEADS_IN_REGS = false, typename Emit>
 __device__ __forceinline__ void score_mfma_rows(const char* slab, int row0, int row_end,
                                                 const bf16x8_t (&bq)[ScoreMfmaGeom<NCH>::NB][3],
-                                                Emit emit) {
+                                                ScoreMfmaBufs<NCH, DEPTH>& bufs, Emit emit) {
   using Gm = ScoreMfmaGeom<NCH>;
-  constexpr int RB = Gm::RB, NL = Gm::NL, RPS = Gm::RPS, UN = Gm::UN;
-  constexpr int UH = UN / 2;                 // steps per buffer
+  constexpr int RB = Gm::RB, NL = Gm::NL, RPS = Gm::RPS;
+  constexpr int UH = ScoreMfmaBufs<NCH, DEPTH>::UH;
   constexpr int kTrip = WAVES * RPS * UH;    // rows the block advances per buffer
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int kgrp = lane >> 4, r16 = lane & 15;
-  const int row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
-  constexpr size_t row_bytes = (size_t)NCH * 16;
-  const char* base = slab + (size_t)row_in_step * row_bytes + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+  const int kgrp = lane >> 4;
+  const ScoreMfmaLane<NCH> ln(slab);
 
-  auto load_trip = [&](uint4 (&raw)[UH][NL], int t0) {
-#pragma unroll
-    for (int u = 0; u < UH; ++u)
-#pragma unroll
-      for (int j = 0; j < NL; ++j) {
-        const int r = min(t0 + u * WAVES * RPS + row_in_step, row_end - 1) - row_in_step;
-        raw[u][j] = load16(base + (long long)r * (long long)row_bytes + (size_t)j * 64);
-      }
-  };
   auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
 #pragma unroll
     for (int u = 0; u < UH; ++u) {
@@ -107,29 +154,30 @@ __device__ __forceinline__ void score_mfma_rows(const char* slab, int row0, int 
           const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][0]);
 #pragma unroll
           for (int t = 2; t >= 0; --t)  // smallest terms first
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[rb][t], acc, 0, 0, 0);
+            acc = HEADS_IN_REGS ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq[rb][t], a, acc, 0, 0, 0)
+                                : __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[rb][t], acc, 0, 0, 0);
         } else {
 #pragma unroll
           for (int j = 0; j < NL; ++j) {
             const bf16x8_t a = __builtin_bit_cast(bf16x8_t, raw[u][j]);
 #pragma unroll
             for (int t = 2; t >= 0; --t)
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
+              acc = HEADS_IN_REGS ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(bq[j][t], a, acc, 0, 0, 0)
+                                  : __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
           }
         }
-        emit(trow + 16 * rb + 4 * kgrp, acc);
+        emit(HEADS_IN_REGS ? trow + 16 * rb : trow + 16 * rb + 4 * kgrp, acc);
       }
     }
   };
-  uint4 buf0[UH][NL], buf1[UH][NL];
   const int t_first = row0 + wave * RPS;
-  load_trip(buf0, t_first);
-  load_trip(buf1, t_first + kTrip);
   for (int t0 = t_first; t0 < row_end; t0 += 2 * kTrip) {
-    score_trip(buf0, t0);
-    load_trip(buf0, t0 + 2 * kTrip);
-    score_trip(buf1, t0 + kTrip);
-    load_trip(buf1, t0 + 3 * kTrip);
+    score_trip(bufs.b0, t0);
+    score_mfma_load<NCH, WAVES, UH>(ln, t0 + 2 * kTrip, row_end, bufs.b0);
+    __builtin_amdgcn_sched_barrier(0);
+    score_trip(bufs.b1, t0 + kTrip);
+    score_mfma_load<NCH, WAVES, UH>(ln, t0 + 3 * kTrip, row_end, bufs.b1);
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 

@@ -301,6 +301,38 @@ __device__ __forceinline__ int resident_pos0(int C) {
   return (int)(threadIdx.x >> 6) * 64 * C + (int)(threadIdx.x & 63) * 4;
 }
 
+// The same for an array that already holds keys (16-byte aligned).
+template <int KPT>
+__device__ __forceinline__ void resident_load_keys(const uint32_t* a, int n, int C, uint32_t (&key)[KPT],
+                                                   uint32_t& valid_mask) {
+  constexpr int kTiles = KPT / 4;
+  const int wbase = resident_pos0(C);
+  valid_mask = 0;
+#pragma unroll
+  for (int j = 0; j < kTiles; ++j) {
+    const int i = 4 * j;
+    const int p = wbase + 256 * j;
+    key[i + 0] = key[i + 1] = key[i + 2] = key[i + 3] = 0u;
+    if (i < C) {
+      if (p + 3 < n) {
+        const uint4 f = *reinterpret_cast<const uint4*>(a + p);
+        key[i + 0] = f.x;
+        key[i + 1] = f.y;
+        key[i + 2] = f.z;
+        key[i + 3] = f.w;
+        valid_mask |= 0xfu << i;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          if (p + e < n) {
+            key[i + e] = a[p + e];
+            valid_mask |= 1u << (i + e);
+          }
+      }
+    }
+  }
+}
+
 template <int KPT>
 __device__ __forceinline__ void resident_load_keys(const float* a, int n, int C, uint32_t (&key)[KPT],
                                                    uint32_t& valid_mask) {
@@ -389,6 +421,65 @@ __device__ __forceinline__ void resident_compact(const uint32_t (&key)[KPT], uin
           emit((int)(g_before + min(e_before, need_eq)), wbase + 256 * j + e, key_to_float(kk));
         g_before += gt;
         e_before += eq;
+      }
+  }
+}
+
+// Ordered split of the register-resident keys by their leading 11 bits against the threshold
+// bin: keys in a higher bin are certain to be selected, keys inside the bin are the candidates
+// among which the exact threshold lies.  emit_gt(rank, pos) sees every key above the bin with
+// its rank among those (ascending with pos); emit_eq(rank, pos, key) every key inside the bin
+// likewise.  Same layout, scans and single barrier as resident_compact.
+template <int THREADS, int KPT, typename EmitGt, typename EmitEq>
+__device__ __forceinline__ void resident_partition(const uint32_t (&key)[KPT], uint32_t valid_mask,
+                                                   int C, uint32_t bin, uint32_t* wave_g_tot,
+                                                   uint32_t* wave_e_tot, EmitGt emit_gt,
+                                                   EmitEq emit_eq) {
+  constexpr int kWaves = THREADS / 64;
+  constexpr int kTiles = KPT / 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wbase = resident_pos0(C);
+  uint32_t excl[kTiles];
+  uint32_t wave_g = 0, wave_e = 0;
+#pragma unroll
+  for (int j = 0; j < kTiles; ++j) {
+    uint32_t mine = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((valid_mask >> (4 * j + e)) & 1u) {
+        const uint32_t b = key[4 * j + e] >> 21;
+        mine += (b > bin ? 1u : 0u) + (b == bin ? 0x10000u : 0u);
+      }
+    const uint32_t incl = wave_inclusive_scan_u32(mine);
+    const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    excl[j] = (wave_g + ((incl - mine) & 0xffffu)) | ((wave_e + ((incl - mine) >> 16)) << 16);
+    wave_g += tot & 0xffffu;
+    wave_e += tot >> 16;
+  }
+  if (lane == 0) {
+    wave_g_tot[wave] = wave_g;
+    wave_e_tot[wave] = wave_e;
+  }
+  __syncthreads();
+  uint32_t before_g = 0, before_e = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const uint32_t tg = wave_g_tot[w], te = wave_e_tot[w];
+    before_g += (w < wave) ? tg : 0u;
+    before_e += (w < wave) ? te : 0u;
+  }
+#pragma unroll
+  for (int j = 0; j < kTiles; ++j) {
+    uint32_t g_before = before_g + (excl[j] & 0xffffu), e_before = before_e + (excl[j] >> 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if ((valid_mask >> (4 * j + e)) & 1u) {
+        const uint32_t kk = key[4 * j + e];
+        const uint32_t b = kk >> 21;
+        if (b > bin) emit_gt((int)g_before, wbase + 256 * j + e);
+        if (b == bin) emit_eq((int)e_before, wbase + 256 * j + e, kk);
+        g_before += b > bin;
+        e_before += b == bin;
       }
   }
 }

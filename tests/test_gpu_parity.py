@@ -226,6 +226,33 @@ def test_ties_go_to_lowest_position():
             assert all(lp in sel for lp in lower)
 
 
+@pytest.mark.parametrize("S,k", [(3000, 1100), (8192, 2048), (12000, 900)])
+def test_grouped_single_kernel_ties(S, k):
+    """The single-launch grouped-query kernel with equal scores: an all-zero cache (the threshold
+    bin holds every row: its candidate list overflows and the plain selection over all keys takes
+    over), planted duplicates (30 equal rows per score: the candidate-list route with ties inside
+    it), and a cache whose rows take 7 distinct values.  Lowest position wins; the index lists must
+    equal the split path's."""
+    w, x = _case(f"gq_ties_{S}", 1, 8, 2, S, "bf16", 32, k, seed=4100 + S)
+    x0 = dict(x)
+    x0["khat"] = np.zeros_like(x["khat"])
+    out, idx = DeviceCase(w, x0).run_loki(1, path=api.PATH_FUSED)
+    for h in range(2):
+        assert idx[0, h].tolist() == list(range(k))
+    for reps in (100, 7):
+        xd = dict(x)
+        kd = x["khat"].copy()
+        kd[:, :, reps:, :] = np.tile(kd[:, :, :reps, :], (1, 1, S // reps + 1, 1))[:, :, :S - reps, :]
+        xd["khat"] = kd
+        case = DeviceCase(w, xd)
+        outs, idxs = case.run_loki(1, path=api.PATH_SPLIT)
+        outf, idxf = case.run_loki(1, path=api.PATH_FUSED)
+        assert np.array_equal(idxs, idxf)
+        st = check_loki(case, 1, out_gpu=outf, idx_gpu=idxf)
+        say(f"{reps} distinct rows: {st}")
+        assert st["heads_with_swaps"] == 0
+
+
 def test_heavy_hitters_are_selected():
     """The peaked-attention recipe of the long-context config at reduced size: the planted
     positions carry > 90 % of the mass and must all be among the selected rows."""

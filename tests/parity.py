@@ -20,6 +20,41 @@ from paper_2406_02542_amd import api, synth
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-2}
 TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 
+# A bound that scales with the result, applied beside the absolute one (which is the benchmark spec's
+# figure and says little when outputs are small: a nearly flat softmax over k rows of N(0,1)
+# values gives outputs of magnitude 1/sqrt(k)).  Per element, for a head's output vector `ref`:
+#   bf16: 2^-8 |ref| + 1e-3 max|ref|.  The first term is the one rounding of the output (bf16
+#         keeps 8 significant bits: half a unit in the last place is at most 2^-8 of the value);
+#         the second covers what precedes the rounding (fp32 accumulation over up to 131 072
+#         rows, the two-term bf16 split of the rotated query and of the softmax weights on the
+#         matrix cores: 2^-16 relative each, the hardware exp2) and a result that sits at a
+#         rounding boundary and goes to the other neighbour.
+#   f32:  2^-23 |ref| + 1e-5 max|ref| (fp32 accumulation; observed 2e-6 of the largest entry).
+REL_TOL = {"f32": (2.0 ** -23, 1e-5), "bf16": (2.0 ** -8, 1e-3)}
+
+
+def out_bound(ref: np.ndarray, dtype: str) -> np.ndarray:
+    """Per-element error bound for one head's output vector (last axis = the D columns)."""
+    ref = np.asarray(ref, dtype=np.float64)
+    rel, scale = REL_TOL[dtype]
+    peak = np.max(np.abs(ref), axis=-1, keepdims=True)
+    return np.minimum(OUT_TOL[dtype], rel * np.abs(ref) + scale * peak + 1e-30)
+
+
+def check_out(got: np.ndarray, ref: np.ndarray, dtype: str, where: str) -> float:
+    """Asserts |got - ref| within both bounds; returns the largest absolute error."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    err = np.abs(got - ref)
+    worst = float(np.max(err))
+    assert worst <= OUT_TOL[dtype], f"{where}: |out - oracle| = {worst:.3e} > {OUT_TOL[dtype]}"
+    over = err - out_bound(ref, dtype)
+    i = np.unravel_index(int(np.argmax(over)), over.shape)
+    assert over[i] <= 0, (f"{where}: |out - oracle| = {err[i]:.3e} at {i} where the oracle has {ref[i]:.4e} "
+                          f"(largest entry {np.max(np.abs(ref)):.3e}): above the scaled bound "
+                          f"{out_bound(ref, dtype)[i]:.3e}")
+    return worst
+
 
 def to_dev(x: np.ndarray, dtype: str) -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(x)).to("cuda").to(TORCH_DT[dtype]).contiguous()
@@ -120,9 +155,8 @@ def check_loki(case: DeviceCase, mode: int, units=None, out_gpu=None, idx_gpu=No
                 qhat = O.rotate_query(x["q"][b, hq], x["P"][h])
                 ref = O.attend_selected(qhat, x["khat"][b, h], x["v"][b, h],
                                         idx_gpu[b, hs].astype(np.int64))
-            err = float(np.max(np.abs(out_gpu[b, hq] - ref)))
+            err = check_out(out_gpu[b, hq], ref, w.dtype, f"{w.name} mode {mode} b={b} hq={hq}")
             max_err = max(max_err, err)
-            assert err <= tol, f"{w.name} mode {mode} b={b} hq={hq}: |out - oracle| = {err:.3e} > {tol}"
     return {"max_err": max_err, "heads_with_swaps": swaps}
 
 
@@ -136,7 +170,6 @@ def check_dense(case: DeviceCase, units=None, out_gpu=None):
     max_err = 0.0
     for b, h in todo:
         for hq in range(h * w.G, (h + 1) * w.G):
-            err = float(np.max(np.abs(out_gpu[b, hq] - ref[b, hq])))
+            err = check_out(out_gpu[b, hq], ref[b, hq], w.dtype, f"{w.name} dense b={b} hq={hq}")
             max_err = max(max_err, err)
-            assert err <= tol, f"{w.name} dense b={b} hq={hq}: {err:.3e} > {tol}"
     return {"max_err": max_err}

@@ -8,7 +8,7 @@ import torch
 
 from oracle import loki_oracle as O
 from paper_2406_02542_amd import api, synth
-from tests.parity import OUT_TOL, TORCH_DT, DeviceCase, check_dense, check_loki
+from tests.parity import OUT_TOL, TORCH_DT, DeviceCase, check_dense, check_loki, check_out
 
 pytestmark = pytest.mark.gpu
 
@@ -72,7 +72,7 @@ def test_full_size_config(name, modes, n_units):
     worst = 0.0
     for b, h in units[:4]:
         for hq in range(h * w.G, (h + 1) * w.G):
-            worst = max(worst, float(np.max(np.abs(got[b, hq] - ref[b, hq]))))
+            worst = max(worst, check_out(got[b, hq], ref[b, hq], w.dtype, f"{name} PCAAttn b={b} hq={hq}"))
     say(f"{name} PCAAttn: max_err {worst:.3e} over {4 * w.G} heads")
     assert worst <= OUT_TOL[w.dtype]
 

@@ -115,7 +115,8 @@ def test_edge_shapes(dtype, S, d, k):
         out, _ = case.run_loki(0)
         K = np.einsum("bhsj,hij->bhsi", x["khat"].astype(np.float64), x["P"].astype(np.float64))
         dn = O.dense_decode_batch(x["q"], K, x["v"])
-        assert np.max(np.abs(out - dn)) <= OUT_TOL[dtype]
+        from tests.parity import check_out
+        check_out(out, dn, dtype, "k = S against dense attention over the unrotated keys")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -266,6 +267,76 @@ def test_heavy_hitters_are_selected():
             planted = set(synth.heavy_positions(w, h).tolist())
             for hs in (range(4 * h, 4 * h + 4) if mode == 0 else [h]):
                 assert planted <= set(idx[0, hs].tolist())
+
+
+def _pca_attn_gpu(case):
+    w = case.w
+    ws = torch.empty(api.loki_workspace_bytes(case.layout, w.S, w.d, 0, -2), dtype=torch.uint8, device="cuda")
+    out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")
+    api.loki_pca_attn(case.layout, case.q, case.P, case.klo, case.v, w.S, w.d, ws, out)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy().astype(np.float64)
+
+
+@pytest.mark.parametrize("G", [4, 8])
+def test_peaked_attention_grouped_heads(G):
+    """Outputs of magnitude 0.1 - 1 on the matrix-core paths (grouped heads, bf16): the peaked
+    recipe of the long-context workload, both select modes, the single-launch kernel, the dense
+    baseline and PCAAttn, all under the bound that scales with the result."""
+    w = synth.paper_configs()["long_gqa"].replace(B=2, Hq=2 * G, Hkv=2, S=6000, k=750, name=f"peaked_g{G}")
+    x = synth.make_inputs(w)
+    case = DeviceCase(w, x)
+    for mode in (0, 1):
+        say(f"G={G} mode {mode} {check_loki(case, mode, path=api.PATH_SPLIT)}")
+    say(f"G={G} single kernel {check_loki(case, 1, path=api.PATH_FUSED)}")
+    say(f"G={G} dense {check_dense(case)}")
+    from tests.parity import check_out
+    ref = O.pca_attention_batch(x["q"], x["P"], x["khat"], x["v"], w.d)
+    say(f"G={G} PCAAttn max_err {check_out(_pca_attn_gpu(case), ref, 'bf16', 'PCAAttn'):.3e}")
+    assert np.max(np.abs(ref)) > 0.2  # the point of the case: results are not tiny
+
+
+@pytest.mark.parametrize("heavy", [False, True])
+def test_scaled_bound_rejects_plausible_mistakes(heavy):
+    """The bound that scales with the result tells a right matrix-core attention from a plausibly
+    wrong one: the mistakes are planted in the expected value on the CPU (softmax in base 2
+    without the log2(e) factor; the 32-row tile that holds the heaviest row left out), never in a
+    kernel.  Gather over a
+    shared selection, dense baseline and PCAAttn, 8 heads per KV head, bf16."""
+    from tests.parity import out_bound
+    base = synth.paper_configs()["long_gqa"] if heavy else synth.paper_configs()["llama2_7b"]
+    w = base.replace(B=1, Hq=8, Hkv=1, S=4096, d=32, k=1024, name=f"mut_{heavy}")
+    x = synth.make_inputs(w)
+    case = DeviceCase(w, x)
+    out, idx = case.run_loki(1, path=api.PATH_SPLIT)
+    dn = case.run_dense()
+    pc = _pca_attn_gpu(case)
+    Kh, V, P = x["khat"][0, 0].astype(np.float64), x["v"][0, 0].astype(np.float64), x["P"][0]
+    rows_all = np.arange(w.S)
+
+    def attend(qvec, K, rows, scale_factor=1.0):
+        logits = (K[rows] @ qvec) / np.sqrt(w.D) * scale_factor
+        return O.softmax(logits) @ V[rows]
+
+    for hq in range(w.Hq):
+        qhat = O.rotate_query(x["q"][0, hq], P)
+        qlo = qhat.copy(); qlo[w.d:] = 0.0
+        sel = idx[0, 0].astype(np.int64)
+        # (the dense baseline is given the cache as it is and the query as it is: Eq. 1 on them)
+        cases = [("gather", out[0, hq], qhat, sel),
+                 ("dense", dn[0, hq], x["q"][0, hq].astype(np.float64), rows_all),
+                 ("PCAAttn", pc[0, hq], qlo, rows_all)]
+        for name, got, qv, rows in cases:
+            good = attend(qv, Kh, rows)
+            assert np.all(np.abs(got - good) <= out_bound(good, "bf16")), (name, hq)
+            wrong_base = attend(qv, Kh, rows, scale_factor=np.log(2.0))   # exp2 without log2(e)
+            # the 32-row tile of the list that holds the row with the largest weight, left out
+            t0 = int(np.argmax(Kh[rows] @ qv)) // 32 * 32
+            wrong_tile = attend(qv, Kh, np.concatenate([rows[:t0], rows[t0 + 32:]]))
+            for label, wrong in (("base-2 softmax", wrong_base), ("a 32-row tile left out", wrong_tile)):
+                assert np.any(np.abs(got - wrong) > out_bound(wrong, "bf16")), \
+                    f"{name} head {hq}: the bound accepts {label}"
+    say(f"heavy={heavy}: both planted mistakes rejected on every head and path")
 
 
 def test_deterministic():

@@ -15,7 +15,7 @@ import torch
 
 from oracle import loki_oracle as O
 from paper_2406_02542_amd import api, synth
-from tests.parity import OUT_TOL, TORCH_DT, check_index_set, to_dev
+from tests.parity import OUT_TOL, TORCH_DT, check_index_set, check_out, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -25,7 +25,9 @@ def say(msg):
 
 
 def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=None, use_ks=True,
-                  boost_tail=0):
+                  boost_tail=0, page_rows=0):
+    """page_rows > 0: the same case on a paged cache (random physical pages, a third of the pool
+    unused); the pools are mapped back to the contiguous layout for the checks below."""
     x = synth.make_inputs(w)
     st = synth.make_step_inputs(w, x["P"], ragged=ragged)
     if lens is not None:
@@ -48,7 +50,12 @@ def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=Non
     if not use_ks:
         ks_np = np.minimum(lens_np, w.k).astype(np.int32)
     S_cap = S_cap or w.S
-    say(f"case {w} mode {mode} path {path:#x} ragged {ragged} append {append} lens {lens_np.tolist()[:8]} ks {ks_np.tolist()[:8]}")
+    pages_per_seq = 0
+    if page_rows:
+        pages_per_seq = (w.S + page_rows - 1) // page_rows
+        S_cap = pages_per_seq * page_rows
+    say(f"case {w} mode {mode} path {path:#x} ragged {ragged} append {append} page_rows {page_rows} "
+        f"lens {lens_np.tolist()[:8]} ks {ks_np.tolist()[:8]}")
     tdt = TORCH_DT[w.dtype]
     lay = api.make_layout(w.B, w.Hq, w.Hkv, w.D, w.d, S_cap, tdt)
     klo, khi, v = api.alloc_cache(lay)
@@ -71,12 +78,35 @@ def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=Non
     eff_mode = 0 if w.G == 1 else mode
     hsel = w.Hq if eff_mode == 0 else w.Hkv
     idx = torch.full((w.B, hsel, w.k), -7, dtype=torch.int32, device="cuda")
-    api.loki_decode_step(
-        lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path, ws, out, idx,
+    step_kw = dict(
         seq_lens=torch.from_numpy(lens_np).cuda() if ragged or lens is not None else None,
         ks=torch.from_numpy(ks_np).cuda() if use_ks and (ragged or lens is not None or ks is not None) else None,
         k_new=to_dev(st["k_new"], w.dtype) if append else None,
         v_new=to_dev(st["v_new"], w.dtype) if append else None)
+    if page_rows:
+        n_pages = w.B * pages_per_seq * 3 // 2 + 1
+        perm = np.random.default_rng(w.seed).permutation(n_pages)[:w.B * pages_per_seq].astype(np.int32)
+        table = torch.from_numpy(perm.reshape(w.B, pages_per_seq)).cuda()
+
+        def to_pool(c, fill):  # [B, Hkv, S_cap, W] -> [n_pages, Hkv, page_rows, W]
+            pool = torch.full((n_pages, w.Hkv, page_rows, c.shape[-1]), fill, dtype=tdt, device="cuda")
+            pool[table.view(-1).long()] = c.view(w.B, w.Hkv, pages_per_seq, page_rows, -1).permute(
+                0, 2, 1, 3, 4).reshape(w.B * pages_per_seq, w.Hkv, page_rows, -1)
+            return pool
+
+        def from_pool(pool):
+            return pool[table.view(-1).long()].view(w.B, pages_per_seq, w.Hkv, page_rows, -1).permute(
+                0, 2, 1, 3, 4).reshape(w.B, w.Hkv, S_cap, -1).contiguous()
+
+        pklo, pv = to_pool(klo, 3e4), to_pool(v, -3e4)
+        pkhi = to_pool(khi, 3e4) if khi is not None else None
+        api.loki_decode_step(lay, q, P, pklo, pkhi, pv, w.S, w.d, w.k, mode | path, ws, out, idx,
+                             page_table=table, page_rows=page_rows, n_pages=n_pages, **step_kw)
+        torch.cuda.synchronize()
+        klo, v = from_pool(pklo), from_pool(pv)
+        khi = from_pool(pkhi) if pkhi is not None else None
+    else:
+        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path, ws, out, idx, **step_kw)
     torch.cuda.synchronize()
     out_g = out.float().cpu().numpy().astype(np.float64)
     idx_g = idx.cpu().numpy()
@@ -127,9 +157,8 @@ def run_step_case(w, mode, ragged, append, path=0, lens=None, ks=None, S_cap=Non
                     qhat = O.rotate_query(x["q"][b, hq], x["P"][h])
                     ref = O.attend_selected(qhat, khat[b, h, :S_b], vref[b, h, :S_b],
                                             idx_g[b, hs, :k_b].astype(np.int64))
-                err = float(np.max(np.abs(out_g[b, hq] - ref)))
+                err = check_out(out_g[b, hq], ref, w.dtype, f"{w.name} b={b} hq={hq}")
                 max_err = max(max_err, err)
-                assert err <= tol, f"{w.name} b={b} hq={hq}: |out - oracle| = {err:.3e} > {tol}"
     say(f"   max_err {max_err:.3e} heads_with_swaps {swaps}")
     return out_g, idx_g
 
@@ -266,8 +295,18 @@ def test_dense_step_ragged(G, dtype):
     got = out.float().cpu().numpy().astype(np.float64)
     for b in range(w.B):
         ref = O.dense_decode_batch(x["q"][b:b + 1], x["khat"][b:b + 1, :, :lens[b]], x["v"][b:b + 1, :, :lens[b]])
-        err = np.max(np.abs(got[b] - ref[0]))
-        assert err <= OUT_TOL[dtype], f"b={b}: {err:.3e}"
+        check_out(got[b], ref[0], dtype, f"dense ragged b={b}")
+
+
+# ------------------------------------------------- paged cache, judged by the oracle directly --
+@pytest.mark.parametrize("G,mode,path,page_rows", [(1, 0, api.PATH_FUSED, 256), (1, 0, api.PATH_SPLIT, 512),
+                                                   (4, 0, api.PATH_SPLIT, 256), (4, 1, api.PATH_SPLIT, 1024),
+                                                   (8, 1, api.PATH_SPLIT, 256)])
+def test_step_paged_cache_against_oracle(G, mode, path, page_rows):
+    """The whole step (ragged, appending) on a paged cache against the oracle itself, not only
+    against the contiguous layout: outputs, index lists and the appended rows."""
+    w = synth.Workload(f"step_paged_g{G}", 4, 2 * G, 2, 128, 3000, "bf16", 32, 700, seed=9660 + G + mode)
+    run_step_case(w, mode, True, True, path=path, page_rows=page_rows)
 
 
 # ---------------------------------------------------------------- PCAAttn (Algorithm 2) --
@@ -292,9 +331,8 @@ def test_pca_attn(G, dtype, d, S):
     api.loki_pca_attn(lay, to_dev(x["q"], dtype), torch.from_numpy(x["P"]).cuda(), klo, v, S, d, ws, out)
     torch.cuda.synchronize()
     ref = O.pca_attention_batch(x["q"], x["P"], x["khat"], x["v"], d)
-    err = np.max(np.abs(out.float().cpu().numpy() - ref))
+    err = check_out(out.float().cpu().numpy(), ref, dtype, f"PCAAttn G={G} d={d}")
     say(f"   max_err {err:.3e}")
-    assert err <= OUT_TOL[dtype]
 
 
 # ------------------------------------------------------------------------- graph capture --
@@ -425,9 +463,8 @@ def test_step_with_several_new_tokens_per_sequence(G, dtype, mode, m, B):
                 if not same[hs]:
                     qhat = O.rotate_query(xq["q"][e, hq], x["P"][h])
                     ref = O.attend_selected(qhat, khat[b, h, :S_e], vref[b, h, :S_e], idx_g[e, hs, :k_e].astype(np.int64))
-                err = float(np.max(np.abs(out_g[e, hq] - ref)))
+                err = check_out(out_g[e, hq], ref, dtype, f"entry {e} hq {hq}")
                 max_err = max(max_err, err)
-                assert err <= tol, f"entry {e} hq {hq}: {err:.3e}"
     say(f"   max_err {max_err:.3e}")
 
 

@@ -21,6 +21,13 @@ int score_rows_per_block(const Shape& s) {
   if (nchunks > max_chunks) nchunks = max_chunks;
   if (nchunks < 1) nchunks = 1;
   int rows = div_up(div_up(s.S, nchunks), kScoreRowsPerStep) * kScoreRowsPerStep;
+  if (s.S > 16384) {
+    // long sequences: a block stays inside one 16384-row chunk of the selection (it adds its
+    // counts into that chunk's histogram): a power of two of at most 16384 rows
+    int r = kScoreRowsPerStep;
+    while (2 * r <= rows && 2 * r <= 16384) r *= 2;
+    rows = r;
+  }
   if (s.pg.table != nullptr) {
     // a block must lie inside one page: the largest power of two (>= 256) within rows and the page
     const int page_rows = 1 << s.pg.lg_rows;
@@ -361,16 +368,23 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
       return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
     }
   }
+  // long sequences, one token each: the score kernel counts the leading key bits into the
+  // chunk histograms at the head of the select scratch (cleared by the rotation kernel), and the
+  // selection leaves its list as two ascending runs, merged only for the caller's copy
+  const int hist_chunks = w.sel_scratch ? select_hist_chunks(s, select_mode) : 0;
+  uint32_t* hist_part = hist_chunks ? w.sel_scratch : nullptr;
+  if (hist_chunks) idx = w.sel_idx;
   tm.begin("rotate_query");
-  e = launch_qrot(s, q, P, w.qhat, klo, khi, v, st);
+  e = launch_qrot(s, q, P, w.qhat, klo, khi, v, hist_part, (size_t)heads_sel * hist_chunks * 2048, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("score");
-  e = launch_score(s, select_mode, q, P, klo, w.scores, w.qhat, st);
+  e = launch_score(s, select_mode, q, P, klo, w.scores, w.qhat, hist_part, hist_chunks, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("select");
-  e = launch_select(s, heads_sel, w.scores, idx, w.sel_score, w.sel_scratch, st);
+  e = launch_select(s, heads_sel, w.scores, idx, w.sel_score, w.sel_scratch, hist_chunks != 0,
+                    hist_chunks ? out_idx : nullptr, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("gather_attend");
@@ -507,7 +521,7 @@ int loki_pca_attn(const loki_layout* layout, const void* q, const float* P, cons
   StageTimer tm(st);
   hipError_t e;
   tm.begin("rotate_query");
-  e = launch_qrot(s, q, P, w.qhat, nullptr, nullptr, nullptr, st);
+  e = launch_qrot(s, q, P, w.qhat, nullptr, nullptr, nullptr, nullptr, 0, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("pca_attend");

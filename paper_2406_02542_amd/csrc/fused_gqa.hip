@@ -196,7 +196,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     // (the barrier inside comes after every thread's key loads and before any list is written)
     resident_partition<THREADS, KPT>(
         key, valid_mask, per_thread, bin1, s_sel.wave[0], s_sel.wave[1],
-        [&](int rank, int pos) { s_idx[rank] = pos; },
+        [&](int rank, int pos, uint32_t) { s_idx[rank] = pos; },
         [&](int rank, int pos, uint32_t kk) {
           if (rank < kCandCap) {
             s_ckey[rank] = kk;

@@ -71,13 +71,25 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
 
 // Rotates every query; with s.ap set also rotates the new key of every unit and writes it and
 // the new value into row seq_len-1 of the unit's cache.
+// zero_words / n_zero: words the kernel also clears (the chunk histograms of a long-sequence
+// selection, which the score kernel then adds into); null: nothing.
 hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
-                       void* khi, void* v, hipStream_t st);
+                       void* khi, void* v, uint32_t* zero_words, size_t n_zero, hipStream_t st);
+// hist_part [selecting heads][hist_chunks][2048] (zeroed) or null: see select_hist_chunks.
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
-                        const void* klo, float* scores, float* qhat, hipStream_t st);
+                        const void* klo, float* scores, float* qhat, uint32_t* hist_part,
+                        int hist_chunks, hipStream_t st);
 size_t select_scratch_words(int S, int n_sel_heads);
+// Long sequences, one token per sequence: the number of 16384-row chunks whose leading-digit
+// histograms the score kernel fills for the selection (they are the first words of the select
+// scratch), 0 when the selection counts for itself.
+int select_hist_chunks(const Shape& s, int select_mode);
+// sel_idx / sel_score: the selection.  one_pass (the score kernel filled the chunk histograms,
+// select_hist_chunks != 0): the list is left as two ascending runs, the certain rows and then
+// the chosen candidates, and only then: user_idx (nullable): the caller's ascending copy.
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
-                         float* sel_score, uint32_t* scratch, hipStream_t st);
+                         float* sel_score, uint32_t* scratch, bool one_pass, int32_t* user_idx,
+                         hipStream_t st);
 hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
                          const float* sel_score, float* partial, void* out, hipStream_t st);

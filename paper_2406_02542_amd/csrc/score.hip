@@ -27,9 +27,16 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
                                                    typename T::store_t* __restrict__ khi,
                                                    typename T::store_t* __restrict__ v, int S_max,
                                                    int S_cap, int d, Ragged rg, Append ap,
-                                                   Paging pg) {
+                                                   Paging pg, uint32_t* __restrict__ zero_words,
+                                                   size_t n_zero) {
   using ST = typename T::store_t;
   constexpr int NV = G + (APPEND ? 1 : 0);
+  // the chunk histograms the score kernel adds into (long sequences) start from zero
+  if (zero_words != nullptr) {
+    const size_t nthreads = (size_t)gridDim.x * gridDim.y * 256;
+    for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; i < n_zero; i += nthreads)
+      zero_words[i] = 0u;
+  }
   __shared__ __align__(16) float s_q[NV][kD];
   __shared__ float s_part[NV][kRotParts][kQrotCols];
   const int tid = threadIdx.x;
@@ -82,17 +89,47 @@ __global__ __launch_bounds__(256) void qrot_kernel(const typename T::store_t* __
   }
 }
 
+// Long sequences (hist_part != nullptr): the first counting pass of the selection rides along.
+// The block counts the leading 11 bits of the key of every score it writes in LDS (16-bit
+// counters, two bins per word: a block scores at most kHistChunk rows) and adds the counts into
+// the histogram of the select chunk its rows belong to, hist_part[selecting head][chunk][2048];
+// the host keeps a block inside one chunk.  The dynamic LDS holds kHistWords words per
+// selecting head of the block (none without hist_part).
+constexpr int kHistChunk = 16384;  // rows per select chunk (select.hip: kMbChunk)
+constexpr int kHistWords = 1024;
+
+__device__ __forceinline__ void hist_count(uint32_t* s_hist, float score) {
+  const uint32_t bin = float_to_key(score) >> 21;
+  atomicAdd(&s_hist[bin >> 1], 1u << ((bin & 1u) * 16));
+}
+
+template <int THREADS>
+__device__ __forceinline__ void hist_flush(const uint32_t* s_hist, uint32_t* __restrict__ dst) {
+  for (int i = threadIdx.x; i < kHistWords; i += THREADS) {
+    const uint32_t w = s_hist[i];
+    if (w & 0xffffu) atomicAdd(&dst[2 * i], w & 0xffffu);
+    if (w >> 16) atomicAdd(&dst[2 * i + 1], w >> 16);
+  }
+}
+
 template <typename T, int LPR, int G, bool GROUP_MAX>
 __global__ __launch_bounds__(256) void score_kernel(
     const typename T::store_t* __restrict__ klo, const float* __restrict__ qhat,
     float* __restrict__ scores, int Hkv, int S_max, int S_cap, int d, int rows_per_block,
-    Ragged rg, Paging pg) {
+    Ragged rg, Paging pg, uint32_t* __restrict__ hist_part, int hist_chunks) {
   constexpr int EPC = T::EPC;
+  constexpr int kSelHeads = GROUP_MAX ? 1 : G;  // selecting heads whose scores the block writes
+  extern __shared__ uint32_t s_hist[];          // [kSelHeads][kHistWords] when hist_part is given
   const int tid = threadIdx.x;
   const int unit = blockIdx.y;
   const int S = seq_rows(rg, unit / Hkv, S_max);  // the score buffer keeps the stride S_max
   if ((int)blockIdx.x * rows_per_block >= S) return;
   const int head0 = unit * G;  // first query head of the group, flattened over batch
+  const bool hist = hist_part != nullptr;
+  if (hist) {
+    for (int i = tid; i < kSelHeads * kHistWords; i += 256) s_hist[i] = 0u;
+    __syncthreads();
+  }
 
   const int lane = tid & 63;
   const int c = lane % LPR;
@@ -119,9 +156,13 @@ __global__ __launch_bounds__(256) void score_kernel(
 #pragma unroll
       for (int g = 1; g < G; ++g) m = fmaxf(m, sc[g]);
       scores[(size_t)unit * S_max + row] = m;
+      if (hist) hist_count(s_hist, m);
     } else {
 #pragma unroll
-      for (int g = 0; g < G; ++g) scores[(size_t)(head0 + g) * S_max + row] = sc[g];
+      for (int g = 0; g < G; ++g) {
+        scores[(size_t)(head0 + g) * S_max + row] = sc[g];
+        if (hist) hist_count(s_hist + g * kHistWords, sc[g]);
+      }
     }
   };
   const ContiguousRows rows{base, row_bytes};
@@ -134,6 +175,14 @@ __global__ __launch_bounds__(256) void score_kernel(
     score_rows_pipelined<T, LPR, G, 4>(rows, qr, row0, row_end, t0, t1, emit);
   } else {
     score_rows<T, LPR, G, 4>(rows, cact, qr, row0, row_end, emit);
+  }
+  if (hist) {
+    __syncthreads();
+    const size_t sel0 = GROUP_MAX ? (size_t)unit : (size_t)head0;
+#pragma unroll
+    for (int g = 0; g < kSelHeads; ++g)
+      hist_flush<256>(s_hist + g * kHistWords,
+                      hist_part + ((sel0 + g) * hist_chunks + row0 / kHistChunk) * 2048);
   }
 }
 
@@ -153,7 +202,10 @@ __global__ __launch_bounds__(256) void score_kernel(
 template <int NCH, int G, bool GROUP_MAX, bool TILE>
 __global__ __launch_bounds__(256) void score_mfma_kernel(
     const uint16_t* __restrict__ klo, const float* __restrict__ qhat, float* __restrict__ scores,
-    int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg, Paging pg) {
+    int Hkv, int S_max, int S_cap, int rows_per_block, Ragged rg, Paging pg,
+    uint32_t* __restrict__ hist_part, int hist_chunks) {
+  constexpr int kSelHeads = GROUP_MAX ? 1 : G;  // (histograms: one token per sequence only)
+  extern __shared__ uint32_t s_hist[];          // [kSelHeads][kHistWords] when hist_part is given
   const int lane = threadIdx.x & 63;
   const int r16 = lane & 15;
 
@@ -188,6 +240,11 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
     S = S_lane = seq_rows(rg, cache_b, S_max);  // the score buffer keeps the stride S_max
   }
   if ((int)blockIdx.x * rows_per_block >= S) return;
+  const bool hist = !TILE && hist_part != nullptr;
+  if (hist) {
+    for (int i = threadIdx.x; i < kSelHeads * kHistWords; i += 256) s_hist[i] = 0u;
+    __syncthreads();
+  }
 
   bf16x8_t bq[ScoreMfmaGeom<NCH>::NB][3];
   score_mfma_operands<NCH>(qhat + head * kD, head_ok, bq);
@@ -219,8 +276,22 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
         for (int i = 0; i < 4; ++i)
           if (rowbase + i < lane_end) dst[i] = v[i];
       }
+      if (hist) {
+        uint32_t* mine = s_hist + (GROUP_MAX ? 0 : r16) * kHistWords;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (rowbase + i < lane_end) hist_count(mine, v[i]);
+      }
     }
   });
+  if (hist) {
+    __syncthreads();
+    const size_t sel0 = GROUP_MAX ? (size_t)blockIdx.y : (size_t)blockIdx.y * G;
+#pragma unroll
+    for (int g = 0; g < kSelHeads; ++g)
+      hist_flush<256>(s_hist + g * kHistWords,
+                      hist_part + ((sel0 + g) * hist_chunks + row0 / kHistChunk) * 2048);
+  }
 }
 
 // tokens of one sequence that share a score block (TILE), and the blocks along z that takes
@@ -228,39 +299,44 @@ static int score_tile_tokens(const Shape& s) { return 16 / s.G; }
 
 template <int NCH, int G, bool TILE>
 static hipError_t launch_score_mfma_g(const Shape& s, int select_mode, const void* klo, float* scores,
-                                      const float* qhat, hipStream_t st) {
+                                      const float* qhat, uint32_t* hist_part, int hist_chunks,
+                                      hipStream_t st) {
   const int m = TILE ? s.rg.queries : 1;
   const int nz = TILE ? (m + score_tile_tokens(s) - 1) / score_tile_tokens(s) : 1;
   Shape blocks = s;  // the grid's y*z extent stands in for the batch when the row block is sized
   blocks.B = s.B / m * nz;
   const int rpb = score_rows_per_block(blocks);
   dim3 grid((s.S + rpb - 1) / rpb, s.B / m * s.Hkv, nz);
+  if (TILE) hist_part = nullptr;  // (several tokens per sequence keep the separate counting pass)
   if (select_mode == 1 && G > 1) {
-    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, (G > 1), TILE>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, (G > 1), TILE>), grid, dim3(256),
+                       hist_part ? kHistWords * 4 : 0, st, static_cast<const uint16_t*>(klo), qhat,
+                       scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg, hist_part, hist_chunks);
   } else {
-    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false, TILE>), grid, dim3(256), 0, st,
-                       static_cast<const uint16_t*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg);
+    hipLaunchKernelGGL((score_mfma_kernel<NCH, G, false, TILE>), grid, dim3(256),
+                       hist_part ? G * kHistWords * 4 : 0, st, static_cast<const uint16_t*>(klo), qhat,
+                       scores, s.Hkv, s.S, s.S_cap, rpb, s.rg, s.pg, hist_part, hist_chunks);
   }
   return hipGetLastError();
 }
 
 template <int NCH>
 static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const void* klo, float* scores,
-                                      const float* qhat, hipStream_t st) {
+                                      const float* qhat, uint32_t* hist_part, int hist_chunks,
+                                      hipStream_t st) {
   if (s.rg.queries > 1) {
     switch (s.G) {
-      case 1: return launch_score_mfma_g<NCH, 1, true>(s, select_mode, klo, scores, qhat, st);
-      case 2: return launch_score_mfma_g<NCH, 2, true>(s, select_mode, klo, scores, qhat, st);
-      case 4: return launch_score_mfma_g<NCH, 4, true>(s, select_mode, klo, scores, qhat, st);
-      case 8: return launch_score_mfma_g<NCH, 8, true>(s, select_mode, klo, scores, qhat, st);
+      case 1: return launch_score_mfma_g<NCH, 1, true>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+      case 2: return launch_score_mfma_g<NCH, 2, true>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+      case 4: return launch_score_mfma_g<NCH, 4, true>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+      case 8: return launch_score_mfma_g<NCH, 8, true>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
       default: return hipErrorInvalidValue;
     }
   }
   switch (s.G) {
-    case 2: return launch_score_mfma_g<NCH, 2, false>(s, select_mode, klo, scores, qhat, st);
-    case 4: return launch_score_mfma_g<NCH, 4, false>(s, select_mode, klo, scores, qhat, st);
-    case 8: return launch_score_mfma_g<NCH, 8, false>(s, select_mode, klo, scores, qhat, st);
+    case 2: return launch_score_mfma_g<NCH, 2, false>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 4: return launch_score_mfma_g<NCH, 4, false>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 8: return launch_score_mfma_g<NCH, 8, false>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -278,60 +354,67 @@ static bool score_mfma_applies(const Shape& s) {
 }
 
 static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* klo, float* scores,
-                                    const float* qhat, hipStream_t st) {
+                                    const float* qhat, uint32_t* hist_part, int hist_chunks,
+                                    hipStream_t st) {
   switch (s.d / 8) {
-    case 1: return launch_score_mfma_n<1>(s, select_mode, klo, scores, qhat, st);
-    case 2: return launch_score_mfma_n<2>(s, select_mode, klo, scores, qhat, st);
-    case 4: return launch_score_mfma_n<4>(s, select_mode, klo, scores, qhat, st);
-    case 8: return launch_score_mfma_n<8>(s, select_mode, klo, scores, qhat, st);
-    case 16: return launch_score_mfma_n<16>(s, select_mode, klo, scores, qhat, st);
+    case 1: return launch_score_mfma_n<1>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 2: return launch_score_mfma_n<2>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 4: return launch_score_mfma_n<4>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 8: return launch_score_mfma_n<8>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 16: return launch_score_mfma_n<16>(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 template <typename T, int LPR, int G>
 static hipError_t launch_score_g(const Shape& s, int select_mode, const void* q, const float* P,
-                                 const void* klo, float* scores, float* qhat, hipStream_t st) {
+                                 const void* klo, float* scores, float* qhat, uint32_t* hist_part,
+                                 int hist_chunks, hipStream_t st) {
   using ST = typename T::store_t;
   const int rpb = score_rows_per_block(s);
   dim3 grid((s.S + rpb - 1) / rpb, s.B * s.Hkv);
   const bool gm = (select_mode == 1) && (G > 1);
+  if (s.rg.queries > 1) hist_part = nullptr;  // (several tokens per sequence keep the separate counting pass)
   if (gm) {
-    hipLaunchKernelGGL((score_kernel<T, LPR, G, (G > 1)>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg);
+    hipLaunchKernelGGL((score_kernel<T, LPR, G, (G > 1)>), grid, dim3(256),
+                       hist_part ? kHistWords * 4 : 0, st, static_cast<const ST*>(klo), qhat, scores,
+                       s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg, hist_part, hist_chunks);
   } else {
-    hipLaunchKernelGGL((score_kernel<T, LPR, G, false>), grid, dim3(256), 0, st,
-                       static_cast<const ST*>(klo), qhat, scores, s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg);
+    hipLaunchKernelGGL((score_kernel<T, LPR, G, false>), grid, dim3(256),
+                       hist_part ? G * kHistWords * 4 : 0, st, static_cast<const ST*>(klo), qhat, scores,
+                       s.Hkv, s.S, s.S_cap, s.d, rpb, s.rg, s.pg, hist_part, hist_chunks);
   }
   return hipGetLastError();
 }
 
 template <typename T, int LPR>
 static hipError_t launch_score_l(const Shape& s, int select_mode, const void* q, const float* P,
-                                 const void* klo, float* scores, float* qhat, hipStream_t st) {
+                                 const void* klo, float* scores, float* qhat, uint32_t* hist_part,
+                                 int hist_chunks, hipStream_t st) {
   switch (s.G) {
-    case 1: return launch_score_g<T, LPR, 1>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 2: return launch_score_g<T, LPR, 2>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 4: return launch_score_g<T, LPR, 4>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 8: return launch_score_g<T, LPR, 8>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 1: return launch_score_g<T, LPR, 1>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 2: return launch_score_g<T, LPR, 2>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 4: return launch_score_g<T, LPR, 4>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 8: return launch_score_g<T, LPR, 8>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 template <typename T>
 static hipError_t launch_score_t(const Shape& s, int select_mode, const void* q, const float* P,
-                                 const void* klo, float* scores, float* qhat, hipStream_t st) {
+                                 const void* klo, float* scores, float* qhat, uint32_t* hist_part,
+                                 int hist_chunks, hipStream_t st) {
   const int nch = s.d / T::EPC;
   int lpr = 1;
   while (lpr < nch) lpr <<= 1;
   switch (lpr) {
-    case 1: return launch_score_l<T, 1>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 2: return launch_score_l<T, 2>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 4: return launch_score_l<T, 4>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 8: return launch_score_l<T, 8>(s, select_mode, q, P, klo, scores, qhat, st);
-    case 16: return launch_score_l<T, 16>(s, select_mode, q, P, klo, scores, qhat, st);
+    case 1: return launch_score_l<T, 1>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 2: return launch_score_l<T, 2>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 4: return launch_score_l<T, 4>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 8: return launch_score_l<T, 8>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
+    case 16: return launch_score_l<T, 16>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
     case 32:
-      if constexpr (T::EPC == 4) return launch_score_l<T, 32>(s, select_mode, q, P, klo, scores, qhat, st);
+      if constexpr (T::EPC == 4) return launch_score_l<T, 32>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
@@ -339,13 +422,13 @@ static hipError_t launch_score_t(const Shape& s, int select_mode, const void* q,
 
 template <typename T, bool APPEND>
 static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
-                                void* khi, void* v, hipStream_t st) {
+                                void* khi, void* v, uint32_t* zero_words, size_t n_zero, hipStream_t st) {
   using ST = typename T::store_t;
   const dim3 grid(s.B * s.Hkv, kD / kQrotCols), block(256);
 #define LOKI_QROT(GV)                                                                            \
   hipLaunchKernelGGL((qrot_kernel<T, GV, APPEND>), grid, block, 0, st, static_cast<const ST*>(q), P, \
                      qhat, s.Hkv, static_cast<ST*>(klo), static_cast<ST*>(khi), static_cast<ST*>(v), \
-                     s.S, s.S_cap, s.d, s.rg, s.ap, s.pg);                                       \
+                     s.S, s.S_cap, s.d, s.rg, s.ap, s.pg, zero_words, n_zero);                   \
   break
   switch (s.G) {
     case 1: LOKI_QROT(1);
@@ -359,19 +442,22 @@ static hipError_t launch_qrot_t(const Shape& s, const void* q, const float* P, f
 }
 
 hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
-                       void* khi, void* v, hipStream_t st) {
+                       void* khi, void* v, uint32_t* zero_words, size_t n_zero, hipStream_t st) {
   if (s.ap.k_new != nullptr)
-    return s.dtype == 0 ? launch_qrot_t<F32, true>(s, q, P, qhat, klo, khi, v, st)
-                        : launch_qrot_t<BF16, true>(s, q, P, qhat, klo, khi, v, st);
-  return s.dtype == 0 ? launch_qrot_t<F32, false>(s, q, P, qhat, klo, khi, v, st)
-                      : launch_qrot_t<BF16, false>(s, q, P, qhat, klo, khi, v, st);
+    return s.dtype == 0 ? launch_qrot_t<F32, true>(s, q, P, qhat, klo, khi, v, zero_words, n_zero, st)
+                        : launch_qrot_t<BF16, true>(s, q, P, qhat, klo, khi, v, zero_words, n_zero, st);
+  return s.dtype == 0 ? launch_qrot_t<F32, false>(s, q, P, qhat, klo, khi, v, zero_words, n_zero, st)
+                      : launch_qrot_t<BF16, false>(s, q, P, qhat, klo, khi, v, zero_words, n_zero, st);
 }
 
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
-                        const void* klo, float* scores, float* qhat, hipStream_t st) {
-  if (score_mfma_applies(s)) return launch_score_mfma(s, select_mode, klo, scores, qhat, st);
-  return s.dtype == 0 ? launch_score_t<F32>(s, select_mode, q, P, klo, scores, qhat, st)
-                      : launch_score_t<BF16>(s, select_mode, q, P, klo, scores, qhat, st);
+                        const void* klo, float* scores, float* qhat, uint32_t* hist_part,
+                        int hist_chunks, hipStream_t st) {
+  if (score_mfma_applies(s))
+    return launch_score_mfma(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
+  return s.dtype == 0
+             ? launch_score_t<F32>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st)
+             : launch_score_t<BF16>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st);
 }
 
 }  // namespace loki

@@ -562,11 +562,220 @@ __global__ __launch_bounds__(THREADS) void mb_write_kernel(const float* __restri
   }
 }
 
+// ---- long sequences, one pass over the scores -------------------------------------------------
+// When the score kernel has already counted the leading 11 key bits of every score into the
+// chunk histograms (one token per sequence), the selection needs one pass over the scores:
+//   bin        (head)         sum the chunk histograms, find the threshold bin; from the chunk
+//                             histograms alone, how many rows of every chunk lie above the bin
+//                             and inside it, i.e. where each chunk's rows go in the lists
+//                             (folded into every partition block instead, the search cost 64 MB of
+//                             histogram reads per step on the long-context workload and the
+//                             stage took twice as long)
+//   partition  (chunk, head)  keys in registers: rows above the bin are certain and go to the
+//                             index list in position order; rows inside the bin go to the
+//                             head's candidate list (key and position), also in position order
+//   resolve    (head)         exact threshold among the candidates; the chosen ones are appended
+//                             to the index list (if the candidates overflow their list — long
+//                             runs of equal scores — the plain digit-pass selection runs instead)
+//   merge      (head)         only when the caller wants the list: ascending merge of the two runs
+// The attention stage reads the two runs as they are.
+constexpr int kMb2Cap = kMbChunk;  // candidates per head
+__host__ __device__ inline int mb2_meta_stride(int nc) { return 8 + 2 * nc; }
+// per head: [0] bin, [1] rows needed from inside it, [2] certain rows, [3] candidates,
+//           [8 + 2c] certain rows before chunk c, [9 + 2c] candidates before chunk c
+
+__global__ __launch_bounds__(kMbThreads) void mb2_bin_kernel(const uint32_t* __restrict__ hist_part,
+                                                             uint32_t* __restrict__ meta, int S_max,
+                                                             int k_max, int nc, int heads_per_seq,
+                                                             Ragged rg) {
+  __shared__ ResidentSelectSmem<kMbThreads> sm;
+  __shared__ uint32_t s_gt[64], s_eq[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, head = blockIdx.x;
+  const int k = seq_keep(rg, head / heads_per_seq, k_max, seq_rows(rg, head / heads_per_seq, S_max));
+  const uint32_t* src = hist_part + (size_t)head * nc * 2048;
+  uint32_t h0 = 0, h1 = 0;
+  for (int c = 0; c < nc; ++c) {
+    h0 += src[(size_t)c * 2048 + tid];
+    h1 += src[(size_t)c * 2048 + tid + kMbThreads];
+  }
+  sm.hist[0][tid] = h0;
+  sm.hist[0][tid + kMbThreads] = h1;
+  __syncthreads();
+  resident_find_bin<kMbThreads>(sm, 0, (uint32_t)k);
+  const uint32_t bin1 = sm.out[0][0], rem1 = sm.out[0][1];
+  for (int c = wave; c < nc; c += kMbThreads / 64) {  // a wave per chunk
+    const uint32_t* hp = src + (size_t)c * 2048;
+    uint32_t g = 0;
+    for (int b = lane; b < 2048; b += 64) g += (uint32_t)b > bin1 ? hp[b] : 0u;
+    g = wave_inclusive_scan_u32(g);
+    if (lane == 63) {
+      s_gt[c] = g;
+      s_eq[c] = hp[bin1];
+    }
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t* m = meta + (size_t)head * mb2_meta_stride(nc);
+    uint32_t g = 0, e = 0;
+    for (int c = 0; c < nc; ++c) {
+      m[8 + 2 * c] = g;
+      m[9 + 2 * c] = e;
+      g += s_gt[c];
+      e += s_eq[c];
+    }
+    m[0] = bin1;
+    m[1] = rem1;
+    m[2] = g;  // = k - rem1
+    m[3] = e;
+  }
+}
+
+__global__ __launch_bounds__(kMbThreads) void mb2_partition_kernel(
+    const float* __restrict__ scores, const uint32_t* __restrict__ meta, int32_t* __restrict__ sel_idx,
+    float* __restrict__ sel_score, uint32_t* __restrict__ cand_key, int32_t* __restrict__ cand_pos,
+    int S_max, int k_max, int nc, int heads_per_seq, Ragged rg) {
+  __shared__ uint32_t s_wg[kMbThreads / 64], s_we[kMbThreads / 64];
+  const int chunk = blockIdx.x, head = blockIdx.y;
+  const int S = seq_rows(rg, head / heads_per_seq, S_max);
+  const int c0 = chunk * kMbChunk, n = max(min(S - c0, kMbChunk), 0);  // 0 past a short sequence's end
+  const uint32_t* m = meta + (size_t)head * mb2_meta_stride(nc);
+  const uint32_t bin1 = m[0], base_g = m[8 + 2 * chunk], base_e = m[9 + 2 * chunk];
+  int32_t* out = sel_idx + (size_t)head * k_max;
+  float* outs = sel_score + (size_t)head * k_max;
+  uint32_t* ck = cand_key + (size_t)head * kMb2Cap;
+  int32_t* cp = cand_pos + (size_t)head * kMb2Cap;
+  uint32_t key[kSelKPT];
+  uint32_t valid_mask;
+  resident_load_keys<kSelKPT>(scores + (size_t)head * S_max + c0, n, kSelKPT, key, valid_mask);
+  resident_partition<kMbThreads, kSelKPT>(
+      key, valid_mask, kSelKPT, bin1, s_wg, s_we,
+      [&](int rank, int pos, uint32_t kk) {
+        out[base_g + rank] = c0 + pos;
+        outs[base_g + rank] = key_to_float(kk);
+      },
+      [&](int rank, int pos, uint32_t kk) {
+        const uint32_t slot = base_e + (uint32_t)rank;
+        if (slot < (uint32_t)kMb2Cap) {
+          ck[slot] = kk;
+          cp[slot] = c0 + pos;
+        }
+      });
+}
+
+__global__ __launch_bounds__(kMbThreads) void mb2_resolve_kernel(
+    const float* __restrict__ scores, uint32_t* __restrict__ meta, const uint32_t* __restrict__ cand_key,
+    const int32_t* __restrict__ cand_pos, int32_t* __restrict__ sel_idx, float* __restrict__ sel_score,
+    int S_max, int k_max, int nc, int heads_per_seq, Ragged rg) {
+  __shared__ ResidentSelectSmem<kMbThreads> sm;
+  __shared__ SelectSmem<kMbThreads> generic;
+  const int tid = threadIdx.x, head = blockIdx.x;
+  const int S = seq_rows(rg, head / heads_per_seq, S_max);
+  const int k = seq_keep(rg, head / heads_per_seq, k_max, S);
+  uint32_t* m = meta + (size_t)head * mb2_meta_stride(nc);
+  const uint32_t rem1 = m[1], n_def = m[2], n_cand = m[3];
+  int32_t* out = sel_idx + (size_t)head * k_max;
+  float* outs = sel_score + (size_t)head * k_max;
+  if (n_cand > (uint32_t)kMb2Cap) {  // uniform
+    const float* a = scores + (size_t)head * S_max;
+    __syncthreads();  // everyone has read the bookkeeping
+    if (tid == 0) m[2] = (uint32_t)k;  // the whole list is one ascending run
+    block_select_topk<kMbThreads>(a, S, k, generic, [&](int rank, int pos) {
+      out[rank] = pos;
+      outs[rank] = a[pos];
+    });
+    return;
+  }
+  resident_select_clear<kMbThreads>(sm);
+  const uint32_t* ck = cand_key + (size_t)head * kMb2Cap;
+  const int32_t* cp = cand_pos + (size_t)head * kMb2Cap;
+  uint32_t key[kSelKPT];
+  uint32_t valid_mask;
+  resident_load_keys<kSelKPT>(ck, (int)n_cand, kSelKPT, key, valid_mask);
+#pragma unroll
+  for (int i = 0; i < kSelKPT; ++i) key[i] <<= 11;  // candidates agree on the top 11 bits: rank on the low 21
+  __syncthreads();
+  uint32_t Tp, need_eq;
+  resident_threshold<kMbThreads, kSelKPT>(key, valid_mask, rem1, sm, Tp, need_eq);
+  resident_compact<kMbThreads, kSelKPT>(key, valid_mask, kSelKPT, Tp, need_eq, 0u, 0u, sm.wave[0],
+                                        sm.wave[1], [&](int rank, int local, float) {
+                                          out[n_def + rank] = cp[local];
+                                          outs[n_def + rank] = key_to_float(ck[local]);
+                                        });
+}
+
+// The caller's copy of a head's list: the certain rows (ascending) and the chosen candidates
+// (ascending) merged into one ascending run, padded with -1 for a sequence that keeps fewer
+// than k_max rows.
+constexpr int kMergeThreads = 1024;
+constexpr int kMergeMaxK = 16384;  // list entries the merge holds in LDS (longer lists: from global)
+__global__ __launch_bounds__(kMergeThreads) void mb2_merge_kernel(
+    const int32_t* __restrict__ sel_idx, const uint32_t* __restrict__ meta,
+    int32_t* __restrict__ user_idx, int S_max, int k_max, int nc, int heads_per_seq, Ragged rg) {
+  __shared__ int32_t s_list[kMergeMaxK];
+  const int head = blockIdx.x;
+  const int k = seq_keep(rg, head / heads_per_seq, k_max, seq_rows(rg, head / heads_per_seq, S_max));
+  const int n_def = (int)meta[(size_t)head * mb2_meta_stride(nc) + 2];
+  const int32_t* glist = sel_idx + (size_t)head * k_max;
+  const bool in_lds = k <= kMergeMaxK;
+  if (in_lds) {
+    for (int i = threadIdx.x; i < k; i += kMergeThreads) s_list[i] = glist[i];
+    __syncthreads();
+  }
+  const int32_t* list = in_lds ? s_list : glist;
+  for (int i = threadIdx.x; i < k_max; i += kMergeThreads) {
+    if (i >= k) {
+      user_idx[(size_t)head * k_max + i] = -1;
+      continue;
+    }
+    const int pos = list[i];
+    const bool certain = i < n_def;
+    const int32_t* other = certain ? list + n_def : list;
+    int lo = 0, hi = certain ? k - n_def : n_def;
+    while (lo < hi) {  // entries of the other run below pos
+      const int mid = (lo + hi) >> 1;
+      if (other[mid] < pos) lo = mid + 1;
+      else hi = mid;
+    }
+    user_idx[(size_t)head * k_max + (certain ? i : i - n_def) + lo] = pos;
+  }
+}
+
 int select_chunks(int S) { return S > kMbChunk ? (S + kMbChunk - 1) / kMbChunk : 0; }
 size_t select_scratch_words(int S, int n_sel_heads) {
   const int nc = select_chunks(S);
   if (nc == 0 || nc > 64) return 0;
-  return (size_t)n_sel_heads * ((size_t)nc * 2048 + kMbChunk + mb_meta_stride(nc));
+  // chunk histograms, then either form's candidate lists and bookkeeping
+  return (size_t)n_sel_heads * ((size_t)nc * 2048 + 2 * (size_t)kMbChunk + mb_meta_stride(nc) + mb2_meta_stride(nc));
+}
+
+int select_hist_chunks(const Shape& s, int select_mode) {
+  const int nc = select_chunks(s.S);
+  // Grouped heads that each select for themselves keep the separate counting passes: with G
+  // histograms per score block the counting slows the score kernel by more than the saved pass
+  // (long-context workload, 4 heads per KV head: 212 us per step against 230 us).
+  if (s.G > 1 && select_mode == 0) return 0;
+  return (nc == 0 || nc > 64 || s.rg.queries > 1) ? 0 : nc;
+}
+
+static hipError_t launch_select_one_pass(const Shape& s, int heads, const float* scores,
+                                         int32_t* sel_idx, float* sel_score, uint32_t* scratch,
+                                         int32_t* user_idx, hipStream_t st) {
+  const int nc = select_chunks(s.S);
+  uint32_t* hist_part = scratch;  // filled by the score kernel
+  uint32_t* cand_key = hist_part + (size_t)heads * nc * 2048;
+  int32_t* cand_pos = reinterpret_cast<int32_t*>(cand_key + (size_t)heads * kMb2Cap);
+  uint32_t* meta = reinterpret_cast<uint32_t*>(cand_pos + (size_t)heads * kMb2Cap);
+  const int hps = heads / s.B;
+  hipLaunchKernelGGL(mb2_bin_kernel, dim3(heads), dim3(kMbThreads), 0, st, hist_part, meta, s.S, s.k, nc,
+                     hps, s.rg);
+  hipLaunchKernelGGL(mb2_partition_kernel, dim3(nc, heads), dim3(kMbThreads), 0, st, scores, meta, sel_idx,
+                     sel_score, cand_key, cand_pos, s.S, s.k, nc, hps, s.rg);
+  hipLaunchKernelGGL(mb2_resolve_kernel, dim3(heads), dim3(kMbThreads), 0, st, scores, meta, cand_key,
+                     cand_pos, sel_idx, sel_score, s.S, s.k, nc, hps, s.rg);
+  if (user_idx != nullptr)
+    hipLaunchKernelGGL(mb2_merge_kernel, dim3(heads), dim3(kMergeThreads), 0, st, sel_idx, meta, user_idx, s.S,
+                       s.k, nc, hps, s.rg);
+  return hipGetLastError();
 }
 
 static hipError_t launch_select_multiblock(const Shape& s, int heads, const float* scores,
@@ -608,7 +817,10 @@ extern "C" int loki_debug_read_select_ts(unsigned long long* host_dst, size_t co
 #endif
 
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
-                         float* sel_score, uint32_t* scratch, hipStream_t st) {
+                         float* sel_score, uint32_t* scratch, bool one_pass, int32_t* user_idx,
+                         hipStream_t st) {
+  if (scratch != nullptr && one_pass)
+    return launch_select_one_pass(s, n_sel_heads, scores, sel_idx, sel_score, scratch, user_idx, st);
   if (scratch != nullptr && select_scratch_words(s.S, n_sel_heads) != 0)
     return launch_select_multiblock(s, n_sel_heads, scores, sel_idx, sel_score, scratch, st);
   const int hps = n_sel_heads / s.B;  // selecting heads per sequence

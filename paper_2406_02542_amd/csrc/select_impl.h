@@ -428,7 +428,7 @@ __device__ __forceinline__ void resident_compact(const uint32_t (&key)[KPT], uin
 // Ordered split of the register-resident keys by their leading 11 bits against the threshold
 // bin: keys in a higher bin are certain to be selected, keys inside the bin are the candidates
 // among which the exact threshold lies.  emit_gt(rank, pos) sees every key above the bin with
-// its rank among those (ascending with pos); emit_eq(rank, pos, key) every key inside the bin
+// its rank among those (ascending with pos) and its key; emit_eq(rank, pos, key) every key inside the bin
 // likewise.  Same layout, scans and single barrier as resident_compact.
 template <int THREADS, int KPT, typename EmitGt, typename EmitEq>
 __device__ __forceinline__ void resident_partition(const uint32_t (&key)[KPT], uint32_t valid_mask,
@@ -476,7 +476,7 @@ __device__ __forceinline__ void resident_partition(const uint32_t (&key)[KPT], u
       if ((valid_mask >> (4 * j + e)) & 1u) {
         const uint32_t kk = key[4 * j + e];
         const uint32_t b = kk >> 21;
-        if (b > bin) emit_gt((int)g_before, wbase + 256 * j + e);
+        if (b > bin) emit_gt((int)g_before, wbase + 256 * j + e, kk);
         if (b == bin) emit_eq((int)e_before, wbase + 256 * j + e, kk);
         g_before += b > bin;
         e_before += b == bin;

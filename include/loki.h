@@ -13,8 +13,13 @@
  *     hipStream_t passed as void* (NULL = the default stream).  Calls enqueue
  *     work on `stream` and return without synchronising.
  *   - The caller owns every buffer, including the workspace.  The library
- *     allocates no device memory and keeps no state between calls; calls on
- *     different streams with different workspaces may overlap.
+ *     allocates no device memory and keeps no state between calls beyond
+ *     per-device facts it establishes once (the number of compute units, which
+ *     shapes grids and workspace layouts; the address of the built-in buffer of
+ *     loki_decode_attn_static; that a kernel's shared-memory limit has been
+ *     raised on the device); calls on different streams with different
+ *     workspaces may overlap.  Size a workspace with the device it will be used
+ *     on current.
  *   - Every entry point returns a loki_status.  Arguments are validated on the
  *     host before anything is launched; on any non-zero status nothing was
  *     enqueued, except LOKI_ERR_HIP, which reports a launch error.

@@ -14,9 +14,37 @@ namespace loki {
 static inline int div_up(int a, int b) { return (a + b - 1) / b; }
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+int device_cus() {
+  constexpr int kSlots = 64;
+  static std::atomic<int> cached[kSlots];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kSlots) {
+    (void)hipGetLastError();  // a size query without a device is not an error of a later launch
+    return kDefaultCUs;
+  }
+  int n = cached[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) {
+    (void)hipGetLastError();
+    n = kDefaultCUs;
+  }
+  cached[dev].store(n, std::memory_order_relaxed);
+  return n;
+}
+
+hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
+
 int score_rows_per_block(const Shape& s) {
   const int units = s.B * s.Hkv;
-  int nchunks = div_up(8 * kNumCU, units);
+  int nchunks = div_up(8 * device_cus(), units);
   const int max_chunks = div_up(s.S, 2 * kScoreRowsPerStep);
   if (nchunks > max_chunks) nchunks = max_chunks;
   if (nchunks < 1) nchunks = 1;
@@ -42,7 +70,7 @@ int gather_splits(const Shape& s, int select_mode) {
   const int heads = (select_mode == 1) ? s.B * s.Hkv : s.B * s.Hq;
   // about two blocks per CU: a block's set-up and merge cost as much as a few hundred rows, and
   // a launch that needs no split also needs no combine kernel
-  int n = div_up(2 * kNumCU, heads);
+  int n = div_up(2 * device_cus(), heads);
   const int max_n = s.k / 128 > 0 ? s.k / 128 : 1;
   if (n > max_n) n = max_n;
   const int min_n = div_up(s.k, kMaxGatherChunk);
@@ -52,7 +80,7 @@ int gather_splits(const Shape& s, int select_mode) {
 
 int dense_splits(const Shape& s) {
   const int units = s.B * s.Hkv;
-  int n = div_up(8 * kNumCU, units);
+  int n = div_up(8 * device_cus(), units);
   const int max_n = s.S / 256 > 0 ? s.S / 256 : 1;
   if (n > max_n) n = max_n;
   return n < 1 ? 1 : n;
@@ -641,7 +669,7 @@ int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** n
 int loki_stream_read(const void* buf, size_t bytes, void* stream) {
   if (!buf || bytes == 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(buf) & 15))
     return LOKI_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(loki::stream_read_kernel, dim3(loki::kNumCU), dim3(512), 0,
+  hipLaunchKernelGGL(loki::stream_read_kernel, dim3(loki::device_cus()), dim3(512), 0,
                      static_cast<hipStream_t>(stream), static_cast<const uint4*>(buf), bytes / 16);
   return hipGetLastError() == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
 }

@@ -360,7 +360,7 @@ __global__ __launch_bounds__(256) void jaccard_kernel(const int32_t* __restrict_
 
 // ---- launchers ----------------------------------------------------------------------------------
 int pca_chunks(int Hkv, long long N, int* rows_per_chunk) {
-  long long want = (2 * kNumCU + Hkv - 1) / Hkv;  // about two blocks per CU over all heads
+  long long want = (2 * device_cus() + Hkv - 1) / Hkv;  // about two blocks per CU over all heads
   long long rows = (N + want - 1) / want;
   if (rows < 1024) rows = 1024;
   rows = (rows + kGramTile - 1) / kGramTile * kGramTile;
@@ -404,13 +404,9 @@ hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, lon
                        sum_part, cov, N, nc);
   } else {
     const size_t lds = (size_t)kD * kJacPitch * sizeof(double);
-    static bool attr_set = false;  // benign race: every caller sets the same value
-    if (!attr_set) {
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      if (e != hipSuccess) return e;
-      attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};  // devices already set up
+    const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void*>(jacobi_kernel), (int)lds, lds_allowed);
+    if (ea != hipSuccess) return ea;
     hipLaunchKernelGGL(jacobi_kernel, dim3(Hkv), dim3(kJacThreads), lds, st, cov, vt, P, eigenvalues);
   }
   return hipGetLastError();

@@ -295,14 +295,10 @@ static hipError_t launch_fused_k(const Shape& s, const void* q, const float* P, 
   using ST = typename T::store_t;
   auto kern = fused_decode_kernel<T, LPR, REUSE_LO, KPT, APPEND, PAGED>;
   const size_t lds = fused_dynamic_lds(s);
-  static bool attr_set = false;  // benign race: every caller sets the same value
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)(kFusedMaxS * 4 + kFusedMaxK * 8));
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  static std::atomic<unsigned long long> lds_allowed{0};  // per instantiation: devices already set up
+  const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void*>(kern),
+                                          (int)(kFusedMaxS * 4 + kFusedMaxK * 8), lds_allowed);
+  if (ea != hipSuccess) return ea;
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(kFusedThreads), lds, st,
                      static_cast<const ST*>(klo), static_cast<const ST*>(khi),
                      static_cast<const ST*>(v), static_cast<const ST*>(q), P, static_cast<ST*>(out),

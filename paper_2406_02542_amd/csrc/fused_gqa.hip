@@ -21,12 +21,6 @@ constexpr int kGqaMaxK = kMaxGatherChunk;  // the index list lives in LDS
 #ifndef LOKI_GQA_SCORE_DEPTH
 #define LOKI_GQA_SCORE_DEPTH(NCH) ((NCH) == 4 ? 16 : 8)
 #endif
-#ifndef LOKI_GQA_STAGGER_TICKS
-#define LOKI_GQA_STAGGER_TICKS 0
-#endif
-#ifndef LOKI_GQA_PRIO
-#define LOKI_GQA_PRIO 0
-#endif
 
 // positions per thread in the select stage: ceil(S / threads) rounded up to a multiple of 4
 __host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
@@ -82,11 +76,6 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   const int k = seq_keep(rag, unit / Hkv, k_max, S);
   const int per_thread = gqa_keys_per_thread(S_max, THREADS);
 
-  if (LOKI_GQA_STAGGER_TICKS > 0 && gridDim.x >= 2 * kNumCU && blockIdx.x >= gridDim.x / 2) {
-    const unsigned long long t_start = wall_clock64();
-    while (wall_clock64() - t_start < (unsigned long long)LOKI_GQA_STAGGER_TICKS) __builtin_amdgcn_s_sleep(32);
-  }
-  if (LOKI_GQA_PRIO > 0 && blockIdx.x >= gridDim.x / 2) __builtin_amdgcn_s_setprio(LOKI_GQA_PRIO);
   LOKI_STAMP(0);
   resident_select_clear<THREADS>(s_sel);  // covered by the barriers of the next stages
 
@@ -291,7 +280,7 @@ bool fused_gqa_eligible(const Shape& s, int select_mode) {
 bool fused_gqa_preferred(const Shape& s, int select_mode) {
   if (!fused_gqa_eligible(s, select_mode)) return false;
   // one block per unit: worth it when the units alone fill the chip
-  return s.B * s.Hkv >= kNumCU;
+  return s.B * s.Hkv >= device_cus();
 }
 
 template <int THREADS, int NCH, int G, int KPT>
@@ -300,10 +289,10 @@ static hipError_t launch_fused_gqa_k(const Shape& s, const void* q, const float*
                                      hipStream_t st) {
   auto kern = fused_gqa_kernel<THREADS, NCH, G, KPT>;
   const size_t lds = GqaLds<THREADS, G>::total_bytes(s.S, s.k);
-  // the limit is a property of the function on the current device; setting it is cheap and
-  // keeps no state in the library
-  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  static std::atomic<unsigned long long> lds_allowed{0};  // per instantiation: devices already set up
+  const hipError_t e = allow_dynamic_lds(
+      reinterpret_cast<const void*>(kern),
+      (int)GqaLds<THREADS, G>::total_bytes(THREADS == 256 ? 8192 : 16384, kGqaMaxK), lds_allowed);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(THREADS), lds, st,
                      static_cast<const uint16_t*>(klo), static_cast<const uint16_t*>(khi),

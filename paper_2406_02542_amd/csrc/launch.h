@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace loki {
 
 constexpr int kD = 128;  // head dimension the kernels are written for
@@ -47,7 +49,16 @@ struct Shape {
 
 // Grid-shaping decisions; pure functions of the shape so that workspace sizing (host only)
 // and the launchers agree.
-constexpr int kNumCU = 256;              // MI355X
+constexpr int kDefaultCUs = 256;          // MI355X; what grids are shaped for when no device can be asked
+// Compute units of the calling thread's current device (asked once per device and remembered;
+// kDefaultCUs when there is no device, e.g. a size query on a machine without a GPU).  Grid
+// shapes and the workspace layout that follows from them are functions of the shape and of this.
+int device_cus();
+
+// Raises the dynamic-LDS limit of a kernel the first time it is launched on each device (the
+// attribute belongs to the function on one device; `done` is a bit mask of devices, one static
+// per kernel instantiation, so that the launch path makes no attribute call afterwards).
+hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done);
 constexpr int kScoreRowsPerStep = 256;   // rows one 256-thread block scores per step
 constexpr int kMaxGatherChunk = 2048;    // selected rows one attend block may own (LDS index list)
 constexpr int kFusedMaxS = 8192;         // fused single-kernel path: scores of a unit live in LDS

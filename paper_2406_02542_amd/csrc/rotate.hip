@@ -277,7 +277,8 @@ hipError_t launch_rotate(const Shape& s, const void* k_new, const float* P, void
     // tail are paid once per block, and on the benchmark prefill 8192 rows per block (one round
     // of blocks) took 289 us against 348 us with 2048 (four rounds).
     constexpr int kTripRows = 16 * kRotMfmaTPW * kRotMfmaWaves;
-    long long want = (n_items_ll * s.Hkv + kNumCU - 1) / kNumCU;
+    const int cus = device_cus();
+    long long want = (n_items_ll * s.Hkv + cus - 1) / cus;
     want = (want + kTripRows - 1) / kTripRows * kTripRows;
     int ipb_m = (int)(want < kRotMfmaMinItems ? kRotMfmaMinItems : want > kRotMfmaMaxItems ? kRotMfmaMaxItems : want);
     if (n_items < ipb_m) ipb_m = ((n_items + 15) / 16) * 16;

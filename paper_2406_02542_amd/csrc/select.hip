@@ -787,7 +787,7 @@ static hipError_t launch_select_multiblock(const Shape& s, int heads, const floa
   uint32_t* meta = cand + (size_t)heads * kMbChunk;
   const dim3 wide(nc, heads), narrow(heads), block(kMbThreads);
   const int hps = heads / s.B;  // selecting heads per sequence
-  const bool small_blocks = (long long)nc * heads >= 4 * kNumCU;
+  const bool small_blocks = (long long)nc * heads >= 4 * device_cus();
   if (small_blocks)
     hipLaunchKernelGGL(mb_hist_kernel<256>, wide, dim3(256), 0, st, scores, hist_part, s.S, nc, hps, s.rg);
   else

@@ -169,20 +169,24 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
   // rows (16 bytes per lane, four rows per instruction); stored straight from the accumulator
   // layout a row leaves in 32-byte pieces spread over the trip, which measured 10 % slower.
   // A row of the tile is 256 bytes = 8 units of 32 bytes; unit c of row r sits at unit
-  // c ^ ((r >> 1) & 7), which keeps both the 4-byte writes (8 rows of equal parity x 8 words)
-  // and the 16-byte reads off each other's banks without padding.
+  // c ^ ((r >> 1) & 7), which spreads the 8-byte writes (16 rows x one 32-byte unit) and the
+  // 16-byte reads over the banks without padding.
   typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
   unsigned char* stage = reinterpret_cast<unsigned char*>(&s_stage[wave][0]);
   auto trip = [&](int t0, const uint4 (&raw)[TPW][4], auto full_tag) {
     constexpr bool FULL = decltype(full_tag)::value;
-    // rows this lane holds per tile: +4*kgrp + {0,1} (even column) or {2,3} (odd column)
-    const int i0 = (r16 & 1) * 2;
     // The operands in LDS never change, but they must be re-read for every trip: hoisted out of
     // the loop, all 96 of them would live in registers and spill.  An offset the compiler
     // cannot see through (always 0) keeps the reads inside the trip.
     uint32_t opaque = 0;
     __asm__ volatile("" : "+v"(opaque));
     const uint4* bop = &s_B[0][0][0][0] + opaque;
+    // P_h is the A operand and the key tile the B operand (the operand layouts are alike, so
+    // the LDS image and the key loads are what they would be the other way round): the
+    // accumulator of column block nb then holds, for this lane's ONE row r16, the four
+    // neighbouring columns 16 nb + 4 kgrp .. + 3, which are packed in registers and leave as one
+    // 8-byte LDS store (with the keys as A operand a lane held one column of four rows, and
+    // pairing neighbouring columns took a lane exchange and two selects per value).
 #pragma unroll
     for (int nb = 0; nb < 8; nb += 2) {
       rot_f32x4_t acc[TPW][2];
@@ -201,29 +205,19 @@ __global__ __launch_bounds__(kRotMfmaThreads) void rotate_mfma_kernel(
 #pragma unroll
           for (int u = 0; u < TPW; ++u) {
             const rot_bf16x8_t a = __builtin_bit_cast(rot_bf16x8_t, raw[u][step]);
-            acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b0, acc[u][0], 0, 0, 0);
-            acc[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b1, acc[u][1], 0, 0, 0);
+            acc[u][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b0, a, acc[u][0], 0, 0, 0);
+            acc[u][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b1, a, acc[u][1], 0, 0, 0);
           }
         }
 #pragma unroll
       for (int u = 0; u < TPW; ++u)
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-          // neighbour lane (r16 ^ 1) holds the other column of the pair for the same rows
-          float other[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) other[i] = dpp_mov<kDppQuadXor1>(acc[u][half][i]);
-#pragma unroll
-          for (int ii = 0; ii < 2; ++ii) {
-            const int i = i0 + ii;
-            const float mine = (r16 & 1) ? acc[u][half][2 + ii] : acc[u][half][ii];
-            const float lo_col = (r16 & 1) ? other[i] : mine;
-            const float hi_col = (r16 & 1) ? mine : other[i];
-            const int rt = 4 * kgrp + i;  // row of the tile
-            const int unit = (nb + half) ^ ((rt >> 1) & 7);
-            *reinterpret_cast<uint32_t*>(stage + (u * 16 + rt) * 256 + unit * 32 + (r16 & ~1) * 2) =
-                BF16::round2(lo_col, hi_col);
-          }
+          const int rt = r16;  // row of the tile
+          const int unit = (nb + half) ^ ((rt >> 1) & 7);
+          *reinterpret_cast<uint2*>(stage + (u * 16 + rt) * 256 + unit * 32 + kgrp * 8) =
+              make_uint2(BF16::round2(acc[u][half][0], acc[u][half][1]),
+                         BF16::round2(acc[u][half][2], acc[u][half][3]));
         }
     }
     __builtin_amdgcn_wave_barrier();

@@ -211,6 +211,9 @@ def bench_configs(args, torch, api, synth):
                          "speedup_vs_dense": dense_us / med,
                          "kernels_us": kern,
                          "dominant_kernel": max(kern, key=lambda n: kern[n]) if kern else None}
+                    # recorded counters (all kernels of one step summed), where the table has the point
+                    e["traffic"], e["traffic_recorded_in"] = recorded_traffic(
+                        f"{name} d={w.d} k={w.k} mode={mode}", "step")
                     if grouped_literal:
                         # every query head gathers its own k rows; heads of a group pick largely the
                         # same rows and share them in cache, so this is a count of requested bytes,

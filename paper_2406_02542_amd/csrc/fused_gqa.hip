@@ -77,17 +77,34 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   const int per_thread = gqa_keys_per_thread(S_max, THREADS);
 
   LOKI_STAMP(0);
+#ifdef LOKI_PHASE_TIMING
+  // where the block runs: XCC_ID (hardware register 20) above HW_ID (register 4: CU in bits 8-11,
+  // shader array bit 12, shader engine bits 13-15)
+  if (threadIdx.x == 0 && blockIdx.x < 8192)
+    g_phase_ts[blockIdx.x * kPhaseSlots + 15] =
+        ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32) |
+        (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4);
+#endif
   resident_select_clear<THREADS>(s_sel);  // covered by the barriers of the next stages
 
-  // the first slab loads need no query: they are in flight during the rotation
+  // Loads return in the order they were issued, so they are issued in the order their results
+  // are needed: the queries, this thread's entries of P_h, then the first slab loads, which need
+  // no query and stay in flight during the rotation (issued first, they would hold P_h back
+  // behind the whole chip's first burst of slab rows).
   constexpr int kDepth = LOKI_GQA_SCORE_DEPTH(NCH);
+  constexpr int kQPerThread = (G * kD + THREADS - 1) / THREADS;
   const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * (size_t)(d * 2);
   ScoreMfmaBufs<NCH, kDepth> sbufs;
-  score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
 
   // ---- qhat = q P_h for the G heads, with the association every path uses (8 parts of 16 terms,
   // parts added in order): wave w owns parts w PPW .. w PPW + PPW - 1, lane l columns 2l, 2l+1 ----
   {
+    float qv[kQPerThread];
+#pragma unroll
+    for (int j = 0; j < kQPerThread; ++j) {
+      const int i = tid + j * THREADS;
+      qv[j] = BF16::load1(q + head0 * kD + (i < G * kD ? i : 0));
+    }
     float2 pv[PPW][kRotPartLen];
     const float* Ph = P + (size_t)h * kD * kD + 2 * lane;
 #pragma unroll
@@ -95,7 +112,13 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
 #pragma unroll
       for (int ii = 0; ii < kRotPartLen; ++ii)
         pv[pp][ii] = *reinterpret_cast<const float2*>(Ph + (size_t)((wave * PPW + pp) * kRotPartLen + ii) * kD);
-    for (int i = tid; i < G * kD; i += THREADS) s_q[i] = BF16::load1(q + head0 * kD + i);
+    __builtin_amdgcn_sched_barrier(0);
+    score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
+#pragma unroll
+    for (int j = 0; j < kQPerThread; ++j) {
+      const int i = tid + j * THREADS;
+      if (i < G * kD) s_q[i] = qv[j];
+    }
     __syncthreads();
 #pragma unroll
     for (int g = 0; g < G; ++g)

@@ -44,7 +44,10 @@ hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned
 
 int score_rows_per_block(const Shape& s) {
   const int units = s.B * s.Hkv;
-  int nchunks = div_up(8 * device_cus(), units);
+#ifndef LOKI_SCORE_BLOCKS_PER_CU
+#define LOKI_SCORE_BLOCKS_PER_CU 8
+#endif
+  int nchunks = div_up(LOKI_SCORE_BLOCKS_PER_CU * device_cus(), units);
   const int max_chunks = div_up(s.S, 2 * kScoreRowsPerStep);
   if (nchunks > max_chunks) nchunks = max_chunks;
   if (nchunks < 1) nchunks = 1;
@@ -103,6 +106,8 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
     w.scores = reinterpret_cast<float*>(take(heads_sel * s.S * sizeof(float)));
     w.sel_idx = reinterpret_cast<int32_t*>(take(heads_sel * s.k * sizeof(int32_t)));
     w.sel_score = reinterpret_cast<float*>(take(heads_sel * s.k * sizeof(float)));
+    w.ticket_words = align_up(heads_q * sizeof(int32_t), 256) / 4;
+    w.tickets = reinterpret_cast<int32_t*>(take(w.ticket_words * 4));
     const size_t scratch_words = select_scratch_words(s.S, (int)heads_sel);
     w.sel_scratch = scratch_words ? reinterpret_cast<uint32_t*>(take(scratch_words * 4)) : nullptr;
     if (scratch_words && !p) w.sel_scratch = nullptr;
@@ -403,7 +408,9 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   uint32_t* hist_part = hist_chunks ? w.sel_scratch : nullptr;
   if (hist_chunks) idx = w.sel_idx;
   tm.begin("rotate_query");
-  e = launch_qrot(s, q, P, w.qhat, klo, khi, v, hist_part, (size_t)heads_sel * hist_chunks * 2048, st);
+  // (the tickets lie directly before the select scratch, whose first words the histograms are)
+  e = launch_qrot(s, q, P, w.qhat, klo, khi, v, reinterpret_cast<uint32_t*>(w.tickets),
+                  w.ticket_words + (size_t)heads_sel * hist_chunks * 2048, st);
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("score");
@@ -416,16 +423,11 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   tm.end();
   if (e != hipSuccess) return LOKI_ERR_HIP;
   tm.begin("gather_attend");
-  e = launch_gather(s, select_mode, nsplit, w.qhat, klo, khi, v, idx, w.sel_score, w.partial, out, st);
+  // (with several row splits the block that finishes a head group last merges them)
+  e = launch_gather(s, select_mode, nsplit, w.qhat, klo, khi, v, idx, w.sel_score, w.partial,
+                    w.tickets, out, st);
   tm.end();
-  if (e != hipSuccess) return LOKI_ERR_HIP;
-  if (nsplit > 1) {
-    tm.begin("combine");
-    e = launch_combine(s, nsplit, w.partial, out, st);
-    tm.end();
-    if (e != hipSuccess) return LOKI_ERR_HIP;
-  }
-  return LOKI_OK;
+  return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
 }
 
 int loki_decode_attn(const loki_layout* layout, const void* q, const float* P, const void* klo,

@@ -25,8 +25,9 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
     const void* __restrict__ qv,    // GATHER: qhat fp32 [B*Hq, 128]; dense: q storage [B*Hq, 128]
     const int32_t* __restrict__ sel_idx,   // GATHER: [blocks_y, n]
     const float* __restrict__ sel_score,   // REUSE_LO: [blocks_y, n] approximate scores of sel_idx
-    float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
-    void* __restrict__ out,         // [B*Hq, 128] storage type when nsplit == 1
+    float* partial,                 // [B*Hq, nsplit, 130] when nsplit > 1
+    int32_t* tickets,               // [blocks_y] zeroed, or null: the merge of the splits is a launch of its own
+    void* __restrict__ out,         // [B*Hq, 128] storage type; written here unless nsplit > 1 and no tickets
     int Hq, int Gq, int S_cap, int d, int n_max, int rows_per_block, int nsplit, int S_max, Ragged rag, Paging pg,
     int xcd_group_blocks, int xcd_sets) {
   using ST = typename T::store_t;
@@ -119,53 +120,32 @@ __global__ __launch_bounds__(kAttThreads) void attend_kernel(
       T::store1(static_cast<ST*>(out) + head * kD + col, os / ls);
     } else {
       float* pr = partial + (head * nsplit + bx) * kPartialStride;
-      pr[col] = os;
+      const bool shared = tickets != nullptr;  // another block of this launch reads them
+      store_shared_f32(pr + col, os, shared);
       if (col == 0) {
-        pr[kD] = mn;
-        pr[kD + 1] = ls;
+        store_shared_f32(pr + kD, mn, shared);
+        store_shared_f32(pr + kD + 1, ls, shared);
       }
+    }
+  }
+  if (nsplit > 1 && tickets != nullptr && splits_all_done(tickets + by, nsplit)) {
+    for (int i = tid; i < NH * kD; i += kAttThreads) {
+      const size_t head = (size_t)(head0 + i / kD);
+      T::store1(static_cast<ST*>(out) + head * kD + i % kD,
+                combine_splits<true>(partial + head * nsplit * kPartialStride, nsplit, i % kD));
     }
   }
 }
 
-// Merges the nsplit partial results of each query head: out = sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).
-// Loads are issued in independent batches of 8 splits so that the merge costs a few memory
-// round trips, not one per split.
+// Merges the nsplit partial results of each query head (launches that have no ticket array:
+// the dense baseline and Algorithm 2 of Appendix E).
 template <typename T>
 __global__ __launch_bounds__(kD) void combine_kernel(const float* __restrict__ partial,
                                                      typename T::store_t* __restrict__ out,
                                                      int nsplit) {
-  constexpr int B8 = 8;
   const size_t head = blockIdx.x;
   const int col = threadIdx.x;
-  const float* pr = partial + head * nsplit * kPartialStride;
-  float mn = kNegBig;
-  for (int i0 = 0; i0 < nsplit; i0 += B8) {
-    float mi[B8];
-#pragma unroll
-    for (int u = 0; u < B8; ++u) mi[u] = (i0 + u < nsplit) ? pr[(i0 + u) * kPartialStride + kD] : kNegBig;
-#pragma unroll
-    for (int u = 0; u < B8; ++u) mn = fmaxf(mn, mi[u]);
-  }
-  float ls = 0.f, os = 0.f;
-  for (int i0 = 0; i0 < nsplit; i0 += B8) {
-    float mi[B8], li[B8], oi[B8];
-#pragma unroll
-    for (int u = 0; u < B8; ++u) {
-      const bool ok = i0 + u < nsplit;
-      const float* p = pr + (ok ? (i0 + u) : 0) * kPartialStride;
-      mi[u] = ok ? p[kD] : kNegBig;
-      li[u] = ok ? p[kD + 1] : 0.f;
-      oi[u] = ok ? p[col] : 0.f;
-    }
-#pragma unroll
-    for (int u = 0; u < B8; ++u) {
-      const float f = fast_exp2(mi[u] - mn);
-      ls = fmaf(li[u], f, ls);
-      os = fmaf(oi[u], f, os);
-    }
-  }
-  T::store1(out + head * kD + col, os / ls);
+  T::store1(out + head * kD + col, combine_splits<false>(partial + head * nsplit * kPartialStride, nsplit, col));
 }
 
 // ---- launchers ------------------------------------------------------------------------
@@ -173,7 +153,7 @@ template <typename T, int NH, bool GATHER>
 static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block, const void* k_a,
                                    const void* k_b, const void* v, const void* qv,
                                    const int32_t* sel_idx, const float* sel_score, float* partial,
-                                   void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
+                                   int32_t* tickets, void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
                                    const Ragged& rg, const Paging& pg, int xcd_group_blocks,
                                    int xcd_sets, hipStream_t st) {
   // the saved ranking score replaces the low-rank slab read when one head owns the selection
@@ -181,12 +161,12 @@ static hipError_t launch_attend_nh(int blocks_y, int nsplit, int rows_per_block,
   constexpr bool kCanReuse = GATHER && NH == 1;
   if (kCanReuse && sel_score != nullptr) {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, kCanReuse>), dim3(nsplit, blocks_y),
-                       dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
+                       dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, tickets,
+                       out, Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
   } else {
     hipLaunchKernelGGL((attend_kernel<T, NH, GATHER, false>), dim3(nsplit, blocks_y),
-                       dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, out,
-                       Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
+                       dim3(kAttThreads), 0, st, k_a, k_b, v, qv, sel_idx, sel_score, partial, tickets,
+                       out, Hq, Gq, S_cap, d, n, rows_per_block, nsplit, S_max, rg, pg, xcd_group_blocks, xcd_sets);
   }
   return hipGetLastError();
 }
@@ -195,12 +175,12 @@ template <typename T, bool GATHER>
 static hipError_t launch_attend_t(int NH, int blocks_y, int nsplit, int rows_per_block,
                                   const void* k_a, const void* k_b, const void* v, const void* qv,
                                   const int32_t* sel_idx, const float* sel_score, float* partial,
-                                  void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
+                                  int32_t* tickets, void* out, int Hq, int Gq, int S_cap, int d, int n, int S_max,
                                   const Ragged& rg, const Paging& pg, int xcd_group_blocks,
                                   int xcd_sets, hipStream_t st) {
 #define LOKI_ATT(NHV)                                                                          \
   return launch_attend_nh<T, NHV, GATHER>(blocks_y, nsplit, rows_per_block, k_a, k_b, v, qv,   \
-                                          sel_idx, sel_score, partial, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, \
+                                          sel_idx, sel_score, partial, tickets, out, Hq, Gq, S_cap, d, n, S_max, rg, pg, \
                                           xcd_group_blocks, xcd_sets, st)
   switch (NH) {
     case 1: LOKI_ATT(1);
@@ -216,10 +196,11 @@ static inline int div_up(int a, int b) { return (a + b - 1) / b; }
 
 hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
-                         const float* sel_score, float* partial, void* out, hipStream_t st) {
+                         const float* sel_score, float* partial, int32_t* tickets, void* out,
+                         hipStream_t st) {
   const int NH = (select_mode == 1) ? s.G : 1;
   if (attend_mfma_applies(s, NH))
-    return launch_gather_mfma(s, nsplit, qhat, klo, khi, v, sel_idx, partial, out, st);
+    return launch_gather_mfma(s, nsplit, qhat, klo, khi, v, sel_idx, partial, tickets, out, st);
   int blocks_y = s.B * s.Hq / NH;
   const int rpb = div_up(s.k, nsplit);
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
@@ -235,9 +216,9 @@ hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const floa
   }
   if (s.dtype == 0)
     return launch_attend_t<F32, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                      sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
+                                      sel_score, partial, tickets, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
   return launch_attend_t<BF16, true>(NH, blocks_y, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     sel_score, partial, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
+                                     sel_score, partial, tickets, out, s.Hq, s.G, s.S_cap, s.d, s.k, s.S, s.rg, s.pg, xcd, sets, st);
 }
 
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
@@ -247,17 +228,17 @@ hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k
   const int rpb = div_up(s.S, nsplit);
   if (s.dtype == 0)
     return launch_attend_t<F32, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                       nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
+                                       nullptr, partial, nullptr, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
   return launch_attend_t<BF16, false>(s.G, blocks_y, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      nullptr, partial, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
+                                      nullptr, partial, nullptr, out, s.Hq, s.G, s.S_cap, kD, s.S, s.S, s.rg, Paging{}, 0, 0, st);
 }
 
 template <typename T, int NH>
 static hipError_t launch_pca_nh(const Shape& s, int nsplit, int rpb, const float* qhat, const void* klo,
                                 const void* v, float* partial, void* out, hipStream_t st) {
   hipLaunchKernelGGL((attend_kernel<T, NH, false, false, true>), dim3(nsplit, s.B * s.Hkv),
-                     dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, out,
-                     s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{}, 0, 0);
+                     dim3(kAttThreads), 0, st, klo, nullptr, v, qhat, nullptr, nullptr, partial, nullptr,
+                     out, s.Hq, s.G, s.S_cap, s.d, s.S, rpb, nsplit, s.S, s.rg, Paging{}, 0, 0);
   return hipGetLastError();
 }
 

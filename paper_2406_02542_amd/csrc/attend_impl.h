@@ -181,6 +181,76 @@ __device__ __forceinline__ void attend_publish(AttendAcc<T, NH>& acc, MergeSmem<
   __syncthreads();
 }
 
+// Partial results that another block of the same launch will read (the merge by the last
+// block, below) are stored and loaded as device-scope relaxed atomics: such a store is written
+// through to the level all XCDs share and such a load is served from there, so no block has to
+// write back or invalidate a whole L2 (a device-scope fence per block costs tens of
+// microseconds on this part: measured 33 -> 144 us on a 512-block gather).
+__device__ __forceinline__ void store_shared_f32(float* p, float v, bool device_scope) {
+  if (device_scope) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+template <bool DEVICE_SCOPE>
+__device__ __forceinline__ float load_shared_f32(const float* p) {
+  if constexpr (DEVICE_SCOPE) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+
+// Merge of the nsplit partial results of one query head, column col:
+// sum_i o_i 2^(m_i - M) / sum_i l_i 2^(m_i - M).  Loads are issued in independent batches of 8
+// splits so that the merge costs a few memory round trips, not one per split.
+template <bool DEVICE_SCOPE>
+__device__ __forceinline__ float combine_splits(const float* pr, int nsplit, int col) {
+  constexpr int B8 = 8;
+  float mn = kNegBig;
+  for (int i0 = 0; i0 < nsplit; i0 += B8) {
+    float mi[B8];
+#pragma unroll
+    for (int u = 0; u < B8; ++u)
+      mi[u] = (i0 + u < nsplit) ? load_shared_f32<DEVICE_SCOPE>(pr + (i0 + u) * kPartialStride + kD) : kNegBig;
+#pragma unroll
+    for (int u = 0; u < B8; ++u) mn = fmaxf(mn, mi[u]);
+  }
+  float ls = 0.f, os = 0.f;
+  for (int i0 = 0; i0 < nsplit; i0 += B8) {
+    float mi[B8], li[B8], oi[B8];
+#pragma unroll
+    for (int u = 0; u < B8; ++u) {
+      const bool ok = i0 + u < nsplit;
+      const float* p = pr + (ok ? (i0 + u) : 0) * kPartialStride;
+      const float m_ = load_shared_f32<DEVICE_SCOPE>(p + kD), l_ = load_shared_f32<DEVICE_SCOPE>(p + kD + 1);
+      const float o_ = load_shared_f32<DEVICE_SCOPE>(p + col);
+      mi[u] = ok ? m_ : kNegBig;
+      li[u] = ok ? l_ : 0.f;
+      oi[u] = ok ? o_ : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < B8; ++u) {
+      const float f = fast_exp2(mi[u] - mn);
+      ls = fmaf(li[u], f, ls);
+      os = fmaf(oi[u], f, os);
+    }
+  }
+  return os / ls;
+}
+
+// The row splits of a head group are merged by whichever of its blocks finishes last, so the
+// merge needs no launch of its own.  Call after the block's partials are stored (with
+// store_shared_f32 at device scope), by every thread of the block; `ticket` counts the group's
+// finished blocks and is zero when the launch starts.  Every thread waits until its own stores
+// are acknowledged (vmcnt(0)), the barrier collects the block, and only then one thread takes
+// the ticket with a device-scope atomic; the block that draws the last one reads the others'
+// partials with device-scope loads issued after that atomic has returned.  No block waits for
+// another.
+__device__ __forceinline__ bool splits_all_done(int32_t* ticket, int nsplit) {
+  __shared__ int s_last_block;
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0); expcnt and lgkmcnt left alone
+  __syncthreads();
+  if (threadIdx.x == 0) s_last_block = (atomicAdd(ticket, 1) == nsplit - 1) ? 1 : 0;
+  __syncthreads();
+  return s_last_block != 0;
+}
+
 // Merged (max, sum, output) of head g, column col over the block's waves.
 template <int WAVES, int NH>
 __device__ __forceinline__ void attend_merged(const MergeSmem<WAVES, NH>& sm, int g, int col,

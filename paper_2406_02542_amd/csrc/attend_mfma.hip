@@ -40,8 +40,9 @@ __global__ __launch_bounds__(kAmThreads, 2) void attend_mfma_kernel(
     const void* __restrict__ v,     // [units, S_cap, 128]
     const void* __restrict__ qv,    // GATHER: qhat fp32 [B*Hq, 128]; dense: q bf16 [B*Hq, 128]
     const int32_t* __restrict__ sel_idx,  // GATHER: [blocks_y, n]
-    float* __restrict__ partial,    // [B*Hq, nsplit, 130] when nsplit > 1
-    uint16_t* __restrict__ out,     // [B*Hq, 128] bf16 when nsplit == 1
+    float* partial,                 // [B*Hq, nsplit, 130] when nsplit > 1
+    int32_t* tickets,               // [KV units] zeroed, or null: the merge of the splits is a launch of its own
+    uint16_t* __restrict__ out,     // [B*Hq, 128] bf16; written here unless nsplit > 1 and no tickets
     int S_cap, int d, int n_max, int rows_per_block, int nsplit, int Hkv, int S_max, Ragged rg,
     Paging pg) {
   constexpr bool kRotated = GATHER || LO_ONLY;  // the query is the fp32 rotated one
@@ -110,11 +111,19 @@ __global__ __launch_bounds__(kAmThreads, 2) void attend_mfma_kernel(
       out[head * kD + col] = BF16::round(os / ls);
     } else {
       float* pr = partial + (head * nsplit + blockIdx.x) * kPartialStride;
-      pr[col] = os;
+      const bool shared = tickets != nullptr;  // another block of this launch reads them
+      store_shared_f32(pr + col, os, shared);
       if (col == 0) {
-        pr[kD] = mn;
-        pr[kD + 1] = ls;
+        store_shared_f32(pr + kD, mn, shared);
+        store_shared_f32(pr + kD + 1, ls, shared);
       }
+    }
+  }
+  if (nsplit > 1 && tickets != nullptr && splits_all_done(tickets + kv_unit, nsplit)) {
+    for (int i = tid; i < NH * kD; i += kAmThreads) {
+      const size_t head = head0 + i / kD;
+      out[head * kD + i % kD] =
+          BF16::round(combine_splits<true>(partial + head * nsplit * kPartialStride, nsplit, i % kD));
     }
   }
 }
@@ -122,19 +131,19 @@ __global__ __launch_bounds__(kAmThreads, 2) void attend_mfma_kernel(
 template <bool GATHER>
 static hipError_t launch_attend_mfma_nh(int NH, int blocks_y, int nsplit, int rpb, const void* k_a,
                                         const void* k_b, const void* v, const void* qv,
-                                        const int32_t* sel_idx, float* partial, void* out, int S_cap,
-                                        int d, int n, int Hkv, int S_max, const Ragged& rg,
+                                        const int32_t* sel_idx, float* partial, int32_t* tickets,
+                                        void* out, int S_cap, int d, int n, int Hkv, int S_max, const Ragged& rg,
                                         const Paging& pg, hipStream_t st) {
   const dim3 grid(nsplit, blocks_y), block(kAmThreads);
   uint16_t* o16 = static_cast<uint16_t*>(out);
   switch (NH) {
     case 4:
       hipLaunchKernelGGL((attend_mfma_kernel<4, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
+                         partial, tickets, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
       break;
     case 8:
       hipLaunchKernelGGL((attend_mfma_kernel<8, GATHER>), grid, block, 0, st, k_a, k_b, v, qv, sel_idx,
-                         partial, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
+                         partial, tickets, o16, S_cap, d, n, rpb, nsplit, Hkv, S_max, rg, pg);
       break;
     default:
       return hipErrorInvalidValue;
@@ -150,7 +159,7 @@ static hipError_t launch_pca_mfma_nh(const Shape& s, int nsplit, int rpb, const 
   uint16_t* o16 = static_cast<uint16_t*>(out);
 #define LOKI_PCA_MFMA(KS)                                                                          \
   hipLaunchKernelGGL((attend_mfma_kernel<NH, false, KS, true>), grid, block, 0, st, klo, nullptr, v, \
-                     qhat, nullptr, partial, o16, s.S_cap, s.d, s.S, rpb, nsplit, s.Hkv, s.S, s.rg,  \
+                     qhat, nullptr, partial, nullptr, o16, s.S_cap, s.d, s.S, rpb, nsplit, s.Hkv, s.S, s.rg,  \
                      Paging{});                                                                    \
   break
   switch ((s.d + 31) / 32) {
@@ -180,16 +189,16 @@ hipError_t launch_dense_mfma(const Shape& s, int nsplit, const void* q, const vo
                              const void* v, float* partial, void* out, hipStream_t st) {
   const int rpb = (s.S + nsplit - 1) / nsplit;
   return launch_attend_mfma_nh<false>(s.G, s.B * s.Hkv, nsplit, rpb, k_full, nullptr, v, q, nullptr,
-                                      partial, out, s.S_cap, kD, s.S, s.Hkv, s.S, s.rg, Paging{}, st);
+                                      partial, nullptr, out, s.S_cap, kD, s.S, s.Hkv, s.S, s.rg, Paging{}, st);
 }
 
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
                               const void* khi, const void* v, const int32_t* sel_idx, float* partial,
-                              void* out, hipStream_t st) {
+                              int32_t* tickets, void* out, hipStream_t st) {
   const int rpb = (s.k + nsplit - 1) / nsplit;
   if (rpb > kMaxGatherChunk) return hipErrorInvalidValue;
   return launch_attend_mfma_nh<true>(s.G, s.B * s.Hkv, nsplit, rpb, klo, khi, v, qhat, sel_idx,
-                                     partial, out, s.S_cap, s.d, s.k, s.Hkv, s.S, s.rg, s.pg, st);
+                                     partial, tickets, out, s.S_cap, s.d, s.k, s.Hkv, s.S, s.rg, s.pg, st);
 }
 
 }  // namespace loki

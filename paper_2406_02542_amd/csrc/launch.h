@@ -73,6 +73,9 @@ struct Workspace {
   float* scores;     // [B*Hsel, S]
   int32_t* sel_idx;  // [B*Hsel, k]
   float* sel_score;  // [B*Hsel, k] approximate scores of the selected rows
+  int32_t* tickets;  // [B*Hq] finished row splits per head group; directly before sel_scratch, so
+                     // that the rotation kernel clears it and the chunk histograms in one range
+  size_t ticket_words;    // its padded length in words
   uint32_t* sel_scratch;  // long sequences only: chunk histograms, candidates, bookkeeping
   float* partial;    // [B*Hq, nsplit, 130]
   size_t total_bytes;
@@ -82,8 +85,8 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
 
 // Rotates every query; with s.ap set also rotates the new key of every unit and writes it and
 // the new value into row seq_len-1 of the unit's cache.
-// zero_words / n_zero: words the kernel also clears (the chunk histograms of a long-sequence
-// selection, which the score kernel then adds into); null: nothing.
+// zero_words / n_zero: words the kernel also clears (the gather's tickets and the chunk
+// histograms of a long-sequence selection, which the score kernel then adds into); null: nothing.
 hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qhat, void* klo,
                        void* khi, void* v, uint32_t* zero_words, size_t n_zero, hipStream_t st);
 // hist_part [selecting heads][hist_chunks][2048] (zeroed) or null: see select_hist_chunks.
@@ -101,9 +104,13 @@ int select_hist_chunks(const Shape& s, int select_mode);
 hipError_t launch_select(const Shape& s, int n_sel_heads, const float* scores, int32_t* sel_idx,
                          float* sel_score, uint32_t* scratch, bool one_pass, int32_t* user_idx,
                          hipStream_t st);
+// tickets [B*Hq] (zeroed, see launch_qrot) or null: with more than one row split, the block that
+// finishes a head group last merges the splits and writes `out`; null leaves the partials for
+// launch_combine.
 hipError_t launch_gather(const Shape& s, int select_mode, int nsplit, const float* qhat,
                          const void* klo, const void* khi, const void* v, const int32_t* sel_idx,
-                         const float* sel_score, float* partial, void* out, hipStream_t st);
+                         const float* sel_score, float* partial, int32_t* tickets, void* out,
+                         hipStream_t st);
 hipError_t launch_dense(const Shape& s, int nsplit, const void* q, const void* k_full,
                         const void* v, float* partial, void* out, hipStream_t st);
 // Matrix-core attention for 8 query heads per block on bf16 caches (attend_mfma.hip).
@@ -114,7 +121,7 @@ hipError_t launch_pca_mfma(const Shape& s, int nsplit, const float* qhat, const 
                            const void* v, float* partial, void* out, hipStream_t st);
 hipError_t launch_gather_mfma(const Shape& s, int nsplit, const float* qhat, const void* klo,
                               const void* khi, const void* v, const int32_t* sel_idx, float* partial,
-                              void* out, hipStream_t st);
+                              int32_t* tickets, void* out, hipStream_t st);
 // Appendix E, Algorithm 2: every row, logits from the low-rank slab alone.
 hipError_t launch_pca_attend(const Shape& s, int nsplit, const float* qhat, const void* klo,
                              const void* v, float* partial, void* out, hipStream_t st);

@@ -28,14 +28,25 @@ __host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
   return (c + 3) & ~3;
 }
 
+// LDS of one block beyond the static part: one region that the stages use in turn — the
+// rotation's partial sums; then the score keys (padded, select_impl.h) followed by the list of
+// threshold-bin candidates; then the value tiles of the attention stage; then the merge of the
+// waves — and behind it the index list.
 template <int THREADS, int G>
 struct GqaLds {
   static constexpr int kWaves = THREADS / 64;
   static constexpr size_t kRotBytes = (size_t)G * (kRotParts + 1) * kD * sizeof(float);  // partial sums + q
   static constexpr size_t kStageBytes = (size_t)kWaves * kAmStageBytes;
   static constexpr size_t kMergeBytes = sizeof(MergeSmem<kWaves, G>);
+  static constexpr int kCandPerThread = 8;
+  static constexpr int kCandCap = kCandPerThread * THREADS;  // threshold-bin candidates kept as a compact list
+  static constexpr size_t kCandBytes = (size_t)kCandCap * 8;  // (key, position)
+  __host__ __device__ static size_t cand_offset(int S) {
+    const size_t b = padded_words((size_t)THREADS * gqa_keys_per_thread(S, THREADS)) * sizeof(uint32_t);
+    return (b + 15) & ~(size_t)15;
+  }
   __host__ __device__ static size_t region_bytes(int S) {
-    size_t b = (size_t)THREADS * gqa_keys_per_thread(S, THREADS) * sizeof(float);  // the scores
+    size_t b = cand_offset(S) + kCandBytes;
     b = b > kRotBytes ? b : kRotBytes;
     b = b > kStageBytes ? b : kStageBytes;
     b = b > kMergeBytes ? b : kMergeBytes;
@@ -178,7 +189,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
           const int row = rowbase + r16;
           if (kgrp == 0 && row < S) {
             const uint32_t key = float_to_key(m);
-            s_key[row] = key;
+            s_key[padded_pos(row)] = key;
             atomicAdd(&s_sel.hist[0][key >> 21], 1u);
           }
         });
@@ -197,50 +208,56 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   const uint32_t bin1 = s_sel.out[0][0], rem1 = s_sel.out[0][1];
   const uint32_t n_cand = s_sel.hist[0][bin1];
   int n_def = k - (int)rem1;
-  constexpr int kCandCap = 4 * THREADS;  // candidates resolved from a compact list (else: all keys)
-  uint32_t* s_ckey = reinterpret_cast<uint32_t*>(dyn_smem);  // over the scores, once they are in registers
+  constexpr int kCandCap = Lds::kCandCap;  // candidates resolved from a compact list (else: all keys)
+  uint32_t* s_ckey = reinterpret_cast<uint32_t*>(dyn_smem + Lds::cand_offset(S_max));  // behind the keys
   int32_t* s_cpos = reinterpret_cast<int32_t*>(s_ckey + kCandCap);
-  {
-    uint32_t key[KPT];
-    uint32_t valid_mask;
-    resident_load_keys<KPT>(s_key, S, per_thread, key, valid_mask);
-    LOKI_STAMP(11);
-    // (the barrier inside comes after every thread's key loads and before any list is written)
-    resident_partition<THREADS, KPT>(
-        key, valid_mask, per_thread, bin1, s_sel.wave[0], s_sel.wave[1],
-        [&](int rank, int pos, uint32_t) { s_idx[rank] = pos; },
+  LOKI_STAMP(11);
+  if (n_cand <= (uint32_t)kCandCap) {
+    // certain rows straight into the list, the bin's rows into the candidate list
+    contiguous_partition<THREADS, KPT>(
+        s_key, S, per_thread, 21, bin1, s_sel.wave[0], [&](int rank, int pos) { s_idx[rank] = pos; },
         [&](int rank, int pos, uint32_t kk) {
-          if (rank < kCandCap) {
-            s_ckey[rank] = kk;
-            s_cpos[rank] = pos;
-          }
+          s_ckey[rank] = kk;
+          s_cpos[rank] = pos;
         });
     for (int i = tid; i < 2048; i += THREADS) s_sel.hist[0][i] = 0u;  // everyone has read n_cand
     __syncthreads();
     LOKI_STAMP(13);
-    if (n_cand <= (uint32_t)kCandCap) {
-      // exact threshold among the candidates (they agree on the leading 11 bits: rank on the
-      // remaining 21, moved to the top of the word) and ordered emission of the rem1 best
-      uint32_t ck[4], vm = 0;
-      const int c0 = resident_pos0(4);
+    // exact threshold among the candidates (they agree on the leading 11 bits: rank on the
+    // remaining 21, moved to the top of the word) and ordered emission of the rem1 best
+    constexpr int CPT = Lds::kCandPerThread;
+    uint32_t ck[CPT], vm = 0;
+    const int c0 = resident_pos0(CPT);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const bool ok = (uint32_t)(c0 + e) < n_cand;
-        ck[e] = ok ? (s_ckey[c0 + e] << 11) : 0u;
-        vm |= (ok ? 1u : 0u) << e;
-      }
-      uint32_t Tp, need_eq;
-      resident_threshold<THREADS, 4>(ck, vm, rem1, s_sel, Tp, need_eq);
-      resident_compact<THREADS, 4>(ck, vm, 4, Tp, need_eq, 0u, 0u, s_sel.wave[0], s_sel.wave[1],
-                                   [&](int rank, int local, float) { s_idx[n_def + rank] = s_cpos[local]; });
-    } else {
-      // long runs of (nearly) equal scores: the plain selection over all keys, still in registers
-      uint32_t T, need_eq;
-      resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, s_sel, T, need_eq);
-      resident_compact<THREADS, KPT>(key, valid_mask, per_thread, T, need_eq, 0u, 0u, s_sel.wave[0],
-                                     s_sel.wave[1], [&](int rank, int pos, float) { s_idx[rank] = pos; });
-      n_def = k;
+    for (int e = 0; e < CPT; ++e) {
+      const int ci = c0 + 256 * (e / 4) + (e % 4);  // the layout resident_compact emits in
+      const bool ok = (uint32_t)ci < n_cand;
+      ck[e] = ok ? (s_ckey[ci] << 11) : 0u;
+      vm |= (ok ? 1u : 0u) << e;
     }
+    uint32_t Tp, need_eq;
+    resident_threshold<THREADS, CPT>(ck, vm, rem1, s_sel, Tp, need_eq);
+    resident_compact<THREADS, CPT>(ck, vm, CPT, Tp, need_eq, 0u, 0u, s_sel.wave[0], s_sel.wave[1],
+                                   [&](int rank, int local, float) { s_idx[n_def + rank] = s_cpos[local]; });
+  } else {
+    // long runs of (nearly) equal scores: the plain selection over all keys, held in registers;
+    // the list is again two ascending runs: the keys above the threshold, then the first
+    // need_eq keys equal to it
+    uint32_t key[KPT];
+    uint32_t valid_mask;
+    contiguous_load_keys<KPT>(s_key, S, per_thread, key, valid_mask);
+    __syncthreads();  // everyone has read n_cand
+    for (int i = tid; i < 2048; i += THREADS) s_sel.hist[0][i] = 0u;
+    __syncthreads();
+    uint32_t T, need_eq;
+    resident_threshold<THREADS, KPT>(key, valid_mask, (uint32_t)k, s_sel, T, need_eq);
+    n_def = k - (int)need_eq;
+    __syncthreads();  // s_sel.wave is free again
+    contiguous_partition<THREADS, KPT>(
+        s_key, S, per_thread, 0, T, s_sel.wave[0], [&](int rank, int pos) { s_idx[rank] = pos; },
+        [&](int rank, int pos, uint32_t) {
+          if (rank < (int)need_eq) s_idx[n_def + rank] = pos;
+        });
   }
   __syncthreads();  // the index list is complete; the scores are dead, the region turns into value tiles
   LOKI_STAMP(6);

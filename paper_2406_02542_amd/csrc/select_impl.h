@@ -484,6 +484,67 @@ __device__ __forceinline__ void resident_partition(const uint32_t (&key)[KPT], u
   }
 }
 
+// ---- keys in LDS, every thread owning C consecutive positions ------------------------------------
+// The array is padded by one word per 32 (position r lives at r + r / 32), so that the lanes of a
+// wave, whose runs start C words apart, read different banks.  Thread t owns positions
+// [t C, (t + 1) C); ranks follow the thread order, so everything emitted is ascending in position.
+__device__ __forceinline__ int padded_pos(int r) { return r + (r >> 5); }
+__host__ __device__ inline size_t padded_words(size_t n) { return n + (n >> 5) + 1; }
+
+template <int KPT>
+__device__ __forceinline__ void contiguous_load_keys(const uint32_t* s_key, int n, int C,
+                                                     uint32_t (&key)[KPT], uint32_t& valid_mask) {
+  const int r0 = (int)threadIdx.x * C;
+  valid_mask = 0;
+#pragma unroll
+  for (int e = 0; e < KPT; ++e) {
+    const bool ok = e < C && r0 + e < n;
+    key[e] = ok ? s_key[padded_pos(r0 + e)] : 0u;
+    valid_mask |= (ok ? 1u : 0u) << e;
+  }
+}
+
+// One pass over the block's keys: emit_gt(rank, pos) for every key whose leading bits
+// (key >> shift) exceed thr, emit_eq(rank, pos, key) for every key whose leading bits equal it,
+// ranks counted separately and ascending with pos.  A thread first builds two bit masks over
+// its run, the ranks come from one wave scan and one barrier (wave_tot: a word per wave), and the
+// emission loops run once per set bit, not once per key.
+template <int THREADS, int KPT, typename EmitGt, typename EmitEq>
+__device__ __forceinline__ void contiguous_partition(const uint32_t* s_key, int n, int C, int shift,
+                                                     uint32_t thr, uint32_t* wave_tot, EmitGt emit_gt,
+                                                     EmitEq emit_eq) {
+  constexpr int kWaves = THREADS / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r0 = (int)threadIdx.x * C;
+  uint32_t gt = 0, eq = 0;
+#pragma unroll
+  for (int e = 0; e < KPT; ++e) {
+    if (e < C && r0 + e < n) {
+      const uint32_t b = s_key[padded_pos(r0 + e)] >> shift;
+      gt |= (b > thr ? 1u : 0u) << e;
+      eq |= (b == thr ? 1u : 0u) << e;
+    }
+  }
+  const uint32_t mine = (uint32_t)__popc(gt) | ((uint32_t)__popc(eq) << 16);
+  const uint32_t incl = wave_inclusive_scan_u32(mine);
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = incl - mine;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) before += (w < wave) ? wave_tot[w] : 0u;
+  int g_rank = (int)(before & 0xffffu), e_rank = (int)(before >> 16);
+  while (gt) {
+    const int e = __ffs((int)gt) - 1;
+    gt &= gt - 1;
+    emit_gt(g_rank++, r0 + e);
+  }
+  while (eq) {
+    const int e = __ffs((int)eq) - 1;
+    eq &= eq - 1;
+    emit_eq(e_rank++, r0 + e, s_key[padded_pos(r0 + e)]);
+  }
+}
+
 // Whole selection for S <= THREADS*C: emit(rank, pos, score) is called exactly k times, rank
 // in [0, k) ascending with pos.
 template <int THREADS, int KPT, typename Emit>

@@ -319,8 +319,11 @@ bool fused_gqa_eligible(const Shape& s, int select_mode) {
 
 bool fused_gqa_preferred(const Shape& s, int select_mode) {
   if (!fused_gqa_eligible(s, select_mode)) return false;
-  // one block per unit: worth it when the units alone fill the chip
-  return s.B * s.Hkv >= device_cus();
+  // one block per unit: worth it from a quarter of the CUs on (three eighths for sequences
+  // beyond 8192 rows); below that the split path's many blocks per unit win (measured at 16 to
+  // 192 units, S = 4096 / 8192 / 16384, 4 and 8 query heads per KV head)
+  const long long units = (long long)s.B * s.Hkv, cus = device_cus();
+  return s.S <= 8192 ? 4 * units >= cus : 8 * units >= 3 * cus;
 }
 
 template <int THREADS, int NCH, int G, int KPT>
@@ -345,9 +348,13 @@ template <int NCH, int G>
 static hipError_t launch_fused_gqa_g(const Shape& s, const void* q, const float* P, const void* klo,
                                      const void* khi, const void* v, void* out, int32_t* out_idx,
                                      hipStream_t st) {
+  // 256 threads when two blocks have to share a CU; 512 when a block has a CU to itself anyway
+  // (a unit's time is set by the instructions its waves issue, so twice the waves per unit is
+  // close to twice as fast: 8 query heads, S = 8192, 128 units: 45 -> 30 us)
+  const bool alone = s.B * s.Hkv <= device_cus();
+  if (s.S > 256 * 32 || alone) return launch_fused_gqa_k<512, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
   if (s.S <= 256 * 16) return launch_fused_gqa_k<256, NCH, G, 16>(s, q, P, klo, khi, v, out, out_idx, st);
-  if (s.S <= 256 * 32) return launch_fused_gqa_k<256, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
-  return launch_fused_gqa_k<512, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
+  return launch_fused_gqa_k<256, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
 }
 
 template <int NCH>

@@ -144,19 +144,24 @@ def kernel_times(api, step_fn, steps):
 
 def bench_configs(args, torch, api, synth):
     """The `configs` array: every other workload of the benchmark list, both select modes where
-    query heads are grouped, and the nine (d, k) points of the large-model sweep.  Inputs come
+    query heads are grouped, the nine (d, k) points of the large-model sweep, and the benchmark
+    workload at batch 1 and 2.  Inputs come
     from the same seeded generator as the parity tests; a workload's cache is generated once and
     the low-rank / residual split is rebuilt on the device per d."""
     cfgs = synth.paper_configs()
-    plan = [("tiny", [cfgs["tiny"]], (0,)),
-            ("llama3_8b_gqa", [cfgs["llama3_8b_gqa"]], (0, 1)),
-            ("long_gqa", [cfgs["long_gqa"]], (0, 1)),
-            ("large_share", synth.large_share_sweep(), (0, 1))]
+    # (the benchmark workload at batch 1 and 2, 32 and 64 units, shows where few units leave every
+    # path bound by latency: dense attention has no dependent stages and can be the faster one there)
+    small = [cfgs["llama2_7b"].replace(B=b, name=f"llama2_7b_batch{b}") for b in (1, 2)]
+    plan = [("tiny", cfgs["tiny"], [cfgs["tiny"]], (0,)),
+            ("llama2_7b_batch1", small[0], [small[0]], (0,)),
+            ("llama2_7b_batch2", small[1], [small[1]], (0,)),
+            ("llama3_8b_gqa", cfgs["llama3_8b_gqa"], [cfgs["llama3_8b_gqa"]], (0, 1)),
+            ("long_gqa", cfgs["long_gqa"], [cfgs["long_gqa"]], (0, 1)),
+            ("large_share", cfgs["large_share"], synth.large_share_sweep(), (0, 1))]
     stream = torch.cuda.current_stream()
     steps = max(20, args.config_steps)
     entries = []
-    for name, variants, modes in plan:
-        base = cfgs[name]
+    for name, base, variants, modes in plan:
         tdt = torch.float32 if base.dtype == "f32" else torch.bfloat16
         t0 = time.perf_counter()
         x = synth.make_inputs(base, threads=min(16, os.cpu_count() or 8))

@@ -349,8 +349,8 @@ static hipError_t launch_fused_gqa_g(const Shape& s, const void* q, const float*
                                      const void* khi, const void* v, void* out, int32_t* out_idx,
                                      hipStream_t st) {
   // 256 threads when two blocks have to share a CU; 512 when a block has a CU to itself anyway
-  // (a unit's time is set by the instructions its waves issue, so twice the waves per unit is
-  // close to twice as fast: 8 query heads, S = 8192, 128 units: 45 -> 30 us)
+  // (a unit's time is set by the instructions its waves issue, so twice the waves per unit are
+  // faster: 8 query heads, S = 8192, 128 units: 45 -> 39 us)
   const bool alone = s.B * s.Hkv <= device_cus();
   if (s.S > 256 * 32 || alone) return launch_fused_gqa_k<512, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
   if (s.S <= 256 * 16) return launch_fused_gqa_k<256, NCH, G, 16>(s, q, P, klo, khi, v, out, out_idx, st);

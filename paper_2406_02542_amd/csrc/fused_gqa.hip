@@ -22,10 +22,12 @@ constexpr int kGqaMaxK = kMaxGatherChunk;  // the index list lives in LDS
 #define LOKI_GQA_SCORE_DEPTH(NCH) ((NCH) == 4 ? 16 : 8)
 #endif
 
-// positions per thread in the select stage: ceil(S / threads) rounded up to a multiple of 4
+// positions per thread in the select stage: ceil(S / threads) rounded up to a power of two (>= 4)
 __host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
   const int c = (S + threads - 1) / threads;
-  return (c + 3) & ~3;
+  int p = 4;
+  while (p < c) p *= 2;
+  return p;
 }
 
 // LDS of one block beyond the static part: one region that the stages use in turn — the

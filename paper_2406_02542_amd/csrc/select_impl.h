@@ -486,21 +486,29 @@ __device__ __forceinline__ void resident_partition(const uint32_t (&key)[KPT], u
 
 // ---- keys in LDS, every thread owning C consecutive positions ------------------------------------
 // The array is padded by one word per 32 (position r lives at r + r / 32), so that the lanes of a
-// wave, whose runs start C words apart, read different banks.  Thread t owns positions
+// wave, whose runs start C words apart, read different banks.  C is a power of two of at most 32,
+// so a run never crosses a multiple of 32 and lies in consecutive words.  Thread t owns positions
 // [t C, (t + 1) C); ranks follow the thread order, so everything emitted is ascending in position.
+// All reads are unconditional (a run past the end of the data is read and masked out): guarded
+// reads cost a branch per key.
 __device__ __forceinline__ int padded_pos(int r) { return r + (r >> 5); }
-__host__ __device__ inline size_t padded_words(size_t n) { return n + (n >> 5) + 1; }
+__host__ __device__ inline size_t padded_words(size_t n) { return n + (n >> 5) + 33; }
+
+// bit e set: position t C + e is inside the thread's run and below n
+__device__ __forceinline__ uint32_t contiguous_valid_mask(int n, int C) {
+  const int nv = max(0, min(C, n - (int)threadIdx.x * C));
+  return nv >= 32 ? 0xffffffffu : ((1u << nv) - 1u);
+}
 
 template <int KPT>
 __device__ __forceinline__ void contiguous_load_keys(const uint32_t* s_key, int n, int C,
                                                      uint32_t (&key)[KPT], uint32_t& valid_mask) {
-  const int r0 = (int)threadIdx.x * C;
-  valid_mask = 0;
+  const uint32_t* run = s_key + padded_pos((int)threadIdx.x * C);
+  valid_mask = contiguous_valid_mask(n, C);
 #pragma unroll
   for (int e = 0; e < KPT; ++e) {
-    const bool ok = e < C && r0 + e < n;
-    key[e] = ok ? s_key[padded_pos(r0 + e)] : 0u;
-    valid_mask |= (ok ? 1u : 0u) << e;
+    const uint32_t x = run[e];  // (inside the array's slack when e >= C)
+    key[e] = ((valid_mask >> e) & 1u) ? x : 0u;
   }
 }
 
@@ -516,19 +524,23 @@ __device__ __forceinline__ void contiguous_partition(const uint32_t* s_key, int 
   constexpr int kWaves = THREADS / 64;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r0 = (int)threadIdx.x * C;
+  const uint32_t* run = s_key + padded_pos(r0);
   uint32_t gt = 0, eq = 0;
 #pragma unroll
   for (int e = 0; e < KPT; ++e) {
-    if (e < C && r0 + e < n) {
-      const uint32_t b = s_key[padded_pos(r0 + e)] >> shift;
-      gt |= (b > thr ? 1u : 0u) << e;
-      eq |= (b == thr ? 1u : 0u) << e;
-    }
+    const uint32_t b = run[e] >> shift;
+    gt |= (b > thr ? 1u : 0u) << e;
+    eq |= (b == thr ? 1u : 0u) << e;
   }
+  const uint32_t vm = contiguous_valid_mask(n, C);
+  gt &= vm;
+  eq &= vm;
+  LOKI_STAMP(3);
   const uint32_t mine = (uint32_t)__popc(gt) | ((uint32_t)__popc(eq) << 16);
   const uint32_t incl = wave_inclusive_scan_u32(mine);
   if (lane == 63) wave_tot[wave] = incl;
   __syncthreads();
+  LOKI_STAMP(5);
   uint32_t before = incl - mine;
 #pragma unroll
   for (int w = 0; w < kWaves; ++w) before += (w < wave) ? wave_tot[w] : 0u;
@@ -541,7 +553,7 @@ __device__ __forceinline__ void contiguous_partition(const uint32_t* s_key, int 
   while (eq) {
     const int e = __ffs((int)eq) - 1;
     eq &= eq - 1;
-    emit_eq(e_rank++, r0 + e, s_key[padded_pos(r0 + e)]);
+    emit_eq(e_rank++, r0 + e, run[e]);
   }
 }
 

@@ -37,7 +37,7 @@ __host__ __device__ inline int gqa_keys_per_thread(int S, int threads) {
 template <int THREADS, int G>
 struct GqaLds {
   static constexpr int kWaves = THREADS / 64;
-  static constexpr size_t kRotBytes = (size_t)G * (kRotParts + 1) * kD * sizeof(float);  // partial sums + q
+  static constexpr size_t kRotBytes = (size_t)(G + 1) * (kRotParts + 1) * kD * sizeof(float);  // partial sums + vectors (G queries, the new key)
   static constexpr size_t kStageBytes = (size_t)kWaves * kAmStageBytes;
   static constexpr size_t kMergeBytes = sizeof(MergeSmem<kWaves, G>);
   static constexpr int kCandPerThread = 8;
@@ -61,9 +61,9 @@ struct GqaLds {
 // NCH = 16-byte chunks per slab row (d = 8 NCH); KPT = keys a thread holds in the select stage.
 template <int THREADS, int NCH, int G, int KPT>
 __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_kernel(
-    const uint16_t* __restrict__ klo, const uint16_t* __restrict__ khi, const uint16_t* __restrict__ v,
+    const uint16_t* klo, const uint16_t* khi, const uint16_t* v,
     const uint16_t* __restrict__ q, const float* __restrict__ P, uint16_t* __restrict__ out,
-    int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag) {
+    int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag, Append ap) {
   constexpr int kWaves = THREADS / 64;
   constexpr int PPW = kRotParts / kWaves;  // parts of the rotation a wave owns
   static_assert(PPW * kWaves == kRotParts, "the rotation's 8 parts divide over the waves");
@@ -72,8 +72,8 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
 
   extern __shared__ __align__(16) unsigned char dyn_smem[];
   uint32_t* s_key = reinterpret_cast<uint32_t*>(dyn_smem);                 // scoring, select: keys of the scores
-  float* s_q = reinterpret_cast<float*>(dyn_smem);                          // rotation: [G][128]
-  float* s_part = s_q + G * kD;                                             // rotation: [G][8][128]
+  float* s_q = reinterpret_cast<float*>(dyn_smem);                          // rotation: [G + 1][128]
+  float* s_part = s_q + (G + 1) * kD;                                       // rotation: [G + 1][8][128]
   unsigned char* s_stage = dyn_smem;                                        // attention: value tiles
   MergeSmem<kWaves, G>& s_merge = *reinterpret_cast<MergeSmem<kWaves, G>*>(dyn_smem);  // merge
   int32_t* s_idx = reinterpret_cast<int32_t*>(dyn_smem + Lds::region_bytes(S_max));  // [k_max]
@@ -111,6 +111,12 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
 
   // ---- qhat = q P_h for the G heads, with the association every path uses (8 parts of 16 terms,
   // parts added in order): wave w owns parts w PPW .. w PPW + PPW - 1, lane l columns 2l, 2l+1 ----
+  // With ap.k_new the block also rotates the unit's new key, as one more vector through the
+  // same partial sums, and writes it (rounded to storage) with the new value into row S - 1 of
+  // the unit's cache before it scores (Algorithm 1 lines 3-4).  The block's own later reads of
+  // that row go through the same L1 and see it after the barrier; no other block reads this
+  // unit's rows.
+  const bool app = ap.k_new != nullptr;
   {
     float qv[kQPerThread];
 #pragma unroll
@@ -118,6 +124,11 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
       const int i = tid + j * THREADS;
       qv[j] = BF16::load1(q + head0 * kD + (i < G * kD ? i : 0));
     }
+    // (no branch around the loads: without a new key they read the first query again)
+    const uint16_t* kn_src = app ? static_cast<const uint16_t*>(ap.k_new) + (size_t)unit * kD : q + head0 * kD;
+    const uint16_t* vn_src = app ? static_cast<const uint16_t*>(ap.v_new) + (size_t)unit * kD : q + head0 * kD;
+    const float kn_mine = BF16::load1(kn_src + (tid & (kD - 1)));
+    const uint16_t vn_mine = vn_src[tid & (kD - 1)];
     float2 pv[PPW][kRotPartLen];
     const float* Ph = P + (size_t)h * kD * kD + 2 * lane;
 #pragma unroll
@@ -132,9 +143,11 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
       const int i = tid + j * THREADS;
       if (i < G * kD) s_q[i] = qv[j];
     }
+    if (tid < kD) s_q[G * kD + tid] = kn_mine;
     __syncthreads();
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+    for (int g = 0; g < G + 1; ++g)
+      if (g < G || app)  // (uniform)
 #pragma unroll
       for (int pp = 0; pp < PPW; ++pp) {
         const int part = wave * PPW + pp;
@@ -154,14 +167,26 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
         *reinterpret_cast<float2*>(&s_part[(g * kRotParts + part) * kD + 2 * lane]) = make_float2(a0, a1);
       }
     __syncthreads();
-    for (int i = tid; i < G * kD; i += THREADS) {
+    const size_t new_row = (size_t)unit * S_cap + (size_t)(S - 1);
+    for (int i = tid; i < (G + (app ? 1 : 0)) * kD; i += THREADS) {
       const int g = i / kD, j = i % kD;
       float sum = 0.f;
 #pragma unroll
       for (int pp = 0; pp < kRotParts; ++pp) sum += s_part[(g * kRotParts + pp) * kD + j];
-      s_qhat[g][j] = sum;
+      if (g < G) {
+        s_qhat[g][j] = sum;
+      } else {  // the new key: columns < d to the low-rank slab, the rest to the residual slab
+        uint16_t* dst = j < d ? const_cast<uint16_t*>(klo) + new_row * d + j
+                              : const_cast<uint16_t*>(khi) + new_row * (kD - d) + (j - d);
+        BF16::store1(dst, sum);
+      }
     }
+    if (app && tid >= THREADS - kD)  // the new value, by the last 128 threads (tid % 128 = column)
+      const_cast<uint16_t*>(v)[new_row * kD + (tid & (kD - 1))] = vn_mine;
     __syncthreads();  // s_qhat complete; the partial sums are dead, the region turns into the scores
+    // the loads put in flight before the rotation may have read row S - 1 before it was written
+    constexpr int kPrefRows = 2 * kWaves * ScoreMfmaGeom<NCH>::RPS * ScoreMfmaBufs<NCH, kDepth>::UH;
+    if (app && S - 1 < kPrefRows) score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
   }
   LOKI_STAMP(1);
 
@@ -313,7 +338,7 @@ extern "C" int loki_debug_read_gqa_ts(unsigned long long* host_dst, size_t count
 bool fused_gqa_eligible(const Shape& s, int select_mode) {
   if (s.dtype != 1 || select_mode != 1) return false;
   if (s.G != 2 && s.G != 4 && s.G != 8) return false;
-  if (s.rg.queries > 1 || s.ap.k_new != nullptr || s.pg.table != nullptr) return false;
+  if (s.rg.queries > 1 || s.pg.table != nullptr) return false;
   const int nch = s.d / 8;
   if (s.d % 8 != 0 || (nch & (nch - 1)) != 0 || nch < 2 || s.d >= kD) return false;
   return s.S <= 16384 && s.k <= kGqaMaxK;
@@ -342,7 +367,7 @@ static hipError_t launch_fused_gqa_k(const Shape& s, const void* q, const float*
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(THREADS), lds, st,
                      static_cast<const uint16_t*>(klo), static_cast<const uint16_t*>(khi),
                      static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(q), P,
-                     static_cast<uint16_t*>(out), out_idx, s.Hkv, s.S, s.S_cap, s.k, s.rg);
+                     static_cast<uint16_t*>(out), out_idx, s.Hkv, s.S, s.S_cap, s.k, s.rg, s.ap);
   return hipGetLastError();
 }
 

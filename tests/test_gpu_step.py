@@ -217,6 +217,19 @@ def test_step_gqa_single_kernel_ragged(G, S, k):
     run_step_case(w, 1, True, False, path=api.PATH_FUSED, lens=[S, 1, 2, 257])
 
 
+@pytest.mark.parametrize("G,S,k,d", [(2, 700, 100, 32), (4, 4096, 512, 16), (8, 8192, 1024, 64),
+                                     (4, 12000, 1500, 32)])
+def test_step_gqa_single_kernel_append(G, S, k, d):
+    """Grouped heads, one launch, the current token's key and value appended by the same launch
+    (Algorithm 1 lines 3-4 folded in): uniform and per-sequence lengths; sequences of one and two
+    rows, where the appended row is certain to be selected and lies in the rows the kernel
+    requests before it has written them (they must be read again)."""
+    w = synth.Workload(f"step_gq{G}_app", 4, 2 * G, 2, 128, S, "bf16", d, k, seed=9670 + G)
+    run_step_case(w, 1, False, True, path=api.PATH_FUSED)
+    run_step_case(w, 1, True, True, path=api.PATH_FUSED)
+    run_step_case(w, 1, True, True, path=api.PATH_FUSED, lens=[S, 1, 2, 257])
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_step_long_sequences_multiblock_select(mode):
     """S_max = 40000 (three chunks of the multi-block select): one full sequence, one inside

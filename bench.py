@@ -216,6 +216,19 @@ def bench_configs(args, torch, api, synth):
                          "speedup_vs_dense": dense_us / med,
                          "kernels_us": kern,
                          "dominant_kernel": max(kern, key=lambda n: kern[n]) if kern else None}
+                    if w.G > 1 and mode == 1:
+                        # the whole step of a grouped-query model: the current token's key and
+                        # value appended by the same launches (loki_decode_step)
+                        kn = torch.randn((w.B, w.Hkv, w.D), device="cuda").to(tdt)
+                        vn = torch.randn((w.B, w.Hkv, w.D), device="cuda").to(tdt)
+
+                        def append_step(i):
+                            c = i % copies
+                            api.loki_decode_step(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode,
+                                                 ws, out, None, k_new=kn, v_new=vn, stream=stream)
+
+                        a_us, _ = event_timed_steps(torch, append_step, steps, 10, stream)
+                        e["step_with_append_us"] = _pct(a_us, 50)
                     # recorded counters (all kernels of one step summed), where the table has the point
                     e["traffic"], e["traffic_recorded_in"] = recorded_traffic(
                         f"{name} d={w.d} k={w.k} mode={mode}", "step")

@@ -78,8 +78,9 @@ enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
  * kernels with the work of a unit spread over many blocks.  FUSED: one kernel, one block per
  * unit; available when Hq == Hkv, S <= 8192 and k <= 2048, and for grouped heads
  * (Hq / Hkv in {2, 4, 8}) with LOKI_SELECT_PER_KV_GROUP on a bf16 cache with d in {16, 32, 64},
- * S <= 16384, k <= 2048 (per-sequence lengths and the append of loki_decode_step included),
- * without paging or several tokens per sequence (else LOKI_ERR_UNSUPPORTED).  Both give the same selected sets; outputs agree to fp32 rounding
+ * S <= 16384, k <= 2048 (per-sequence lengths, the append and a paged cache of at most 64
+ * pages per sequence of loki_decode_step included), one token per sequence (else
+ * LOKI_ERR_UNSUPPORTED).  Both give the same selected sets; outputs agree to fp32 rounding
  * (bf16 rounding of two-term products for grouped heads). */
 enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_MASK = 0x300 };
 

@@ -51,20 +51,6 @@ __device__ __forceinline__ int fused_unit_of_block(const Ragged& rag, int B, int
 // writes it, with the new value, into row S-1 of the unit's cache before it scores.  The block's
 // own later reads of that row go through the same L1 and see it after the barrier; no other
 // block reads this unit's rows.
-// Slab rows of a paged cache: the sequence's page list sits in LDS; a row's page is looked up
-// per lane (rows past the end are clamped to the last row, which may lie in an earlier page).
-struct PagedRows {
-  const char* base;       // this lane's chunk of row 0 of the pool
-  size_t row_bytes;
-  const int32_t* pages;   // LDS: physical page of every logical page of the sequence
-  int lg, Hkv, h;
-  __device__ __forceinline__ long long pool_row(int row) const {
-    return ((((long long)pages[row >> lg] * Hkv + h) << lg) | (long long)(row & ((1 << lg) - 1)));
-  }
-  __device__ __forceinline__ const char* operator()(int row) const {
-    return base + pool_row(row) * (long long)row_bytes;
-  }
-};
 constexpr int kFusedMaxPages = kFusedMaxS / 256;  // pages are at least 256 rows
 
 // PAGED: the three slabs are pools addressed through the sequence's page list (see Paging).

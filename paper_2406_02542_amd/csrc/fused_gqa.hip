@@ -16,6 +16,7 @@
 namespace loki {
 
 constexpr int kGqaMaxK = kMaxGatherChunk;  // the index list lives in LDS
+constexpr int kGqaMaxPages = 64;           // a paged cache: 16384 rows in pages of at least 256
 // 16-byte slab loads a lane keeps in flight in the scoring stage (measured on the 64/8-head
 // shapes at S = 8192: 64-byte slab rows gain 6 % from 16 against 8, the other widths nothing)
 #ifndef LOKI_GQA_SCORE_DEPTH
@@ -59,11 +60,15 @@ struct GqaLds {
 
 // THREADS = 256: two blocks share a CU (S <= 8192); 512: one block per CU (S <= 16384).
 // NCH = 16-byte chunks per slab row (d = 8 NCH); KPT = keys a thread holds in the select stage.
-template <int THREADS, int NCH, int G, int KPT>
+// PAGED: the three slabs are pools addressed through the sequence's page list (see Paging): the
+// list sits in LDS, every slab load looks its page up, and the selected positions are translated
+// to pool rows before the attention stage.
+template <int THREADS, int NCH, int G, int KPT, bool PAGED>
 __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_kernel(
     const uint16_t* klo, const uint16_t* khi, const uint16_t* v,
     const uint16_t* __restrict__ q, const float* __restrict__ P, uint16_t* __restrict__ out,
-    int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag, Append ap) {
+    int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag, Append ap,
+    Paging pg) {
   constexpr int kWaves = THREADS / 64;
   constexpr int PPW = kRotParts / kWaves;  // parts of the rotation a wave owns
   static_assert(PPW * kWaves == kRotParts, "the rotation's 8 parts divide over the waves");
@@ -78,6 +83,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   MergeSmem<kWaves, G>& s_merge = *reinterpret_cast<MergeSmem<kWaves, G>*>(dyn_smem);  // merge
   int32_t* s_idx = reinterpret_cast<int32_t*>(dyn_smem + Lds::region_bytes(S_max));  // [k_max]
   __shared__ __align__(16) float s_qhat[G][kD];
+  __shared__ int32_t s_pages[PAGED ? kGqaMaxPages : 1];
   __shared__ ResidentSelectSmem<THREADS> s_sel;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -106,7 +112,18 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   // behind the whole chip's first burst of slab rows).
   constexpr int kDepth = LOKI_GQA_SCORE_DEPTH(NCH);
   constexpr int kQPerThread = (G * kD + THREADS - 1) / THREADS;
-  const char* slab = reinterpret_cast<const char*>(klo) + (size_t)unit * S_cap * (size_t)(d * 2);
+  using Rows = std::conditional_t<PAGED, PagedRows, ContiguousRows>;
+  Rows slab;
+  if constexpr (PAGED) {
+    // the sequence's page list, clamped into the pool; readable after the first barrier below
+    if (tid < kGqaMaxPages && tid < pg.pages_per_seq)
+      s_pages[tid] = min(max(pg.table[(size_t)(unit / Hkv) * pg.pages_per_seq + tid], 0), pg.n_pages - 1);
+    slab = PagedRows{reinterpret_cast<const char*>(klo) + score_mfma_chunk_bytes<NCH>(), (size_t)(d * 2),
+                     s_pages, pg.lg_rows, Hkv, h};
+  } else {
+    slab = score_mfma_contiguous<NCH>(reinterpret_cast<const char*>(klo) +
+                                      (size_t)unit * S_cap * (size_t)(d * 2));
+  }
   ScoreMfmaBufs<NCH, kDepth> sbufs;
 
   // ---- qhat = q P_h for the G heads, with the association every path uses (8 parts of 16 terms,
@@ -137,7 +154,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
       for (int ii = 0; ii < kRotPartLen; ++ii)
         pv[pp][ii] = *reinterpret_cast<const float2*>(Ph + (size_t)((wave * PPW + pp) * kRotPartLen + ii) * kD);
     __builtin_amdgcn_sched_barrier(0);
-    score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
+    if constexpr (!PAGED) score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);
 #pragma unroll
     for (int j = 0; j < kQPerThread; ++j) {
       const int i = tid + j * THREADS;
@@ -145,6 +162,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     }
     if (tid < kD) s_q[G * kD + tid] = kn_mine;
     __syncthreads();
+    if constexpr (PAGED) score_mfma_prefetch<NCH, kWaves, kDepth>(slab, 0, S, sbufs);  // the page list is in LDS now
 #pragma unroll
     for (int g = 0; g < G + 1; ++g)
       if (g < G || app)  // (uniform)
@@ -167,7 +185,9 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
         *reinterpret_cast<float2*>(&s_part[(g * kRotParts + part) * kD + 2 * lane]) = make_float2(a0, a1);
       }
     __syncthreads();
-    const size_t new_row = (size_t)unit * S_cap + (size_t)(S - 1);
+    size_t new_row;
+    if constexpr (PAGED) new_row = (size_t)slab.pool_row(S - 1);
+    else new_row = (size_t)unit * S_cap + (size_t)(S - 1);
     for (int i = tid; i < (G + (app ? 1 : 0)) * kD; i += THREADS) {
       const int g = i / kD, j = i % kD;
       float sum = 0.f;
@@ -306,12 +326,19 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     }
   }
 
+  if constexpr (PAGED) {
+    // the attention stage addresses the pools from their start: positions -> pool rows
+    __syncthreads();  // the merge above has read the positions
+    for (int i = tid; i < k; i += THREADS) s_idx[i] = (int32_t)slab.pool_row(s_idx[i]);
+    __syncthreads();
+  }
+
   // ---- exact attention over the selected rows, all G heads ---------------------------------------
   {
     const bool head_ok = r16 < G;
     am_bf16x8_t bq[4][2];
     am_query_operands<4, 2>(s_qhat[head_ok ? r16 : 0], head_ok, kD, bq);
-    const AmAddr<4> ad = am_make_addr<4, false>(klo, khi, v, (size_t)unit, S_cap, d);
+    const AmAddr<4> ad = am_make_addr<4, false>(klo, khi, v, PAGED ? (size_t)0 : (size_t)unit, S_cap, d);
     AmState st;
     st.init();
     am_attend_rows<true, 4, 2, kWaves>(ad, bq, s_idx, 0, k, s_stage + (size_t)wave * kAmStageBytes, st);
@@ -338,7 +365,8 @@ extern "C" int loki_debug_read_gqa_ts(unsigned long long* host_dst, size_t count
 bool fused_gqa_eligible(const Shape& s, int select_mode) {
   if (s.dtype != 1 || select_mode != 1) return false;
   if (s.G != 2 && s.G != 4 && s.G != 8) return false;
-  if (s.rg.queries > 1 || s.pg.table != nullptr) return false;
+  if (s.rg.queries > 1) return false;
+  if (s.pg.table != nullptr && s.pg.pages_per_seq > kGqaMaxPages) return false;  // page list in LDS
   const int nch = s.d / 8;
   if (s.d % 8 != 0 || (nch & (nch - 1)) != 0 || nch < 2 || s.d >= kD) return false;
   return s.S <= 16384 && s.k <= kGqaMaxK;
@@ -353,11 +381,11 @@ bool fused_gqa_preferred(const Shape& s, int select_mode) {
   return s.S <= 8192 ? 4 * units >= cus : 8 * units >= 3 * cus;
 }
 
-template <int THREADS, int NCH, int G, int KPT>
+template <int THREADS, int NCH, int G, int KPT, bool PAGED = false>
 static hipError_t launch_fused_gqa_k(const Shape& s, const void* q, const float* P, const void* klo,
                                      const void* khi, const void* v, void* out, int32_t* out_idx,
                                      hipStream_t st) {
-  auto kern = fused_gqa_kernel<THREADS, NCH, G, KPT>;
+  auto kern = fused_gqa_kernel<THREADS, NCH, G, KPT, PAGED>;
   const size_t lds = GqaLds<THREADS, G>::total_bytes(s.S, s.k);
   static std::atomic<unsigned long long> lds_allowed{0};  // per instantiation: devices already set up
   const hipError_t e = allow_dynamic_lds(
@@ -367,7 +395,7 @@ static hipError_t launch_fused_gqa_k(const Shape& s, const void* q, const float*
   hipLaunchKernelGGL(kern, dim3(s.B * s.Hkv), dim3(THREADS), lds, st,
                      static_cast<const uint16_t*>(klo), static_cast<const uint16_t*>(khi),
                      static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(q), P,
-                     static_cast<uint16_t*>(out), out_idx, s.Hkv, s.S, s.S_cap, s.k, s.rg, s.ap);
+                     static_cast<uint16_t*>(out), out_idx, s.Hkv, s.S, s.S_cap, s.k, s.rg, s.ap, s.pg);
   return hipGetLastError();
 }
 
@@ -379,6 +407,11 @@ static hipError_t launch_fused_gqa_g(const Shape& s, const void* q, const float*
   // (a unit's time is set by the instructions its waves issue, so twice the waves per unit are
   // faster: 8 query heads, S = 8192, 128 units: 45 -> 39 us)
   const bool alone = s.B * s.Hkv <= device_cus();
+  if (s.pg.table != nullptr) {  // (a paged cache: two block shapes)
+    if (s.S > 256 * 32 || alone)
+      return launch_fused_gqa_k<512, NCH, G, 32, true>(s, q, P, klo, khi, v, out, out_idx, st);
+    return launch_fused_gqa_k<256, NCH, G, 32, true>(s, q, P, klo, khi, v, out, out_idx, st);
+  }
   if (s.S > 256 * 32 || alone) return launch_fused_gqa_k<512, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);
   if (s.S <= 256 * 16) return launch_fused_gqa_k<256, NCH, G, 16>(s, q, P, klo, khi, v, out, out_idx, st);
   return launch_fused_gqa_k<256, NCH, G, 32>(s, q, P, klo, khi, v, out, out_idx, st);

@@ -257,14 +257,15 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   const char* slab = reinterpret_cast<const char*>(klo) + row_shift * (long long)(NCH * 16);
   const bool vec_ok = (S_max & 3) == 0;
   ScoreMfmaBufs<NCH, 8> bufs;
-  score_mfma_prefetch<NCH, 4, 8>(slab, row0, row_end, bufs);
+  const ContiguousRows slab_rows = score_mfma_contiguous<NCH>(slab);
+  score_mfma_prefetch<NCH, 4, 8>(slab_rows, row0, row_end, bufs);
   if constexpr (GROUP_MAX && !TILE) {
     // One score per row, the maximum over the group: qhat is the A operand and the row tile the
     // B operand, so a lane holds one row and four heads in its registers and the maximum needs
     // no exchange between lanes (8 heads: one, between the lanes that hold heads 0-3 and 4-7);
     // sixteen lanes store sixteen consecutive rows.
     const int kgrp = lane >> 4;
-    score_mfma_rows<NCH, 4, 8, true>(slab, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
+    score_mfma_rows<NCH, 4, 8, true>(slab_rows, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
       float m = fmaxf(acc[0], acc[1]);
       if constexpr (G >= 4) m = fmaxf(m, fmaxf(acc[2], acc[3]));
       if constexpr (G == 8) {
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
       }
     });
   } else {
-  score_mfma_rows<NCH, 4, 8>(slab, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
+  score_mfma_rows<NCH, 4, 8>(slab_rows, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
     float v[4] = {acc[0], acc[1], acc[2], acc[3]};
     bool writer = head_ok;
     if constexpr (GROUP_MAX) {

@@ -23,6 +23,21 @@ struct ContiguousRows {
   }
 };
 
+// Slab rows of a paged cache: the sequence's page list sits in LDS; a row's page is looked up
+// per lane (rows past the end are clamped to the last row, which may lie in an earlier page).
+struct PagedRows {
+  const char* base;       // this lane's chunk of row 0 of the pool
+  size_t row_bytes;
+  const int32_t* pages;   // LDS: physical page of every logical page of the sequence
+  int lg, Hkv, h;
+  __device__ __forceinline__ long long pool_row(int row) const {
+    return ((((long long)pages[row >> lg] * Hkv + h) << lg) | (long long)(row & ((1 << lg) - 1)));
+  }
+  __device__ __forceinline__ const char* operator()(int row) const {
+    return base + pool_row(row) * (long long)row_bytes;
+  }
+};
+
 // Scores rows [row0, row_end) of one unit's low-rank slab with the block's WAVES waves.
 // qr is this lane's slice of qhat (zero for lanes past the slab row's last chunk); `rows`
 // maps a row to this lane's 16-byte chunk of it.  emit(row, scores[G]) is called once

@@ -9,7 +9,7 @@
 // are exact.  Shared by the stand-alone score kernel and the single-launch grouped-query kernel.
 #pragma once
 
-#include "common.h"
+#include "score_impl.h"
 
 namespace loki {
 
@@ -73,32 +73,45 @@ struct ScoreMfmaBufs {
   uint4 b0[UH][NL], b1[UH][NL];
 };
 
-// Where this lane's chunk of step-row 0 lives, and its row inside a step.
+// This lane's place in a wave step: its row inside the step and the byte offset of its 16-byte
+// chunk inside a slab row.
 template <int NCH>
+__device__ __forceinline__ int score_mfma_row_in_step() {
+  const int lane = threadIdx.x & 63;
+  return NCH <= 4 ? (lane & 15) + 16 * ((lane >> 4) / NCH) : (lane & 15);
+}
+template <int NCH>
+__device__ __forceinline__ int score_mfma_chunk_bytes() {
+  const int kgrp = (threadIdx.x & 63) >> 4;
+  return (NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
+}
+// `rows` maps a slab row to the address of this lane's chunk of it (ContiguousRows, or a paged
+// cache's functor; the lane's chunk offset is part of its base).
+template <int NCH, typename Rows>
 struct ScoreMfmaLane {
-  const char* base;
+  Rows rows;
   int row_in_step;
-  __device__ __forceinline__ explicit ScoreMfmaLane(const char* slab) {
-    const int lane = threadIdx.x & 63;
-    const int kgrp = lane >> 4, r16 = lane & 15;
-    row_in_step = NCH <= 4 ? r16 + 16 * (kgrp / NCH) : r16;
-    base = slab + (size_t)row_in_step * (NCH * 16) + (size_t)(NCH <= 4 ? (kgrp % NCH) : kgrp) * 16;
-  }
+  __device__ __forceinline__ explicit ScoreMfmaLane(const Rows& r)
+      : rows(r), row_in_step(score_mfma_row_in_step<NCH>()) {}
 };
+// rows one after the other from `slab` (the address row 0 would have)
+template <int NCH>
+__device__ __forceinline__ ContiguousRows score_mfma_contiguous(const char* slab) {
+  return ContiguousRows{slab + score_mfma_chunk_bytes<NCH>(), (size_t)(NCH * 16)};
+}
 
 // One buffer's loads for the steps starting at row t0; rows past the end re-read the last row
 // (no branch around a load).
-template <int NCH, int WAVES, int UH>
-__device__ __forceinline__ void score_mfma_load(const ScoreMfmaLane<NCH>& ln, int t0, int row_end,
+template <int NCH, int WAVES, int UH, typename Rows>
+__device__ __forceinline__ void score_mfma_load(const ScoreMfmaLane<NCH, Rows>& ln, int t0, int row_end,
                                                 uint4 (&raw)[UH][ScoreMfmaGeom<NCH>::NL]) {
   constexpr int RPS = ScoreMfmaGeom<NCH>::RPS, NL = ScoreMfmaGeom<NCH>::NL;
 #pragma unroll
-  for (int u = 0; u < UH; ++u)
+  for (int u = 0; u < UH; ++u) {
+    const char* p = ln.rows(min(t0 + u * WAVES * RPS + ln.row_in_step, row_end - 1));
 #pragma unroll
-    for (int j = 0; j < NL; ++j) {
-      const int r = min(t0 + u * WAVES * RPS + ln.row_in_step, row_end - 1) - ln.row_in_step;
-      raw[u][j] = load16(ln.base + (long long)r * (long long)(NCH * 16) + (size_t)j * 64);
-    }
+    for (int j = 0; j < NL; ++j) raw[u][j] = load16(p + (size_t)j * 64);
+  }
 }
 
 // Puts the loads of the first two buffers in flight; needs no query, so a caller can issue it
@@ -106,12 +119,12 @@ __device__ __forceinline__ void score_mfma_load(const ScoreMfmaLane<NCH>& ln, in
 // order (buffer 0 before buffer 1, here as in the loop): loads return in order, and the wait in
 // front of a buffer's first use can only leave the other buffer's loads in flight if they were
 // issued after it on every path into the loop.
-template <int NCH, int WAVES, int DEPTH>
-__device__ __forceinline__ void score_mfma_prefetch(const char* slab, int row0, int row_end,
+template <int NCH, int WAVES, int DEPTH, typename Rows>
+__device__ __forceinline__ void score_mfma_prefetch(const Rows& rows, int row0, int row_end,
                                                     ScoreMfmaBufs<NCH, DEPTH>& bufs) {
   constexpr int UH = ScoreMfmaBufs<NCH, DEPTH>::UH;
   constexpr int kTrip = WAVES * ScoreMfmaGeom<NCH>::RPS * UH;
-  const ScoreMfmaLane<NCH> ln(slab);
+  const ScoreMfmaLane<NCH, Rows> ln(rows);
   const int t_first = row0 + (int)(threadIdx.x >> 6) * ScoreMfmaGeom<NCH>::RPS;
   score_mfma_load<NCH, WAVES, UH>(ln, t_first, row_end, bufs.b0);
   __builtin_amdgcn_sched_barrier(0);
@@ -120,8 +133,8 @@ __device__ __forceinline__ void score_mfma_prefetch(const char* slab, int row0, 
 }
 
 // Scores rows [row0, row_end) with the block's WAVES waves; `bufs` holds the first two buffers
-// (score_mfma_prefetch with the same arguments).  `slab` is the address row 0 would have (rows
-// are consecutive, 16 NCH bytes each); emit(rowbase, acc) is called by every lane with acc[i] =
+// (score_mfma_prefetch with the same arguments).  `rows` maps a row to this lane's chunk of it
+// (score_mfma_contiguous for rows that follow each other in memory, 16 NCH bytes each); emit(rowbase, acc) is called by every lane with acc[i] =
 // score of head (lane % 16) at row rowbase + i, rowbase = ... + 4 (lane / 16); rows at or past
 // row_end carry the values of the last row and must not be used.  A buffer is refilled right
 // after it is consumed, so that a wave always has loads in flight while it computes.
@@ -131,8 +144,8 @@ __device__ __forceinline__ void score_mfma_prefetch(const char* slab, int row0, 
 // lane in its registers: emit(rowbase, acc) then gets acc[i] = score of head 4 (lane / 16) + i at
 // row rowbase + lane % 16, rowbase a multiple of 16.  A maximum over the heads of a group is
 // then taken in registers instead of across lanes.
-template <int NCH, int WAVES, int DEPTH = 8, bool HEADS_IN_REGS = false, typename Emit>
-__device__ __forceinline__ void score_mfma_rows(const char* slab, int row0, int row_end,
+template <int NCH, int WAVES, int DEPTH = 8, bool HEADS_IN_REGS = false, typename Rows, typename Emit>
+__device__ __forceinline__ void score_mfma_rows(const Rows& rows, int row0, int row_end,
                                                 const bf16x8_t (&bq)[ScoreMfmaGeom<NCH>::NB][3],
                                                 ScoreMfmaBufs<NCH, DEPTH>& bufs, Emit emit) {
   using Gm = ScoreMfmaGeom<NCH>;
@@ -141,7 +154,7 @@ __device__ __forceinline__ void score_mfma_rows(const char* slab, int row0, int 
   constexpr int kTrip = WAVES * RPS * UH;    // rows the block advances per buffer
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int kgrp = lane >> 4;
-  const ScoreMfmaLane<NCH> ln(slab);
+  const ScoreMfmaLane<NCH, Rows> ln(rows);
 
   auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
 #pragma unroll

@@ -314,7 +314,8 @@ def test_dense_step_ragged(G, dtype):
 # ------------------------------------------------- paged cache, judged by the oracle directly --
 @pytest.mark.parametrize("G,mode,path,page_rows", [(1, 0, api.PATH_FUSED, 256), (1, 0, api.PATH_SPLIT, 512),
                                                    (4, 0, api.PATH_SPLIT, 256), (4, 1, api.PATH_SPLIT, 1024),
-                                                   (8, 1, api.PATH_SPLIT, 256)])
+                                                   (8, 1, api.PATH_SPLIT, 256), (4, 1, api.PATH_FUSED, 256),
+                                                   (8, 1, api.PATH_FUSED, 1024), (2, 1, api.PATH_FUSED, 512)])
 def test_step_paged_cache_against_oracle(G, mode, path, page_rows):
     """The whole step (ragged, appending) on a paged cache against the oracle itself, not only
     against the contiguous layout: outputs, index lists and the appended rows."""
@@ -572,7 +573,8 @@ def test_multi_token_step_equals_single_token_steps_on_random_shapes(seed):
     (2, "f32", 0, 256, 1, api.PATH_SPLIT), (4, "bf16", 0, 256, 2, api.PATH_SPLIT),
     (4, "bf16", 1, 512, 5, api.PATH_SPLIT), (1, "bf16", 0, 256, 3, api.PATH_SPLIT),
     (1, "bf16", 0, 256, 1, api.PATH_FUSED), (1, "bf16", 0, 2048, 1, api.PATH_FUSED),
-    (1, "f32", 0, 512, 1, api.PATH_FUSED)])
+    (1, "f32", 0, 512, 1, api.PATH_FUSED), (4, "bf16", 1, 256, 1, api.PATH_FUSED),
+    (8, "bf16", 1, 2048, 1, api.PATH_FUSED), (2, "bf16", 1, 512, 1, api.PATH_FUSED)])
 def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path):
     """The same rows scattered over randomly ordered physical pages (with unused pages in
     between) give bit-identical outputs, index lists and appended rows, on either kernel
@@ -595,7 +597,8 @@ def test_paged_cache_equals_contiguous_cache_on_random_shapes(seed):
     k = int(rng.integers(1, max(2, min(S // 3, 2000))))
     mode = int(rng.integers(0, 2))
     page_rows = int(rng.choice([256, 512, 1024, 2048]))
-    fused_ok = G == 1 and m == 1 and (S + page_rows - 1) // page_rows <= 32
+    fused_ok = m == 1 and (S + page_rows - 1) // page_rows <= 32 and (
+        G == 1 or (mode == 1 and dtype == "bf16" and d in (16, 32, 64) and k <= 2048))
     path = api.PATH_FUSED if (fused_ok and rng.random() < 0.5) else api.PATH_SPLIT
     rows = [S] + [int(rng.integers(max(m, 2), S + 1)) for _ in range(B - 1)]
     w = synth.Workload(f"paged_rnd{seed}", B, Hkv * G, Hkv, 128, S, dtype, d, k, seed=17000 + seed)

@@ -222,19 +222,11 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     bf16x8_t bq[ScoreMfmaGeom<NCH>::NB][3];
     score_mfma_operands<NCH>(s_qhat[head_ok ? r16 : 0], head_ok, bq);
     score_mfma_rows<NCH, kWaves, kDepth, true>(
-        slab, 0, S, bq, sbufs, [&](int rowbase, const f32x4_t& acc) {
-          float m = fmaxf(acc[0], acc[1]);
-          if constexpr (G >= 4) m = fmaxf(m, fmaxf(acc[2], acc[3]));
-          if constexpr (G == 8) {
-            // heads 4-7 sit in the next 16 lanes: v_permlane16_swap exchanges the odd 16-lane
-            // rows of one operand with the even rows of the other, so with the same value in
-            // both, row 0 ends up holding its own value and row 1's
-            typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-            const u32x2_t sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
-            m = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-          }
-          const int row = rowbase + r16;
-          if (kgrp == 0 && row < S) {
+        slab, 0, S, bq, sbufs, [&](int rowbase_a, const f32x4_t& acc_a, int rowbase_b, const f32x4_t& acc_b) {
+          // lanes 0-15: the group maximum of tile a's rows, lanes 16-31: of tile b's
+          const float m = group_max_pair<G>(acc_a, acc_b);
+          const int row = (kgrp == 0 ? rowbase_a : rowbase_b) + r16;
+          if (kgrp < 2 && row < S) {
             const uint32_t key = float_to_key(m);
             s_key[padded_pos(row)] = key;
             atomicAdd(&s_sel.hist[0][key >> 21], 1u);

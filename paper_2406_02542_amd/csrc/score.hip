@@ -262,23 +262,20 @@ __global__ __launch_bounds__(256) void score_mfma_kernel(
   if constexpr (GROUP_MAX && !TILE) {
     // One score per row, the maximum over the group: qhat is the A operand and the row tile the
     // B operand, so a lane holds one row and four heads in its registers and the maximum needs
-    // no exchange between lanes (8 heads: one, between the lanes that hold heads 0-3 and 4-7);
-    // sixteen lanes store sixteen consecutive rows.
+    // no exchange between lanes but one, which also puts the results of two tiles side by side:
+    // thirty-two lanes store the rows of two tiles.
     const int kgrp = lane >> 4;
-    score_mfma_rows<NCH, 4, 8, true>(slab_rows, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
-      float m = fmaxf(acc[0], acc[1]);
-      if constexpr (G >= 4) m = fmaxf(m, fmaxf(acc[2], acc[3]));
-      if constexpr (G == 8) {
-        typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-        const u32x2_t sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(m), __float_as_uint(m), false, false);
-        m = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-      }
-      const int row = rowbase + r16;
-      if (kgrp == 0 && row < lane_end) {
-        scores[score_row * S_max + row] = m;
-        if (hist) hist_count(s_hist, m);
-      }
-    });
+    score_mfma_rows<NCH, 4, 8, true>(
+        slab_rows, row0, row_end, bq, bufs,
+        [&](int rowbase_a, const f32x4_t& acc_a, int rowbase_b, const f32x4_t& acc_b) {
+          // lanes 0-15: the group maximum of tile a's rows, lanes 16-31: of tile b's
+          const float m = group_max_pair<G>(acc_a, acc_b);
+          const int row = (kgrp == 0 ? rowbase_a : rowbase_b) + r16;
+          if (kgrp < 2 && row < lane_end) {
+            scores[score_row * S_max + row] = m;
+            if (hist) hist_count(s_hist, m);
+          }
+        });
   } else {
   score_mfma_rows<NCH, 4, 8>(slab_rows, row0, row_end, bq, bufs, [&](int rowbase, const f32x4_t& acc) {
     float v[4] = {acc[0], acc[1], acc[2], acc[3]};

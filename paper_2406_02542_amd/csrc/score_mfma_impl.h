@@ -65,6 +65,24 @@ __device__ __forceinline__ void score_mfma_operands(const float* qh, bool active
   }
 }
 
+// HEADS_IN_REGS epilogue for two tiles: acc_x holds heads 4 (lane / 16) .. + 3 of row lane % 16 of
+// tile x.  Returns, in the lanes of 16-lane row 0, the maximum over the G heads of tile a's row and,
+// in the lanes of row 1, that of tile b's row (rows 2 and 3 hold nothing of use).
+// v_permlane16_swap exchanges the odd 16-lane rows of its first operand with the even rows of
+// its second: afterwards the first holds (a.row0, b.row0, ..) and the second (a.row1, b.row1, ..).
+template <int G>
+__device__ __forceinline__ float group_max_pair(const f32x4_t& acc_a, const f32x4_t& acc_b) {
+  float ma = fmaxf(acc_a[0], acc_a[1]), mb = fmaxf(acc_b[0], acc_b[1]);
+  if constexpr (G >= 4) {
+    ma = fmaxf(ma, fmaxf(acc_a[2], acc_a[3]));
+    mb = fmaxf(mb, fmaxf(acc_b[2], acc_b[3]));
+  }
+  typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+  const u32x2_t sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(ma), __float_as_uint(mb), false, false);
+  if constexpr (G == 8) return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));  // heads 0-3 | 4-7
+  else return __uint_as_float(sw[0]);  // the heads sit in row 0 alone
+}
+
 // The two register buffers of the tile loop (DEPTH / 2 16-byte loads per lane each).
 template <int NCH, int DEPTH>
 struct ScoreMfmaBufs {
@@ -141,9 +159,12 @@ __device__ __forceinline__ void score_mfma_prefetch(const Rows& rows, int row0, 
 // DEPTH = 16-byte loads a lane keeps in flight (both buffers together).
 // HEADS_IN_REGS: the two operands trade places (qhat is the A operand, the row tile the B
 // operand), so that the accumulator holds the scores of ONE row per lane and four heads per
-// lane in its registers: emit(rowbase, acc) then gets acc[i] = score of head 4 (lane / 16) + i at
-// row rowbase + lane % 16, rowbase a multiple of 16.  A maximum over the heads of a group is
-// then taken in registers instead of across lanes.
+// lane in its registers, and tiles are handed out in pairs: emit(rowbase_a, acc_a, rowbase_b,
+// acc_b) gets acc_x[i] = score of head 4 (lane / 16) + i at row rowbase_x + lane % 16, rowbase_x a
+// multiple of 16 (rowbase_b >= row_end when a buffer holds an odd number of tiles and the second
+// one is missing).  A maximum over the heads of a group is then taken in registers instead of
+// across lanes, and one exchange between 16-lane rows (group_max_pair) leaves the two tiles'
+// results in different lanes, so that what follows — key, store, count — is done once for both.
 template <int NCH, int WAVES, int DEPTH = 8, bool HEADS_IN_REGS = false, typename Rows, typename Emit>
 __device__ __forceinline__ void score_mfma_rows(const Rows& rows, int row0, int row_end,
                                                 const bf16x8_t (&bq)[ScoreMfmaGeom<NCH>::NB][3],
@@ -157,6 +178,8 @@ __device__ __forceinline__ void score_mfma_rows(const Rows& rows, int row0, int 
   const ScoreMfmaLane<NCH, Rows> ln(rows);
 
   auto score_trip = [&](const uint4 (&raw)[UH][NL], int t0) {
+    f32x4_t pend = {0.f, 0.f, 0.f, 0.f};  // HEADS_IN_REGS: the first tile of a pair
+    int pend_row = 0;
 #pragma unroll
     for (int u = 0; u < UH; ++u) {
       const int trow = t0 + u * WAVES * RPS;
@@ -179,7 +202,19 @@ __device__ __forceinline__ void score_mfma_rows(const Rows& rows, int row0, int 
                                   : __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bq[j][t], acc, 0, 0, 0);
           }
         }
-        emit(HEADS_IN_REGS ? trow + 16 * rb : trow + 16 * rb + 4 * kgrp, acc);
+        if constexpr (HEADS_IN_REGS) {
+          constexpr bool kPairs = (UH * RB) % 2 == 0;
+          if constexpr (!kPairs) {
+            emit(trow + 16 * rb, acc, 0x3fffffff, acc);
+          } else if ((u * RB + rb) % 2 == 0) {
+            pend = acc;
+            pend_row = trow + 16 * rb;
+          } else {
+            emit(pend_row, pend, trow + 16 * rb, acc);
+          }
+        } else {
+          emit(trow + 16 * rb + 4 * kgrp, acc);
+        }
       }
     }
   };

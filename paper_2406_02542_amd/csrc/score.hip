@@ -364,13 +364,15 @@ static hipError_t launch_score_mfma_n(const Shape& s, int select_mode, const voi
 // bf16 cache, a power-of-two number of chunks per slab row, and at least two query heads that
 // share a slab: 2..8 per KV head, or several new tokens per sequence.  With rows of 16 or 32
 // bytes (d <= 16) a matrix instruction is spent on very few bytes and the vector kernel is the
-// faster one (d = 16, 4 heads per KV head, one selection per group, S = 131072: 33 against
-// 41 us; d = 8: 12 against 33 us), so grouped heads alone do not take this path there.
-static bool score_mfma_applies(const Shape& s) {
+// faster one when every head's score is written (d = 16, 4 heads per KV head, S = 131072: 39
+// against 44 us; d = 8: 12 against 33 us); with one selection per group, where the tiles are
+// finished in pairs in registers, 32-byte rows are level or slightly ahead (35 against 36 us).
+static bool score_mfma_applies(const Shape& s, int select_mode) {
   const int nch = s.d / 8;
   const bool tile = s.rg.queries > 1;
   const bool shared = (s.G >= 2 || tile) && s.G <= 8;
-  return s.dtype == 1 && shared && s.d % 8 == 0 && (nch & (nch - 1)) == 0 && (nch > 2 || tile);
+  const bool wide_enough = nch > 2 || tile || (nch == 2 && select_mode == 1);
+  return s.dtype == 1 && shared && s.d % 8 == 0 && (nch & (nch - 1)) == 0 && wide_enough;
 }
 
 static hipError_t launch_score_mfma(const Shape& s, int select_mode, const void* klo, float* scores,
@@ -473,7 +475,7 @@ hipError_t launch_qrot(const Shape& s, const void* q, const float* P, float* qha
 hipError_t launch_score(const Shape& s, int select_mode, const void* q, const float* P,
                         const void* klo, float* scores, float* qhat, uint32_t* hist_part,
                         int hist_chunks, hipStream_t st) {
-  if (score_mfma_applies(s))
+  if (score_mfma_applies(s, select_mode))
     return launch_score_mfma(s, select_mode, klo, scores, qhat, hist_part, hist_chunks, st);
   return s.dtype == 0
              ? launch_score_t<F32>(s, select_mode, q, P, klo, scores, qhat, hist_part, hist_chunks, st)

@@ -38,3 +38,27 @@ def random_case(seed):
 def test_random_shape(seed):
     w, mode, ragged, append, path, S_cap = random_case(seed)
     run_step_case(w, mode, ragged, append, path=path, S_cap=S_cap)
+
+
+def random_grouped_case(seed):
+    """Shapes the single-launch grouped-query kernel accepts (bf16, one selection per KV group,
+    d in {16, 32, 64}, up to 16384 rows, k <= 2048), with every option it has."""
+    rng = np.random.default_rng(99000 + seed)
+    G = int(rng.choice([2, 4, 8]))
+    Hkv = int(rng.integers(1, 4))
+    B = int(rng.integers(1, 5))
+    S = int(np.exp(rng.uniform(0.0, np.log(16384.0))))
+    d = int(rng.choice([16, 32, 64]))
+    k = int(rng.integers(1, min(S, 2048) + 1))
+    ragged = bool(rng.integers(0, 2))
+    append = bool(rng.integers(0, 2))
+    page_rows = int(rng.choice([0, 0, 256, 512, 1024]))
+    S_cap = None if page_rows else S + int(rng.integers(0, 40))
+    w = synth.Workload(f"rand_g{seed}", B, G * Hkv, Hkv, 128, S, "bf16", d, k, seed=99500 + seed)
+    return w, ragged, append, S_cap, page_rows
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shape_grouped_single_kernel(seed):
+    w, ragged, append, S_cap, page_rows = random_grouped_case(seed)
+    run_step_case(w, 1, ragged, append, path=api.PATH_FUSED, S_cap=S_cap, page_rows=page_rows)

@@ -4,9 +4,9 @@
 //
 //   gram_kernel        (chunk, head)  G = sum_s k_s^T k_s and column sums over a run of rows, on
 //                                     the matrix cores: a 32-row tile is written transposed into
-//                                     LDS so that both operands of v_mfma_f32_16x16x32_bf16 (eight
-//                                     consecutive rows of one column per lane) are one 16-byte LDS
-//                                     read; bf16 keys are exact, fp32 keys enter as two bf16 terms
+//                                     LDS (swizzled, see gram_swizzle) so that both operands of
+//                                     v_mfma_f32_16x16x32_bf16 (eight consecutive rows of one
+//                                     column per lane) are one 16-byte LDS read; bf16 keys are exact, fp32 keys enter as two bf16 terms
 //   cov_reduce_kernel  (head)         chunk partials added in a fixed order in fp64; sample
 //                                     covariance C = (G - s s^T / N) / (N - 1)
 //   jacobi_kernel      (head)         cyclic Jacobi eigensolver in fp64, C resident in LDS
@@ -24,7 +24,13 @@ typedef float cal_f32x4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kGramThreads = 256;
 constexpr int kGramTile = 32;    // rows per tile = the k dimension of one MFMA
-constexpr int kGramPitch = 80;   // bytes per column of the transposed tile (64 + 16: conflict-free 16-byte reads)
+constexpr int kGramPitch = 144;  // bytes per column of the transposed tile: 8 slots of 16 bytes + 16
+// A column's four 16-byte granules (rows 8 g .. 8 g + 7) sit in slots g ^ gram_swizzle(column).
+// Columns one 16-byte chunk of a key row apart (8 columns) are written by neighbouring lanes in
+// the same instruction and lie a multiple of 128 bytes apart whatever the pitch, i.e. in the same
+// bank; the swizzle spreads the 16 chunks of a row over 8 bank groups (2-way instead of 16-way
+// conflicts of the 2-byte transposing writes).
+__device__ __forceinline__ int gram_swizzle(int col) { return (col >> 3) & 7; }
 
 // NT = bf16 terms per element: 1 for bf16 storage, 2 for fp32 storage (value, remainder).
 template <int NT>
@@ -80,7 +86,7 @@ __global__ __launch_bounds__(kGramThreads) void gram_kernel(const void* __restri
         for (int e = 0; e < 8; ++e) {
           csum[e] += f[e];
           const uint16_t h = (uint16_t)((e & 1) ? (w[e >> 1] >> 16) : (w[e >> 1] & 0xffffu));
-          *reinterpret_cast<uint16_t*>(&s_t[0][(8 * c + e) * kGramPitch + row * 2]) = h;
+          *reinterpret_cast<uint16_t*>(&s_t[0][(8 * c + e) * kGramPitch + (((row >> 3) ^ gram_swizzle(8 * c + e)) << 4) + (row & 7) * 2]) = h;
         }
       } else {
         float f[4];
@@ -90,8 +96,8 @@ __global__ __launch_bounds__(kGramThreads) void gram_kernel(const void* __restri
           csum[e] += f[e];
           const uint16_t hi = BF16::round(f[e]);
           const uint16_t lo = BF16::round(f[e] - __uint_as_float((uint32_t)hi << 16));
-          *reinterpret_cast<uint16_t*>(&s_t[0][(4 * c + e) * kGramPitch + row * 2]) = hi;
-          *reinterpret_cast<uint16_t*>(&s_t[NT - 1][(4 * c + e) * kGramPitch + row * 2]) = lo;
+          *reinterpret_cast<uint16_t*>(&s_t[0][(4 * c + e) * kGramPitch + (((row >> 3) ^ gram_swizzle(4 * c + e)) << 4) + (row & 7) * 2]) = hi;
+          *reinterpret_cast<uint16_t*>(&s_t[NT - 1][(4 * c + e) * kGramPitch + (((row >> 3) ^ gram_swizzle(4 * c + e)) << 4) + (row & 7) * 2]) = lo;
         }
       }
     }
@@ -104,13 +110,14 @@ __global__ __launch_bounds__(kGramThreads) void gram_kernel(const void* __restri
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         a[t][i] = *reinterpret_cast<const cal_bf16x8_t*>(
-            &s_t[t][(32 * wave + 16 * i + r16) * kGramPitch + kgrp * 16]);
+            &s_t[t][(32 * wave + 16 * i + r16) * kGramPitch + ((kgrp ^ gram_swizzle(32 * wave + 16 * i + r16)) << 4)]);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       cal_bf16x8_t b[NT];
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        b[t] = *reinterpret_cast<const cal_bf16x8_t*>(&s_t[t][(16 * j + r16) * kGramPitch + kgrp * 16]);
+        b[t] = *reinterpret_cast<const cal_bf16x8_t*>(
+            &s_t[t][(16 * j + r16) * kGramPitch + ((kgrp ^ gram_swizzle(16 * j + r16)) << 4)]);
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         if constexpr (NT == 2) {  // smallest terms first; remainder x remainder is below fp32's last place

@@ -80,9 +80,16 @@ enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
  * (Hq / Hkv in {2, 4, 8}) with LOKI_SELECT_PER_KV_GROUP on a bf16 cache with d in {16, 32, 64},
  * S <= 16384, k <= 2048 (per-sequence lengths, the append and a paged cache of at most 64
  * pages per sequence of loki_decode_step included), one token per sequence (else
- * LOKI_ERR_UNSUPPORTED).  Both give the same selected sets; outputs agree to fp32 rounding
- * (bf16 rounding of two-term products for grouped heads). */
-enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_MASK = 0x300 };
+ * LOKI_ERR_UNSUPPORTED).  CLUSTER: the grouped-heads kernel of FUSED with 2, 4 or 8 cooperating
+ * blocks per (batch, KV head) unit, each on a slice of the unit's rows, for batches with too few
+ * units to fill the chip with one block each: the same conditions as FUSED for grouped heads
+ * except that the cache is contiguous (no page table), B * Hkv (rounded up to a multiple of 8) is
+ * at most half the device's compute units, and S / blocks <= 16384, min(k, S / blocks) <= 8192
+ * (so S up to 131072 and k up to 8192 with 8 blocks).  Its blocks wait for each other inside the
+ * launch: every wait is bounded, and a block that gives up (see loki_debug_cluster_spin_limit)
+ * writes NaN into its unit's outputs.  All three give the same selected sets; outputs agree
+ * to fp32 rounding (bf16 rounding of two-term products for grouped heads). */
+enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_CLUSTER = 0x300, LOKI_PATH_MASK = 0x300 };
 
 typedef struct {
   int32_t B;        /* sequences in the batch; B * Hq <= 65535           */
@@ -334,6 +341,15 @@ int loki_profile_create(loki_profile** out);
 int loki_profile_destroy(loki_profile* p);
 int loki_profile_attach(loki_profile* p);
 int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** names);
+
+/*
+ * Test aid for LOKI_PATH_CLUSTER, whose blocks wait for each other: the number of polls a block
+ * spends in one wait before it gives up, raises the error state and writes NaN into the outputs
+ * of its unit (the default, restored by 0, is a few seconds' worth; a wait normally ends within
+ * microseconds).  With a limit of 1 a test can watch the give-up path: the launch still ends and
+ * every output is either right or NaN.  Process-wide; affects launches enqueued afterwards.
+ */
+int loki_debug_cluster_spin_limit(unsigned polls);
 
 /*
  * Measurement aid, not part of the method: enqueues one trivial kernel that reads

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libloki.so")
 
 LOKI_F32, LOKI_BF16 = 0, 1
 SELECT_PER_QUERY_HEAD, SELECT_PER_KV_GROUP = 0, 1
-PATH_SPLIT, PATH_FUSED, PATH_MASK = 0x100, 0x200, 0x300
+PATH_SPLIT, PATH_FUSED, PATH_CLUSTER, PATH_MASK = 0x100, 0x200, 0x300, 0x300
 PROFILE_MAX_KERNELS = 8
 
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
     L.loki_profile_destroy.argtypes = [vp]
     L.loki_profile_attach.restype = i32
     L.loki_profile_attach.argtypes = [vp]
+    L.loki_debug_cluster_spin_limit.restype = i32
+    L.loki_debug_cluster_spin_limit.argtypes = [ctypes.c_uint]
     L.loki_stream_read.restype = i32
     L.loki_stream_read.argtypes = [vp, sz, vp]
     L.loki_profile_read.restype = i32
@@ -398,6 +400,12 @@ def loki_index_jaccard(idx_a: torch.Tensor, idx_b: torch.Tensor, out: torch.Tens
                                     _ptr(idx_b, "idx_b", torch.int32, n * k), n, k,
                                     _ptr(out, "out", torch.float32, n), _stream_ptr(stream)),
            "loki_index_jaccard")
+
+
+def loki_debug_cluster_spin_limit(polls: int) -> None:
+    """Sets how many polls a block of a PATH_CLUSTER launch waits for its unit's other blocks
+    (0 restores the default)."""
+    _check(lib().loki_debug_cluster_spin_limit(int(polls)), "loki_debug_cluster_spin_limit")
 
 
 def loki_stream_read(buf: torch.Tensor, nbytes: int, stream=None) -> None:

@@ -9,8 +9,8 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libloki.so")
-SOURCES = ["api.hip", "score.hip", "select.hip", "attend.hip", "attend_mfma.hip", "fused.hip", "fused_gqa.hip", "rotate.hip", "calibrate.hip"]
-HEADERS = ["common.h", "launch.h", "score_impl.h", "select_impl.h", "attend_impl.h", "score_mfma_impl.h", "attend_mfma_impl.h", os.path.join("..", "..", "include", "loki.h")]
+SOURCES = ["api.hip", "score.hip", "select.hip", "attend.hip", "attend_mfma.hip", "fused.hip", "fused_gqa.hip", "fused_gqa_cluster.hip", "rotate.hip", "calibrate.hip"]
+HEADERS = ["common.h", "launch.h", "score_impl.h", "select_impl.h", "attend_impl.h", "score_mfma_impl.h", "attend_mfma_impl.h", "fused_gqa_impl.h", "cluster_impl.h", os.path.join("..", "..", "include", "loki.h")]
 
 # -packed-fp32-ops is switched off on purpose: the compiler must not form v_pk_*_f32.
 HIPCC_FLAGS = [

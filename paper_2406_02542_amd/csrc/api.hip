@@ -89,7 +89,7 @@ int dense_splits(const Shape& s) {
   return n < 1 ? 1 : n;
 }
 
-Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base) {
+Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base, bool with_cluster) {
   Workspace w{};
   char* p = static_cast<char*>(base);
   size_t off = 0;
@@ -111,6 +111,8 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
     const size_t scratch_words = select_scratch_words(s.S, (int)heads_sel);
     w.sel_scratch = scratch_words ? reinterpret_cast<uint32_t*>(take(scratch_words * 4)) : nullptr;
     if (scratch_words && !p) w.sel_scratch = nullptr;
+    const size_t cluster_bytes = with_cluster ? fused_gqa_cluster_bytes(s, select_mode) : 0;
+    w.cluster = cluster_bytes ? take(cluster_bytes) : nullptr;
   }
   w.partial = reinterpret_cast<float*>(
       take(nsplit > 1 ? heads_q * nsplit * (size_t)(kD + 2) * sizeof(float) : 0));
@@ -358,7 +360,8 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   select_mode &= ~LOKI_PATH_MASK;
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
-  if (path != 0 && path != LOKI_PATH_SPLIT && path != LOKI_PATH_FUSED) return LOKI_ERR_INVALID_ARG;
+  if (path != 0 && path != LOKI_PATH_SPLIT && path != LOKI_PATH_FUSED && path != LOKI_PATH_CLUSTER)
+    return LOKI_ERR_INVALID_ARG;
   if (S < 1 || S > s.S_cap) return LOKI_ERR_INVALID_ARG;
   if (k < 1 || k > S) return LOKI_ERR_INVALID_ARG;
   if (d != s.d) return LOKI_ERR_UNSUPPORTED;
@@ -376,7 +379,9 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   s.pg = pg;
   if (s.G == 1) select_mode = LOKI_SELECT_PER_QUERY_HEAD;  // identical; one code path
   const int nsplit = gather_splits(s, select_mode);
-  const Workspace w = plan_workspace(s, select_mode, nsplit, workspace);
+  Workspace w = plan_workspace(s, select_mode, nsplit, workspace);
+  if (w.total_bytes > workspace_bytes && w.cluster != nullptr && path != LOKI_PATH_CLUSTER)
+    w = plan_workspace(s, select_mode, nsplit, workspace, false);  // no room for the exchange area: the other sequences
   if (w.total_bytes > workspace_bytes) return LOKI_ERR_WORKSPACE;
 
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -384,6 +389,8 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   int32_t* idx = out_idx ? out_idx : w.sel_idx;
   StageTimer tm(st);
   hipError_t e;
+  if (path == LOKI_PATH_CLUSTER && (s.G == 1 || !fused_gqa_cluster_eligible(s, select_mode)))
+    return LOKI_ERR_UNSUPPORTED;
   if (s.G == 1) {
     if (path == LOKI_PATH_FUSED && !fused_eligible(s)) return LOKI_ERR_UNSUPPORTED;
     if (path == LOKI_PATH_FUSED || (path == 0 && fused_preferred(s))) {
@@ -393,6 +400,12 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
       return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
     }
   } else {
+    if (path == LOKI_PATH_CLUSTER || (path == 0 && w.cluster != nullptr && fused_gqa_cluster_preferred(s, select_mode))) {
+      tm.begin("fused_decode");
+      e = launch_fused_gqa_cluster(s, q, P, klo, khi, v, out, out_idx, w.cluster, st);
+      tm.end();
+      return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
+    }
     if (path == LOKI_PATH_FUSED && !fused_gqa_eligible(s, select_mode)) return LOKI_ERR_UNSUPPORTED;
     if (path == LOKI_PATH_FUSED || (path == 0 && fused_gqa_preferred(s, select_mode))) {
       tm.begin("fused_decode");
@@ -665,6 +678,11 @@ int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** n
       return LOKI_ERR_HIP;
     if (names) names[i] = p->names[i];
   }
+  return LOKI_OK;
+}
+
+int loki_debug_cluster_spin_limit(unsigned polls) {
+  set_cluster_spin_limit(polls ? polls : kClusterSpinLimit);
   return LOKI_OK;
 }
 

@@ -78,10 +78,13 @@ struct Workspace {
   size_t ticket_words;    // its padded length in words
   uint32_t* sel_scratch;  // long sequences only: chunk histograms, candidates, bookkeeping
   float* partial;    // [B*Hq, nsplit, 130]
+  void* cluster;     // exchange area of the several-blocks-per-unit launch (fused_gqa_cluster.hip), or null
   size_t total_bytes;
 };
-// Lays the workspace out from `base` (may be null to only size it).
-Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base);
+// Lays the workspace out from `base` (may be null to only size it).  with_cluster = false leaves
+// the cluster launch's exchange area out (a workspace sized for a larger batch, which has no
+// such area, still serves the other kernel sequences).
+Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base, bool with_cluster = true);
 
 // Rotates every query; with s.ap set also rotates the new key of every unit and writes it and
 // the new value into row seq_len-1 of the unit's cache.
@@ -139,6 +142,22 @@ bool fused_gqa_preferred(const Shape& s, int select_mode);
 hipError_t launch_fused_gqa(const Shape& s, const void* q, const float* P, const void* klo,
                             const void* khi, const void* v, void* out, int32_t* out_idx,
                             hipStream_t st);
+// The same step with 2, 4 or 8 cooperating blocks per unit, for launches with fewer units than
+// compute units (fused_gqa_cluster.hip).  fused_gqa_cluster_blocks: blocks per unit the shape
+// would get (0: not applicable; a function of B, Hkv, G, d, S, k and the device alone, so that
+// the workspace can be sized without the step's other arguments); `region`: the workspace's
+// exchange area of fused_gqa_cluster_bytes bytes.
+int fused_gqa_cluster_blocks(const Shape& s, int select_mode);
+size_t fused_gqa_cluster_bytes(const Shape& s, int select_mode);
+bool fused_gqa_cluster_eligible(const Shape& s, int select_mode);
+bool fused_gqa_cluster_preferred(const Shape& s, int select_mode);
+// Polls a block of a cluster spends in one wait before it gives up (a test aid: the default is
+// seconds; nothing a wait is for takes longer than the launch itself).
+constexpr uint32_t kClusterSpinLimit = 1u << 22;
+void set_cluster_spin_limit(uint32_t polls);
+hipError_t launch_fused_gqa_cluster(const Shape& s, const void* q, const float* P, const void* klo,
+                                    const void* khi, const void* v, void* out, int32_t* out_idx,
+                                    void* region, hipStream_t st);
 // Calibration and diagnostics (calibrate.hip).
 size_t pca_workspace_bytes(int Hkv, long long N);
 hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, long long N, float* P,

@@ -57,14 +57,17 @@ def test_full_size_config(name, modes, n_units):
             assert np.array_equal(idx, idx2)
             say(f"{name} mode {mode} split path: "
                 f"{check_loki(case, mode, units=units, out_gpu=out2, idx_gpu=idx2)}")
-        elif mode == 1 and w.S <= 16384:
-            # grouped heads, one selection per group, 128 units: the library's choice is the
-            # single-launch grouped kernel (512-thread blocks, one per CU); pin both ways
-            out2, idx2 = case.run_loki(mode, path=api.PATH_SPLIT)
-            assert np.array_equal(idx, idx2)
-            say(f"{name} mode 1 split path: "
-                f"{check_loki(case, mode, units=units, out_gpu=out2, idx_gpu=idx2)}")
-            out3, idx3 = case.run_loki(mode, path=api.PATH_FUSED)
+        elif mode == 1:
+            # grouped heads, one selection per group, 128 / 32 units: the library's choice is the
+            # single launch with 2 / 8 cooperating blocks per unit; pin every sequence that takes
+            # the shape and require the same index lists
+            others = [("split", api.PATH_SPLIT)] + ([("one block per unit", api.PATH_FUSED)] if w.S <= 16384 else [])
+            for label, p in others:
+                out2, idx2 = case.run_loki(mode, path=p)
+                assert np.array_equal(idx, idx2)
+                say(f"{name} mode 1, {label}: "
+                    f"{check_loki(case, mode, units=units, out_gpu=out2, idx_gpu=idx2)}")
+            out3, idx3 = case.run_loki(mode, path=api.PATH_CLUSTER)
             assert np.array_equal(idx, idx3) and np.array_equal(out, out3)
     out = case.run_dense()
     assert np.all(np.isfinite(out))

@@ -254,6 +254,76 @@ def test_grouped_single_kernel_ties(S, k):
         assert st["heads_with_swaps"] == 0
 
 
+@pytest.mark.parametrize("shape", [(1, 8, 2, 3000, 32, 500), (4, 32, 8, 4000, 32, 700), (2, 16, 8, 2500, 16, 300),
+                                   (16, 16, 8, 6000, 64, 1000), (3, 8, 4, 1000, 32, 1000),
+                                   (1, 16, 2, 20000, 32, 2500), (2, 8, 1, 50000, 16, 4000)])
+def test_cluster_matches_oracle_and_split_path(shape):
+    """The launch with several blocks per unit (2, 4 or 8, by the number of units): outputs against
+    the oracle, index lists identical to the split path's (the same matrix-core scoring)."""
+    B, Hq, Hkv, S, d, k = shape
+    w, x = _case(f"cluster_{Hq}_{Hkv}_{S}", B, Hq, Hkv, S, "bf16", d, k, seed=7000 + S)
+    case = DeviceCase(w, x)
+    outc, idxc = case.run_loki(1, path=api.PATH_CLUSTER)
+    _, idxs = case.run_loki(1, path=api.PATH_SPLIT)
+    assert np.array_equal(idxc, idxs)
+    st = check_loki(case, 1, out_gpu=outc, idx_gpu=idxc)
+    say(f"{w.name}: {st}")
+    assert st["heads_with_swaps"] == 0
+
+
+@pytest.mark.parametrize("S,k", [(3000, 1100), (12000, 900), (40000, 5000)])
+def test_cluster_ties(S, k):
+    """Equal scores across the blocks of a unit: an all-zero cache (every row ties: all three
+    histogram exchanges run and each block takes what the blocks before it leave), planted
+    duplicates (ties inside the candidate exchange) and a cache whose rows take 7 distinct
+    values.  Lowest position wins; the index lists must equal the split path's."""
+    w, x = _case(f"cluster_ties_{S}", 1, 8, 2, S, "bf16", 32, k, seed=4100 + S)
+    x0 = dict(x)
+    x0["khat"] = np.zeros_like(x["khat"])
+    out, idx = DeviceCase(w, x0).run_loki(1, path=api.PATH_CLUSTER)
+    for h in range(2):
+        assert idx[0, h].tolist() == list(range(k))
+    for reps in (100, 7):
+        xd = dict(x)
+        kd = x["khat"].copy()
+        kd[:, :, reps:, :] = np.tile(kd[:, :, :reps, :], (1, 1, S // reps + 1, 1))[:, :, :S - reps, :]
+        xd["khat"] = kd
+        case = DeviceCase(w, xd)
+        _, idxs = case.run_loki(1, path=api.PATH_SPLIT)
+        outc, idxc = case.run_loki(1, path=api.PATH_CLUSTER)
+        assert np.array_equal(idxs, idxc)
+        st = check_loki(case, 1, out_gpu=outc, idx_gpu=idxc)
+        say(f"{reps} distinct rows: {st}")
+        assert st["heads_with_swaps"] == 0
+
+
+def test_cluster_wait_gives_up_cleanly():
+    """The blocks of a unit wait for each other with a bounded number of polls.  With the bound
+    set to one poll by the host, blocks that find a partner late give up: the launch must still
+    end, and every unit's output is then either NaN (for all its heads) or the regular result.
+    With the default restored the same call is regular again."""
+    w, x = _case("cluster_give_up", 2, 16, 4, 20000, "bf16", 32, 2000, seed=7777)
+    case = DeviceCase(w, x)
+    ref, idx_ref = case.run_loki(1, path=api.PATH_CLUSTER)
+    assert np.all(np.isfinite(ref))
+    api.loki_debug_cluster_spin_limit(1)
+    try:
+        out, _ = case.run_loki(1, path=api.PATH_CLUSTER)
+    finally:
+        api.loki_debug_cluster_spin_limit(0)
+    gave_up = 0
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            o = out[b, h * w.G:(h + 1) * w.G]
+            if np.all(np.isnan(o)):
+                gave_up += 1
+            else:
+                assert np.array_equal(o, ref[b, h * w.G:(h + 1) * w.G])
+    say(f"units that gave up with a one-poll limit: {gave_up} of {w.B * w.Hkv}")
+    again, idx_again = case.run_loki(1, path=api.PATH_CLUSTER)
+    assert np.array_equal(again, ref) and np.array_equal(idx_again, idx_ref)
+
+
 def test_heavy_hitters_are_selected():
     """The peaked-attention recipe of the long-context config at reduced size: the planted
     positions carry > 90 % of the mass and must all be among the selected rows."""

@@ -58,6 +58,30 @@ def random_grouped_case(seed):
     return w, ragged, append, S_cap, page_rows
 
 
+def random_cluster_case(seed):
+    """Shapes the launch with several blocks per unit accepts (bf16, one selection per KV group,
+    d in {16, 32, 64}, at most 128 units, slices of at most 16384 rows), with every option it has:
+    1 to 60000 rows, so that slices run from a single row (and empty ones) to several thousand."""
+    rng = np.random.default_rng(123000 + seed)
+    G = int(rng.choice([2, 4, 8]))
+    Hkv = int(rng.choice([1, 2, 3, 8]))
+    B = int(rng.integers(1, 6))
+    S = int(np.exp(rng.uniform(0.0, np.log(60000.0))))
+    d = int(rng.choice([16, 32, 64]))
+    k = int(rng.integers(1, min(S, 6000) + 1))
+    ragged = bool(rng.integers(0, 2))
+    append = bool(rng.integers(0, 2))
+    S_cap = S + int(rng.integers(0, 40))
+    w = synth.Workload(f"rand_c{seed}", B, G * Hkv, Hkv, 128, S, "bf16", d, k, seed=123500 + seed)
+    return w, ragged, append, S_cap
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_random_shape_grouped_cluster(seed):
+    w, ragged, append, S_cap = random_cluster_case(seed)
+    run_step_case(w, 1, ragged, append, path=api.PATH_CLUSTER, S_cap=S_cap)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shape_grouped_single_kernel(seed):
     w, ragged, append, S_cap, page_rows = random_grouped_case(seed)

@@ -230,6 +230,19 @@ def test_step_gqa_single_kernel_append(G, S, k, d):
     run_step_case(w, 1, True, True, path=api.PATH_FUSED, lens=[S, 1, 2, 257])
 
 
+@pytest.mark.parametrize("G,B,Hkv,S,k,d", [(4, 3, 2, 1500, 300, 32), (8, 5, 8, 9000, 1200, 16),
+                                             (2, 2, 2, 30000, 3000, 64), (4, 16, 8, 2000, 256, 32)])
+def test_step_gqa_cluster(G, B, Hkv, S, k, d):
+    """Several cooperating blocks per unit (8, 4, 8 and 2 of them): per-sequence lengths, so that
+    slices differ from sequence to sequence; the append, written by the block whose slice holds
+    the last row; both; and sequences so short that most blocks of a unit hold no row at all."""
+    w = synth.Workload(f"step_cluster_g{G}", B, G * Hkv, Hkv, 128, S, "bf16", d, k, seed=G * 1000 + S)
+    for ragged, append in [(True, False), (False, True), (True, True)]:
+        run_step_case(w, 1, ragged, append, path=api.PATH_CLUSTER)
+    lens = ([1, 2, 65, S, 64, 129, 3, S - 1] * 2)[:B]
+    run_step_case(w, 1, True, True, path=api.PATH_CLUSTER, lens=lens, S_cap=S + 13)
+
+
 @pytest.mark.parametrize("mode", [0, 1])
 def test_step_long_sequences_multiblock_select(mode):
     """S_max = 40000 (three chunks of the multi-block select): one full sequence, one inside

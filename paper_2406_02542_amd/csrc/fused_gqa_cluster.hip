@@ -49,12 +49,12 @@ bool fused_gqa_cluster_eligible(const Shape& s, int select_mode) {
 
 bool fused_gqa_cluster_preferred(const Shape& s, int select_mode) {
   if (!fused_gqa_cluster_eligible(s, select_mode)) return false;
-  // The exchanges between a unit's blocks cost about 10 us; they pay off once a unit moves
-  // enough bytes (measured at 16 to 128 units, 4 and 8 query heads per KV head: from
-  // S = 12288, k = 1536, d = 32 on, 1.5 MB a unit, the cluster is 3 to 25 % faster than the better
-  // of the other two sequences; at S = 8192, k = 1024, 1 MB a unit, it is 3 to 10 % slower).
+  // The exchanges between a unit's blocks cost about 10 us; they pay off once a unit has enough
+  // rows or moves enough bytes (measured at 16 to 128 units, 2, 4 and 8 query heads per KV head:
+  // from S = 12288 on the cluster is level with or up to 25 % faster than the better of the other
+  // two sequences; at S = 8192, k = 1024, d = 32, 1 MB a unit, it is 3 to 10 % slower).
   const long long unit_bytes = (long long)s.S * s.d * 2 + (long long)s.k * kD * 4;
-  return unit_bytes >= 1310720;
+  return s.S >= 12288 || unit_bytes >= 1310720;
 }
 
 static std::atomic<uint32_t> g_spin_limit{kClusterSpinLimit};

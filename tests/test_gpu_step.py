@@ -363,11 +363,14 @@ def test_pca_attn(G, dtype, d, S):
 
 
 # ------------------------------------------------------------------------- graph capture --
-@pytest.mark.parametrize("G,mode", [(1, 0), (4, 0), (4, 1)])
-def test_decode_step_replays_from_a_captured_graph(G, mode):
+@pytest.mark.parametrize("G,mode,path", [(1, 0, 0), (4, 0, 0), (4, 1, 0), (4, 1, api.PATH_FUSED),
+                                         (4, 1, api.PATH_CLUSTER)])
+def test_decode_step_replays_from_a_captured_graph(G, mode, path):
     """The library allocates nothing and records no memset, so a step can be captured once and
     replayed: every replay (with eager work and synchronisations in between, and with the
-    inputs changed in place) must equal the eager result on the same inputs bit for bit."""
+    inputs changed in place) must equal the eager result on the same inputs bit for bit.  (The
+    launch with cooperating blocks clears its meeting flags with a kernel of its own, which is
+    part of the captured sequence.)"""
     w = synth.Workload(f"graph_g{G}", 2, 2 * G, 2, 128, 3000, "bf16", 32, 600, seed=9970 + G)
     x = synth.make_inputs(w)
     st = synth.make_step_inputs(w, x["P"])
@@ -383,7 +386,7 @@ def test_decode_step_replays_from_a_captured_graph(G, mode):
     out_e = torch.zeros_like(out_g)
 
     def step(out):
-        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode, ws, out, None,
+        api.loki_decode_step(lay, q, P, klo, khi, v, w.S, w.d, w.k, mode | path, ws, out, None,
                              seq_lens=lens, ks=ks, k_new=k_new, v_new=v_new)
 
     step(out_e)  # warm-up outside the capture (first-launch set-up of the kernels)

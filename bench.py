@@ -192,11 +192,15 @@ def bench_configs(args, torch, api, synth):
             khis = [kf[..., d:].contiguous() if d < base.D else None for kf in kfs]
             for w in [w for w in variants if w.d == d]:
                 for mode in modes:
-                    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+                    # a workspace allocated once, cleared, and written by the library alone, as a
+                    # serving loop holds it: the launch with cooperating blocks per unit (few
+                    # units, long sequences) then needs no clearing kernel in front
+                    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode, zeroed=True)
+                    mode_ws = mode | api.WORKSPACE_ZEROED
 
                     def loki_step(i):
                         c = i % copies
-                        api.loki_decode_attn(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode, ws,
+                        api.loki_decode_attn(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode_ws, ws,
                                              out, None, stream)
 
                     l_us, l_wall = event_timed_steps(torch, loki_step, steps, 10, stream)
@@ -206,7 +210,7 @@ def bench_configs(args, torch, api, synth):
                     grouped_literal = (mode == 0 and w.G > 1)
                     e = {"workload": name, "B": w.B, "Hq": w.Hq, "Hkv": w.Hkv, "S": w.S, "d": w.d,
                          "k": w.k, "select_mode": mode, "units": w.B * w.Hkv, "steps": steps,
-                         "cache_copies": copies,
+                         "cache_copies": copies, "workspace": "zeroed once, then the library's alone",
                          "us_per_step": med, "us_p10": _pct(l_us, 10), "us_p90": _pct(l_us, 90),
                          "us_mean": float(np.mean(l_us)), "us_wall_clock": l_wall,
                          "tokens_heads_per_s": w.B * w.Hq / (med * 1e-6),
@@ -224,7 +228,7 @@ def bench_configs(args, torch, api, synth):
 
                         def append_step(i):
                             c = i % copies
-                            api.loki_decode_step(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode,
+                            api.loki_decode_step(lay, q, P, klos[c], khis[c], vs[c], w.S, w.d, w.k, mode_ws,
                                                  ws, out, None, k_new=kn, v_new=vn, stream=stream)
 
                         a_us, _ = event_timed_steps(torch, append_step, steps, 10, stream)

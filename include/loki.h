@@ -91,6 +91,16 @@ enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
  * to fp32 rounding (bf16 rounding of two-term products for grouped heads). */
 enum { LOKI_PATH_SPLIT = 0x100, LOKI_PATH_FUSED = 0x200, LOKI_PATH_CLUSTER = 0x300, LOKI_PATH_MASK = 0x300 };
 
+/* Optional bit OR-ed into select_mode: the caller vouches that the workspace was filled with
+ * zeros after it was allocated and that nothing but calls of this library (any shapes) has
+ * written to it since.  LOKI_PATH_CLUSTER keeps a few control words at the start of the
+ * workspace that must be zero when a launch starts; every finished launch leaves them zero, so
+ * with this bit the clearing kernel in front of the launch (about 5 us) is left out.  Without the
+ * bit the workspace needs no initialisation at all.  A launch whose blocks gave up waiting
+ * (NaN outputs) leaves a mark there: with the bit, later LOKI_PATH_CLUSTER launches on that
+ * workspace write NaN too until it is filled with zeros again. */
+enum { LOKI_WORKSPACE_ZEROED = 0x400 };
+
 typedef struct {
   int32_t B;        /* sequences in the batch; B * Hq <= 65535           */
   int32_t Hq;       /* query heads                                    */
@@ -114,8 +124,13 @@ int loki_cache_bytes(const loki_layout* layout, size_t* klo_bytes, size_t* khi_b
 /* Bytes of workspace loki_decode_attn needs for (S, d, k, select_mode) and
  * dense_decode_attn needs for S (pass d = 0, k = 0, select_mode = -1 for the
  * dense baseline).  Host-only; touches no GPU.  The workspace holds the
- * approximate scores, the selected indices, qhat and the partial softmax
- * results of split rows; its contents are undefined between calls. */
+ * approximate scores, the selected indices, qhat, the partial softmax
+ * results of split rows and, for shapes that LOKI_PATH_CLUSTER takes, the area
+ * its blocks exchange counts through; its contents are undefined between calls
+ * and nothing in it has to be initialised.  A workspace sized for a larger
+ * batch of the same layout also serves a smaller one (without room for the
+ * exchange area the library picks another kernel sequence; LOKI_PATH_CLUSTER
+ * pinned then returns LOKI_ERR_WORKSPACE). */
 int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int select_mode,
                          size_t* bytes);
 

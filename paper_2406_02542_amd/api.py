@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libloki.so")
 LOKI_F32, LOKI_BF16 = 0, 1
 SELECT_PER_QUERY_HEAD, SELECT_PER_KV_GROUP = 0, 1
 PATH_SPLIT, PATH_FUSED, PATH_CLUSTER, PATH_MASK = 0x100, 0x200, 0x300, 0x300
+WORKSPACE_ZEROED = 0x400
 PROFILE_MAX_KERNELS = 8
 
 
@@ -175,9 +176,11 @@ def alloc_cache(layout: Layout, device="cuda"):
 
 
 def alloc_workspace(layout: Layout, S: int, d: int, k: int, select_mode: int,
-                    device="cuda") -> torch.Tensor:
+                    device="cuda", zeroed: bool = False) -> torch.Tensor:
+    """zeroed: a workspace filled with zeros, which the caller may then pass with WORKSPACE_ZEROED."""
     n = loki_workspace_bytes(layout, S, d, k, select_mode)
-    return torch.empty(max(n, 256), dtype=torch.uint8, device=device)
+    make = torch.zeros if zeroed else torch.empty
+    return make(max(n, 256), dtype=torch.uint8, device=device)
 
 
 def loki_rotate_keys(layout: Layout, k_new: torch.Tensor, P: torch.Tensor, klo: torch.Tensor,
@@ -217,7 +220,7 @@ def loki_decode_attn(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
     dt = _torch_dtype(layout)
     rows = layout.B * layout.Hkv
     nq = layout.B * layout.Hq * layout.D
-    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
+    hsel = layout.Hq if (select_mode & ~(PATH_MASK | WORKSPACE_ZEROED)) == SELECT_PER_QUERY_HEAD else layout.Hkv
     _check(lib().loki_decode_attn(
         ctypes.byref(layout),
         _ptr(q, "q", dt, nq),
@@ -243,7 +246,7 @@ def loki_decode_attn_static(layout: Layout, q: torch.Tensor, P: torch.Tensor, kl
     dt = _torch_dtype(layout)
     rows = layout.B * layout.Hkv
     nq = layout.B * layout.Hq * layout.D
-    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
+    hsel = layout.Hq if (select_mode & ~(PATH_MASK | WORKSPACE_ZEROED)) == SELECT_PER_QUERY_HEAD else layout.Hkv
     _check(lib().loki_decode_attn_static(
         ctypes.byref(layout),
         _ptr(q, "q", dt, nq),
@@ -280,7 +283,7 @@ def loki_decode_step(layout: Layout, q: torch.Tensor, P: torch.Tensor, klo: torc
     m = max(1, queries_per_seq)
     rows = layout.B * layout.Hkv
     nq = layout.B * m * layout.Hq * layout.D
-    hsel = layout.Hq if (select_mode & ~PATH_MASK) == SELECT_PER_QUERY_HEAD else layout.Hkv
+    hsel = layout.Hq if (select_mode & ~(PATH_MASK | WORKSPACE_ZEROED)) == SELECT_PER_QUERY_HEAD else layout.Hkv
     args = StepArgs(
         _ptr(seq_lens, "seq_lens", torch.int32, layout.B * m),
         _ptr(ks, "ks", torch.int32, layout.B * m),

@@ -102,6 +102,7 @@ Workspace plan_workspace(const Shape& s, int select_mode, int nsplit, void* base
   if (select_mode == -2) w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
   if (select_mode >= 0) {
     const size_t heads_sel = (select_mode == 1) ? (size_t)s.B * s.Hkv : heads_q;
+    w.cluster_ctl = reinterpret_cast<uint32_t*>(take(kClusterCtlBytes));  // at offset 0 for every shape
     w.qhat = reinterpret_cast<float*>(take(heads_q * kD * sizeof(float)));
     w.scores = reinterpret_cast<float*>(take(heads_sel * s.S * sizeof(float)));
     w.sel_idx = reinterpret_cast<int32_t*>(take(heads_sel * s.k * sizeof(int32_t)));
@@ -275,7 +276,7 @@ int loki_workspace_bytes(const loki_layout* layout, int S, int d, int k, int sel
     return LOKI_OK;
   }
   if (select_mode < 0) return LOKI_ERR_INVALID_ARG;
-  select_mode &= ~LOKI_PATH_MASK;
+  select_mode &= ~(LOKI_PATH_MASK | LOKI_WORKSPACE_ZEROED);
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
   if (d != s.d) return LOKI_ERR_UNSUPPORTED;
@@ -357,7 +358,8 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   if (!q || !P || !klo || !v || !out || !workspace) return LOKI_ERR_INVALID_ARG;
   if (s.d < 128 && !khi) return LOKI_ERR_INVALID_ARG;
   const int path = select_mode & LOKI_PATH_MASK;
-  select_mode &= ~LOKI_PATH_MASK;
+  const bool ws_zeroed = (select_mode & LOKI_WORKSPACE_ZEROED) != 0;
+  select_mode &= ~(LOKI_PATH_MASK | LOKI_WORKSPACE_ZEROED);
   if (select_mode != LOKI_SELECT_PER_QUERY_HEAD && select_mode != LOKI_SELECT_PER_KV_GROUP)
     return LOKI_ERR_INVALID_ARG;
   if (path != 0 && path != LOKI_PATH_SPLIT && path != LOKI_PATH_FUSED && path != LOKI_PATH_CLUSTER)
@@ -402,7 +404,7 @@ static int decode_impl(const loki_layout* layout, const void* q, const float* P,
   } else {
     if (path == LOKI_PATH_CLUSTER || (path == 0 && w.cluster != nullptr && fused_gqa_cluster_preferred(s, select_mode))) {
       tm.begin("fused_decode");
-      e = launch_fused_gqa_cluster(s, q, P, klo, khi, v, out, out_idx, w.cluster, st);
+      e = launch_fused_gqa_cluster(s, q, P, klo, khi, v, out, out_idx, w.cluster_ctl, ws_zeroed, w.cluster, st);
       tm.end();
       return e == hipSuccess ? LOKI_OK : LOKI_ERR_HIP;
     }
@@ -463,9 +465,10 @@ int loki_decode_attn_static(const loki_layout* layout, const void* q, const floa
   void* ptr = nullptr;
   const int ra = static_scratch_address(&ptr);
   if (ra != LOKI_OK) return ra;
-  // nothing in the workspace has to start at zero: every kernel writes what the next one reads
+  // the array starts as zeros and only this library writes it: the condition of
+  // LOKI_WORKSPACE_ZEROED (nothing else in the workspace has to start at zero)
   return decode_impl(layout, q, P, const_cast<void*>(klo), const_cast<void*>(khi),
-                     const_cast<void*>(v), S, d, k, select_mode, Ragged{}, Append{}, Paging{}, ptr,
+                     const_cast<void*>(v), S, d, k, select_mode | LOKI_WORKSPACE_ZEROED, Ragged{}, Append{}, Paging{}, ptr,
                      (size_t)LOKI_STATIC_SCRATCH_BYTES, out, out_idx, stream);
 }
 

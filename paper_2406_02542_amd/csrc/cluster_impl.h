@@ -19,16 +19,14 @@
 
 namespace loki {
 
-constexpr int kClusterMax = 8;        // blocks per unit at most
-constexpr int kClusterFlagStride = 16;     // words between the arrival flags of two blocks: a cache line each
-constexpr int kClusterCounterStride = (kClusterMax + 1) * kClusterFlagStride;  // words of a unit's flags and ticket
 constexpr int kClusterRounds = 3;     // histogram exchanges of one launch at most (11 + 11 + 10 bits)
 
 // Device memory of the exchange (all of it inside the caller's workspace).
 struct ClusterArgs {
   uint32_t* counters = nullptr;  // [units][kClusterCounterStride]: the blocks' arrival flags (kClusterFlagStride
-                                 // words apart), then the count of finished blocks; zero at launch
-  uint32_t* error = nullptr;     // one word, zero at launch: set when a block gave up waiting
+                                 // words apart), then the count of finished blocks; zero at launch, and
+                                 // left zero by the block that merges the unit
+  uint32_t* error = nullptr;     // one word: set when a block gave up waiting
   uint32_t* xhist = nullptr;     // [units][kClusterRounds][C][threads] slots: suffix sums of the digit histograms
   size_t xhist_bytes = 0;
   uint32_t* xcand = nullptr;     // [units][candidate capacity] low key bits of the threshold-bin rows
@@ -58,8 +56,10 @@ __device__ __forceinline__ uint32_t cluster_load_u32(const uint32_t* p) {
 // the meeting's number there once its own stores are acknowledged, and the first C lanes of its
 // first wave poll one flag each until all carry that number.  Returns false when the others did
 // not arrive within spin_limit polls.  Every thread of the block calls it.
+// poisoned (thread 0's value counts): the workspace's error word was set when the launch began —
+// an earlier launch on it gave up and left flags behind; the wait then fails at once.
 __device__ __forceinline__ bool cluster_arrive_and_wait(uint32_t* flags, int C, int c, uint32_t meet,
-                                                        uint32_t spin_limit, ClusterSmem& cs) {
+                                                        uint32_t spin_limit, bool poisoned, ClusterSmem& cs) {
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this thread's stores are acknowledged
   __syncthreads();
   if (threadIdx.x < 64) {
@@ -74,7 +74,7 @@ __device__ __forceinline__ bool cluster_arrive_and_wait(uint32_t* flags, int C, 
       ++spins;
     }
     const bool all = __ballot(!ok) == 0ull;
-    if (lane == 0) cs.ok = all ? 1 : 0;
+    if (lane == 0) cs.ok = (all && !poisoned) ? 1 : 0;
   }
   __syncthreads();
   return cs.ok != 0;
@@ -108,7 +108,7 @@ template <int THREADS>
 __device__ __forceinline__ bool cluster_hist_round(const uint32_t* hist, __amdgpu_buffer_rsrc_t xh,
                                                    uint32_t xh_off, int C, int c, uint32_t* flags,
                                                    uint32_t meet, uint32_t rem, uint32_t spin_limit,
-                                                   uint32_t* wave_tot, ClusterSmem& cs) {
+                                                   bool poisoned, uint32_t* wave_tot, ClusterSmem& cs) {
   constexpr int kWaves = THREADS / 64;
   constexpr int BPT = 2048 / THREADS;
   static_assert(BPT == 4, "a slot holds the sums of four bins and of the bin above");
@@ -135,7 +135,7 @@ __device__ __forceinline__ bool cluster_hist_round(const uint32_t* hist, __amdgp
     cluster_store_x4(xh, slot, cluster_u32x4{s0, s1, s2, s3});
     cluster_store_x4(xh, slot + 16, cluster_u32x4{s4, 0u, 0u, 0u});
   }
-  if (!cluster_arrive_and_wait(flags, C, c, meet, spin_limit, cs)) return false;
+  if (!cluster_arrive_and_wait(flags, C, c, meet, spin_limit, poisoned, cs)) return false;
   // sc[cc][j]: block cc's suffix sum at bin top - 3 + j (j = 4: the bin above this thread's)
   uint32_t sc[kClusterMax][BPT + 1];
 #pragma unroll

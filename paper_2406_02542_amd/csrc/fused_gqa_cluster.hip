@@ -19,9 +19,14 @@ extern "C" int loki_debug_read_cluster_ts(unsigned long long* host_dst, size_t c
 }
 #endif
 
-__global__ void cluster_reset_kernel(uint32_t* words, int n) {
+// Clears the control words that must start at zero: every block's arrival flag and the ticket
+// of every unit (one word in each kClusterFlagStride words), and the error word behind the
+// last unit a launch can have.
+__global__ void cluster_reset_kernel(uint32_t* counters, int units) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) words[i] = 0u;
+  const int n = units * (kClusterMax + 1);
+  if (i < n) counters[(size_t)i * kClusterFlagStride] = 0u;
+  if (i == n) counters[(size_t)kClusterMaxUnits * kClusterCounterStride] = 0u;
 }
 
 static inline int cluster_padded_units(const Shape& s) { return (s.B * s.Hkv + 7) / 8 * 8; }
@@ -34,6 +39,7 @@ int fused_gqa_cluster_blocks(const Shape& s, int select_mode) {
   // every block of the launch must be resident at once (the blocks of a unit wait for each
   // other): one block per compute unit at most
   const int padded = cluster_padded_units(s), cus = device_cus();
+  if (s.B * s.Hkv > kClusterMaxUnits) return 0;
   int C = 1;
   while (2 * C <= kClusterMax && padded * 2 * C <= cus) C *= 2;
   if (C < 2) return 0;
@@ -62,15 +68,13 @@ void set_cluster_spin_limit(uint32_t polls) { g_spin_limit.store(polls, std::mem
 
 namespace {
 struct ClusterPlan {
-  size_t counters, xhist, xcand, partial, total;  // byte offsets; counters are followed by the error word
+  size_t xhist, xcand, partial, total;  // byte offsets
 };
 ClusterPlan cluster_plan(const Shape& s, int C) {
   const size_t units = (size_t)s.B * s.Hkv;
   auto up = [](size_t x) { return (x + 255) / 256 * 256; };
   ClusterPlan p;
   size_t off = 0;
-  p.counters = off;
-  off += up((units * kClusterCounterStride + 1) * 4);
   p.xhist = off;
   off += up(units * kClusterRounds * C * kClusterThreads * kClusterSlotBytes);
   p.xcand = off;
@@ -90,7 +94,8 @@ size_t fused_gqa_cluster_bytes(const Shape& s, int select_mode) {
 template <int NCH, int G>
 static hipError_t launch_cluster_k(const Shape& s, int C, const void* q, const float* P, const void* klo,
                                    const void* khi, const void* v, void* out, int32_t* out_idx,
-                                   void* region, uint32_t spin_limit, hipStream_t st) {
+                                   uint32_t* ctl, bool ctl_clean, void* region, uint32_t spin_limit,
+                                   hipStream_t st) {
   using Lds = GqaLds<kClusterThreads, G, true>;
   auto kern = fused_gqa_kernel<kClusterThreads, NCH, G, kClusterKpt, false, true>;
   const int L = gqa_slice_rows(s.S, C);
@@ -102,8 +107,8 @@ static hipError_t launch_cluster_k(const Shape& s, int C, const void* q, const f
   const ClusterPlan p = cluster_plan(s, C);
   char* base = static_cast<char*>(region);
   ClusterArgs cl;
-  cl.counters = reinterpret_cast<uint32_t*>(base + p.counters);
-  cl.error = cl.counters + (size_t)s.B * s.Hkv * kClusterCounterStride;
+  cl.counters = ctl;
+  cl.error = ctl + (size_t)kClusterMaxUnits * kClusterCounterStride;
   cl.xhist = reinterpret_cast<uint32_t*>(base + p.xhist);
   cl.xhist_bytes = p.xcand - p.xhist;
   cl.xcand = reinterpret_cast<uint32_t*>(base + p.xcand);
@@ -112,10 +117,12 @@ static hipError_t launch_cluster_k(const Shape& s, int C, const void* q, const f
   cl.C = C;
   cl.units = s.B * s.Hkv;
   cl.spin_limit = spin_limit;
-  // the meeting-point counters and the error word start at zero (a kernel, not a memset: a
-  // caller may be capturing the stream into a graph)
-  const int n_zero = cl.units * kClusterCounterStride + 1;
-  hipLaunchKernelGGL(cluster_reset_kernel, dim3((n_zero + 255) / 256), dim3(256), 0, st, cl.counters, n_zero);
+  // the arrival flags and tickets start at zero: unless the caller vouches for the workspace,
+  // clear them (with a kernel, not a memset: a caller may be capturing the stream into a graph)
+  if (!ctl_clean) {
+    const int n_zero = cl.units * (kClusterMax + 1) + 1;
+    hipLaunchKernelGGL(cluster_reset_kernel, dim3((n_zero + 255) / 256), dim3(256), 0, st, cl.counters, cl.units);
+  }
   hipLaunchKernelGGL(kern, dim3(cluster_padded_units(s) * C), dim3(kClusterThreads), lds, st,
                      static_cast<const uint16_t*>(klo), static_cast<const uint16_t*>(khi),
                      static_cast<const uint16_t*>(v), static_cast<const uint16_t*>(q), P,
@@ -126,25 +133,26 @@ static hipError_t launch_cluster_k(const Shape& s, int C, const void* q, const f
 template <int NCH>
 static hipError_t launch_cluster_n(const Shape& s, int C, const void* q, const float* P, const void* klo,
                                    const void* khi, const void* v, void* out, int32_t* out_idx,
-                                   void* region, uint32_t spin_limit, hipStream_t st) {
+                                   uint32_t* ctl, bool ctl_clean, void* region, uint32_t spin_limit,
+                                   hipStream_t st) {
   switch (s.G) {
-    case 2: return launch_cluster_k<NCH, 2>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
-    case 4: return launch_cluster_k<NCH, 4>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
-    case 8: return launch_cluster_k<NCH, 8>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
+    case 2: return launch_cluster_k<NCH, 2>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
+    case 4: return launch_cluster_k<NCH, 4>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
+    case 8: return launch_cluster_k<NCH, 8>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_fused_gqa_cluster(const Shape& s, const void* q, const float* P, const void* klo,
                                     const void* khi, const void* v, void* out, int32_t* out_idx,
-                                    void* region, hipStream_t st) {
-  if (!fused_gqa_cluster_eligible(s, 1) || region == nullptr) return hipErrorInvalidValue;
+                                    uint32_t* ctl, bool ctl_clean, void* region, hipStream_t st) {
+  if (!fused_gqa_cluster_eligible(s, 1) || region == nullptr || ctl == nullptr) return hipErrorInvalidValue;
   const int C = fused_gqa_cluster_blocks(s, 1);
   const uint32_t spin_limit = g_spin_limit.load(std::memory_order_relaxed);
   switch (s.d / 8) {
-    case 2: return launch_cluster_n<2>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
-    case 4: return launch_cluster_n<4>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
-    case 8: return launch_cluster_n<8>(s, C, q, P, klo, khi, v, out, out_idx, region, spin_limit, st);
+    case 2: return launch_cluster_n<2>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
+    case 4: return launch_cluster_n<4>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
+    case 8: return launch_cluster_n<8>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
     default: return hipErrorInvalidValue;
   }
 }

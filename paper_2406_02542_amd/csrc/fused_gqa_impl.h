@@ -113,6 +113,12 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   const int L = CLUSTER ? gqa_slice_rows(S, cl.C) : S;
   const int row0 = CLUSTER ? min(cidx * L, S) : 0;
   const int row1 = CLUSTER ? min(row0 + L, S) : S;
+  // a launch that gave up earlier on this workspace left arrival flags behind (only a workspace
+  // that is not cleared in front of every launch can show this): then this launch must not trust them
+  bool poisoned = false;
+  if constexpr (CLUSTER) {
+    if (threadIdx.x == 0) poisoned = cluster_load_u32(cl.error) != 0u;
+  }
 
   LOKI_STAMP(0);
 #ifdef LOKI_PHASE_TIMING
@@ -299,7 +305,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
       shift -= bits;
       ++meet;
       ok = cluster_hist_round<THREADS>(s_sel.hist[0], xh, xh_unit + (uint32_t)level * round_bytes, C, cidx, counter,
-                                       meet, rem, cl.spin_limit, s_sel.wave[0], s_cl);
+                                       meet, rem, cl.spin_limit, poisoned, s_sel.wave[0], s_cl);
       if (!ok) break;
       const ClusterRound r = cluster_round_result(s_cl, C, cidx);
       prefix = (prefix << bits) | r.bin;
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
       for (int i = tid; i < 2048; i += THREADS) s_sel.hist[0][i] = 0u;  // (read for the last time inside the round)
       if (tid == 0) s_cl.red[0] = s_cl.red[1] = 0u;
       ++meet;
-      ok = cluster_arrive_and_wait(counter, C, cidx, meet, cl.spin_limit, s_cl);
+      ok = cluster_arrive_and_wait(counter, C, cidx, meet, cl.spin_limit, poisoned, s_cl);
       LOKI_STAMP(4);
       if (ok) {
         // every block ranks all candidates (on their remaining bits, moved to the top of the
@@ -515,10 +521,15 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
   if constexpr (CLUSTER) {
     LOKI_STAMP(9);
     // the block of the unit that finishes last merges the slices' partial results
-    if (splits_all_done(reinterpret_cast<int32_t*>(cl.counters + (size_t)unit * kClusterCounterStride + kClusterMax * kClusterFlagStride), cl.C))
+    uint32_t* ctl = cl.counters + (size_t)unit * kClusterCounterStride;
+    if (splits_all_done(reinterpret_cast<int32_t*>(ctl + kClusterMax * kClusterFlagStride), cl.C)) {
       for (int i = tid; i < G * kD; i += THREADS)
         out[head0 * kD + i] = BF16::round(
             combine_splits<true>(cl.partial + (head0 + i / kD) * cl.C * kPartialStride, cl.C, i % kD));
+      // every block of the unit is past its last wait and its flag store is acknowledged (it
+      // took a ticket): leave the unit's flags and ticket at zero for the next launch
+      if (tid <= kClusterMax) ctl[tid * kClusterFlagStride] = 0u;
+    }
   }
   LOKI_STAMP(8);
 }

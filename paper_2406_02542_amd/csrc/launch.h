@@ -78,6 +78,8 @@ struct Workspace {
   size_t ticket_words;    // its padded length in words
   uint32_t* sel_scratch;  // long sequences only: chunk histograms, candidates, bookkeeping
   float* partial;    // [B*Hq, nsplit, 130]
+  uint32_t* cluster_ctl;  // first bytes of every Loki workspace (kClusterCtlBytes): the arrival flags and tickets
+                          // of the several-blocks-per-unit launch, at the same place whatever the shape
   void* cluster;     // exchange area of the several-blocks-per-unit launch (fused_gqa_cluster.hip), or null
   size_t total_bytes;
 };
@@ -154,10 +156,19 @@ bool fused_gqa_cluster_preferred(const Shape& s, int select_mode);
 // Polls a block of a cluster spends in one wait before it gives up (a test aid: the default is
 // seconds; nothing a wait is for takes longer than the launch itself).
 constexpr uint32_t kClusterSpinLimit = 1u << 22;
+constexpr int kClusterMax = 8;             // blocks per unit at most
+constexpr int kClusterMaxUnits = 128;      // units of a cluster launch at most (two blocks each on 256 compute units)
+constexpr int kClusterFlagStride = 16;     // words between the arrival flags of two blocks: a cache line each
+constexpr int kClusterCounterStride = (kClusterMax + 1) * kClusterFlagStride;  // words of a unit's flags and ticket
+// the control words of every unit a cluster launch can have, and the error word behind them
+constexpr size_t kClusterCtlBytes = ((size_t)kClusterMaxUnits * kClusterCounterStride + 64) * 4;
 void set_cluster_spin_limit(uint32_t polls);
+// ctl: the workspace's control words (Workspace::cluster_ctl); ctl_clean: they are known to be
+// zero (a workspace the caller cleared once and only this library has written since: every
+// finished launch leaves them zero), so no clearing kernel goes in front.
 hipError_t launch_fused_gqa_cluster(const Shape& s, const void* q, const float* P, const void* klo,
                                     const void* khi, const void* v, void* out, int32_t* out_idx,
-                                    void* region, hipStream_t st);
+                                    uint32_t* ctl, bool ctl_clean, void* region, hipStream_t st);
 // Calibration and diagnostics (calibrate.hip).
 size_t pca_workspace_bytes(int Hkv, long long N);
 hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, long long N, float* P,

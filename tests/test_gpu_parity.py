@@ -297,6 +297,38 @@ def test_cluster_ties(S, k):
         assert st["heads_with_swaps"] == 0
 
 
+def test_cluster_on_a_workspace_the_caller_cleared_once():
+    """With LOKI_WORKSPACE_ZEROED the launch clears nothing in front: it relies on the control
+    words at the start of the workspace being zero, and leaves them zero.  Calls of two shapes
+    (8 and 4 blocks per unit, different numbers of units) share one cleared workspace, take
+    turns ten times, and must each time equal the call that asks for nothing (bit for bit);
+    calls on other kernel sequences in between write the rest of the workspace."""
+    wa, xa = _case("cluster_ws_a", 1, 8, 2, 9000, "bf16", 32, 900, seed=8101)
+    wb, xb = _case("cluster_ws_b", 5, 32, 8, 3000, "bf16", 16, 400, seed=8102)
+    ca, cb = DeviceCase(wa, xa), DeviceCase(wb, xb)
+    ref = {}
+    for name, c in (("a", ca), ("b", cb)):
+        ref[name] = c.run_loki(1, path=api.PATH_CLUSTER)
+    n = max(api.loki_workspace_bytes(c.layout, c.w.S, c.w.d, c.w.k, 1) for c in (ca, cb))
+    ws = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    for it in range(10):
+        for name, c in (("a", ca), ("b", cb)):
+            w = c.w
+            out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+            idx = torch.full((w.B, w.Hkv, w.k), -7, dtype=torch.int32, device="cuda")
+            api.loki_decode_attn(c.layout, c.q, c.P, c.klo, c.khi, c.v, w.S, w.d, w.k,
+                                 1 | api.PATH_CLUSTER | api.WORKSPACE_ZEROED, ws, out, idx)
+            if it % 3 == 1:  # another kernel sequence on the same workspace
+                api.loki_decode_attn(c.layout, c.q, c.P, c.klo, c.khi, c.v, w.S, w.d, w.k,
+                                     1 | api.PATH_SPLIT | api.WORKSPACE_ZEROED, ws,
+                                     torch.empty_like(out), None)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.float().cpu().numpy().astype(np.float64), ref[name][0]), (it, name)
+            assert np.array_equal(idx.cpu().numpy(), ref[name][1]), (it, name)
+    # the control words are zero again
+    assert int(ws[:128 * 144 * 4].view(torch.int32).abs().max()) == 0
+
+
 def test_cluster_wait_gives_up_cleanly():
     """The blocks of a unit wait for each other with a bounded number of polls.  With the bound
     set to one poll by the host, blocks that find a partner late give up: the launch must still
@@ -322,6 +354,29 @@ def test_cluster_wait_gives_up_cleanly():
     say(f"units that gave up with a one-poll limit: {gave_up} of {w.B * w.Hkv}")
     again, idx_again = case.run_loki(1, path=api.PATH_CLUSTER)
     assert np.array_equal(again, ref) and np.array_equal(idx_again, idx_ref)
+
+    # On a workspace the caller vouches for (LOKI_WORKSPACE_ZEROED: nothing is cleared in front of
+    # a launch) a give-up leaves its mark: later launches refuse (NaN everywhere) instead of
+    # trusting the flags it left behind, until the caller has zeroed the workspace again.
+    ws = torch.zeros(api.loki_workspace_bytes(case.layout, w.S, w.d, w.k, 1), dtype=torch.uint8, device="cuda")
+
+    def run_vouched():
+        o = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+        api.loki_decode_attn(case.layout, case.q, case.P, case.klo, case.khi, case.v, w.S, w.d, w.k,
+                             1 | api.PATH_CLUSTER | api.WORKSPACE_ZEROED, ws, o, None)
+        torch.cuda.synchronize()
+        return o.float().cpu().numpy().astype(np.float64)
+
+    assert np.array_equal(run_vouched(), ref)
+    api.loki_debug_cluster_spin_limit(1)
+    try:
+        o1 = run_vouched()
+    finally:
+        api.loki_debug_cluster_spin_limit(0)
+    if np.isnan(o1).any():
+        assert np.all(np.isnan(run_vouched()))
+        ws.zero_()
+    assert np.array_equal(run_vouched(), ref)
 
 
 def test_heavy_hitters_are_selected():

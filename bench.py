@@ -267,7 +267,7 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="KV-cache copies cycled through")
     ap.add_argument("--d", type=int, default=None)
     ap.add_argument("--k", type=int, default=None)
-    ap.add_argument("--path", choices=["auto", "split", "fused"], default="auto",
+    ap.add_argument("--path", choices=["auto", "split", "fused", "cluster"], default="auto",
                     help="kernel sequence: the library's choice, or pinned")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
@@ -309,7 +309,9 @@ def main():
     if args.k is not None:
         w = w.replace(k=args.k)
     mode = args.select_mode
-    path_bits = {"auto": 0, "split": api.PATH_SPLIT, "fused": api.PATH_FUSED}[args.path]
+    # the workspace is allocated once, cleared, and written by the library alone (see `ws` below)
+    path_bits = {"auto": 0, "split": api.PATH_SPLIT, "fused": api.PATH_FUSED,
+                 "cluster": api.PATH_CLUSTER}[args.path] | api.WORKSPACE_ZEROED
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
 
     log(f"[bench] generating {w}")
@@ -328,7 +330,7 @@ def main():
     del kh, vv
     q = torch.from_numpy(x["q"]).to("cuda").to(tdt)
     P = torch.from_numpy(x["P"]).to("cuda")
-    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode)
+    ws = api.alloc_workspace(lay, w.S, w.d, w.k, mode, zeroed=True)
     wsd = torch.empty(max(api.loki_workspace_bytes(lay, w.S, 0, 0, -1), 256), dtype=torch.uint8,
                       device="cuda")
     out = torch.empty((w.B, w.Hq, w.D), dtype=tdt, device="cuda")

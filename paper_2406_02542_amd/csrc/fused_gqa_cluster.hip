@@ -49,7 +49,8 @@ int fused_gqa_cluster_blocks(const Shape& s, int select_mode) {
 }
 
 bool fused_gqa_cluster_eligible(const Shape& s, int select_mode) {
-  if (s.rg.queries > 1 || s.pg.table != nullptr) return false;
+  if (s.rg.queries > 1) return false;
+  if (s.pg.table != nullptr && s.pg.pages_per_seq > kGqaMaxPages) return false;  // page list in LDS
   return fused_gqa_cluster_blocks(s, select_mode) > 0;
 }
 
@@ -91,13 +92,13 @@ size_t fused_gqa_cluster_bytes(const Shape& s, int select_mode) {
   return C ? cluster_plan(s, C).total : 0;
 }
 
-template <int NCH, int G>
+template <int NCH, int G, bool PAGED>
 static hipError_t launch_cluster_k(const Shape& s, int C, const void* q, const float* P, const void* klo,
                                    const void* khi, const void* v, void* out, int32_t* out_idx,
                                    uint32_t* ctl, bool ctl_clean, void* region, uint32_t spin_limit,
                                    hipStream_t st) {
   using Lds = GqaLds<kClusterThreads, G, true>;
-  auto kern = fused_gqa_kernel<kClusterThreads, NCH, G, kClusterKpt, false, true>;
+  auto kern = fused_gqa_kernel<kClusterThreads, NCH, G, kClusterKpt, PAGED, true>;
   const int L = gqa_slice_rows(s.S, C);
   const size_t lds = Lds::total_bytes(L, s.k < L ? s.k : L);
   static std::atomic<unsigned long long> lds_allowed{0};  // per instantiation: devices already set up
@@ -135,12 +136,20 @@ static hipError_t launch_cluster_n(const Shape& s, int C, const void* q, const f
                                    const void* khi, const void* v, void* out, int32_t* out_idx,
                                    uint32_t* ctl, bool ctl_clean, void* region, uint32_t spin_limit,
                                    hipStream_t st) {
+#define LOKI_CLUSTER_G(Gn)                                                                              \
+  case Gn:                                                                                              \
+    return s.pg.table != nullptr                                                                        \
+               ? launch_cluster_k<NCH, Gn, true>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, \
+                                                 spin_limit, st)                                        \
+               : launch_cluster_k<NCH, Gn, false>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, \
+                                                  spin_limit, st)
   switch (s.G) {
-    case 2: return launch_cluster_k<NCH, 2>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
-    case 4: return launch_cluster_k<NCH, 4>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
-    case 8: return launch_cluster_k<NCH, 8>(s, C, q, P, klo, khi, v, out, out_idx, ctl, ctl_clean, region, spin_limit, st);
+    LOKI_CLUSTER_G(2);
+    LOKI_CLUSTER_G(4);
+    LOKI_CLUSTER_G(8);
     default: return hipErrorInvalidValue;
   }
+#undef LOKI_CLUSTER_G
 }
 
 hipError_t launch_fused_gqa_cluster(const Shape& s, const void* q, const float* P, const void* klo,

@@ -74,7 +74,6 @@ __global__ __launch_bounds__(THREADS, THREADS == 256 ? 2 : 1) void fused_gqa_ker
     const uint16_t* __restrict__ q, const float* __restrict__ P, uint16_t* __restrict__ out,
     int32_t* __restrict__ out_idx, int Hkv, int S_max, int S_cap, int k_max, Ragged rag, Append ap,
     Paging pg, ClusterArgs cl) {
-  static_assert(!(CLUSTER && PAGED), "a cluster works on a contiguous cache");
   constexpr int kWaves = THREADS / 64;
   constexpr int PPW = kRotParts / kWaves;  // parts of the rotation a wave owns
   static_assert(PPW * kWaves == kRotParts, "the rotation's 8 parts divide over the waves");

@@ -71,15 +71,16 @@ def random_cluster_case(seed):
     k = int(rng.integers(1, min(S, 6000) + 1))
     ragged = bool(rng.integers(0, 2))
     append = bool(rng.integers(0, 2))
-    S_cap = S + int(rng.integers(0, 40))
+    page_rows = int(rng.choice([0, 0, 1024, 2048]))  # (at most 64 pages per sequence)
+    S_cap = None if page_rows else S + int(rng.integers(0, 40))
     w = synth.Workload(f"rand_c{seed}", B, G * Hkv, Hkv, 128, S, "bf16", d, k, seed=123500 + seed)
-    return w, ragged, append, S_cap
+    return w, ragged, append, S_cap, page_rows
 
 
 @pytest.mark.parametrize("seed", range(20))
 def test_random_shape_grouped_cluster(seed):
-    w, ragged, append, S_cap = random_cluster_case(seed)
-    run_step_case(w, 1, ragged, append, path=api.PATH_CLUSTER, S_cap=S_cap)
+    w, ragged, append, S_cap, page_rows = random_cluster_case(seed)
+    run_step_case(w, 1, ragged, append, path=api.PATH_CLUSTER, S_cap=S_cap, page_rows=page_rows)
 
 
 @pytest.mark.parametrize("seed", range(24))

@@ -328,7 +328,9 @@ def test_dense_step_ragged(G, dtype):
 @pytest.mark.parametrize("G,mode,path,page_rows", [(1, 0, api.PATH_FUSED, 256), (1, 0, api.PATH_SPLIT, 512),
                                                    (4, 0, api.PATH_SPLIT, 256), (4, 1, api.PATH_SPLIT, 1024),
                                                    (8, 1, api.PATH_SPLIT, 256), (4, 1, api.PATH_FUSED, 256),
-                                                   (8, 1, api.PATH_FUSED, 1024), (2, 1, api.PATH_FUSED, 512)])
+                                                   (8, 1, api.PATH_FUSED, 1024), (2, 1, api.PATH_FUSED, 512),
+                                                   (4, 1, api.PATH_CLUSTER, 256), (8, 1, api.PATH_CLUSTER, 1024),
+                                                   (2, 1, api.PATH_CLUSTER, 512)])
 def test_step_paged_cache_against_oracle(G, mode, path, page_rows):
     """The whole step (ragged, appending) on a paged cache against the oracle itself, not only
     against the contiguous layout: outputs, index lists and the appended rows."""
@@ -590,7 +592,8 @@ def test_multi_token_step_equals_single_token_steps_on_random_shapes(seed):
     (4, "bf16", 1, 512, 5, api.PATH_SPLIT), (1, "bf16", 0, 256, 3, api.PATH_SPLIT),
     (1, "bf16", 0, 256, 1, api.PATH_FUSED), (1, "bf16", 0, 2048, 1, api.PATH_FUSED),
     (1, "f32", 0, 512, 1, api.PATH_FUSED), (4, "bf16", 1, 256, 1, api.PATH_FUSED),
-    (8, "bf16", 1, 2048, 1, api.PATH_FUSED), (2, "bf16", 1, 512, 1, api.PATH_FUSED)])
+    (8, "bf16", 1, 2048, 1, api.PATH_FUSED), (2, "bf16", 1, 512, 1, api.PATH_FUSED),
+    (4, "bf16", 1, 256, 1, api.PATH_CLUSTER), (8, "bf16", 1, 1024, 1, api.PATH_CLUSTER)])
 def test_paged_cache_equals_contiguous_cache(G, dtype, mode, page_rows, m, path):
     """The same rows scattered over randomly ordered physical pages (with unused pages in
     between) give bit-identical outputs, index lists and appended rows, on either kernel

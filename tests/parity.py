@@ -81,7 +81,7 @@ class DeviceCase:
         self.P = torch.from_numpy(inputs["P"]).to("cuda").contiguous()
 
     def run_loki(self, mode: int, want_idx: bool = True, path: int = 0):
-        """path: 0 = library's choice, api.PATH_SPLIT or api.PATH_FUSED to pin it."""
+        """path: 0 = library's choice; api.PATH_SPLIT, api.PATH_FUSED or api.PATH_CLUSTER pin it."""
         w = self.w
         ws = api.alloc_workspace(self.layout, w.S, w.d, w.k, mode)
         out = torch.full((w.B, w.Hq, w.D), float("nan"), dtype=TORCH_DT[w.dtype], device="cuda")

@@ -9,11 +9,12 @@
 //                                     column per lane) are one 16-byte LDS read; bf16 keys are exact, fp32 keys enter as two bf16 terms
 //   cov_reduce_kernel  (head)         chunk partials added in a fixed order in fp64; sample
 //                                     covariance C = (G - s s^T / N) / (N - 1)
-//   jacobi_kernel      (head)         cyclic Jacobi eigensolver in fp64, C resident in LDS
-//                                     (129 KiB), 64 disjoint rotations per round in a
-//                                     round-robin order, eigenvectors accumulated in L2-resident
-//                                     global memory; eigenpairs sorted by decreasing eigenvalue,
-//                                     every component's largest entry made positive
+//   jacobi_sweep_kernel, jacobi_apply_kernel, jacobi_finish_kernel
+//                                     cyclic Jacobi eigensolver in fp64 (see there): C resident in
+//                                     LDS (129 KiB), 64 disjoint rotations per round in a
+//                                     round-robin order, the eigenvector accumulation spread over
+//                                     8 blocks per head; eigenpairs sorted by decreasing
+//                                     eigenvalue, every component's largest entry made positive
 //   rank_at_kernel, layer_width_kernel, jaccard_kernel    small reductions
 #include "common.h"
 
@@ -170,28 +171,64 @@ __global__ __launch_bounds__(1024) void cov_reduce_kernel(const float* __restric
 }
 
 // ---- eigensolver ------------------------------------------------------------------------------
+// Cyclic Jacobi in fp64, one sweep (127 rounds of 64 disjoint rotations, round-robin pairing)
+// per launch pair:
+//   jacobi_sweep_kernel (head)            C resident in LDS (129 KiB); checks convergence, then
+//                                         rotates C round by round and logs every rotation's
+//                                         (cos, sin); C goes back to global memory for the next sweep
+//   jacobi_apply_kernel (column slice, head)  the eigenvector accumulator Vt is only ever rotated,
+//                                         row pair by row pair, and columns do not mix: each block
+//                                         keeps 16 columns of Vt in LDS and replays the sweep's log
+// so that the accumulation, which used to cost the solver block 256 KiB of L2 traffic per round,
+// is spread over 8 blocks per head.  The host enqueues kJacMaxSweeps pairs; a converged head's
+// blocks leave at once.  jacobi_finish_kernel sorts the eigenpairs and writes P.
 constexpr int kJacThreads = 1024;
 constexpr int kJacPitch = kD + 1;  // doubles per row of the LDS-resident matrix
 constexpr int kJacMaxSweeps = 30;
+constexpr int kJacRounds = kD - 1;
+constexpr int kJacSliceCols = 16;                  // columns of Vt one apply block owns
+constexpr int kJacSlices = kD / kJacSliceCols;
+constexpr int kJacApplyThreads = 256;
 
-__global__ __launch_bounds__(kJacThreads) void jacobi_kernel(const double* __restrict__ cov,
-                                                             double* __restrict__ vt_all,
-                                                             float* __restrict__ P,
-                                                             float* __restrict__ eigenvalues) {
+// round-robin pairing of 128 indices: slot 0 pairs (round, 127), slot t pairs
+// ((round + t) % 127, (round - t) % 127); returned with p < q
+__device__ __forceinline__ void jacobi_pair(int round, int slot, int& p, int& q) {
+  if (slot == 0) {
+    p = round;
+    q = kD - 1;
+  } else {
+    p = (round + slot) % (kD - 1);
+    q = (round - slot + (kD - 1)) % (kD - 1);
+  }
+  if (p > q) {
+    const int t = p;
+    p = q;
+    q = t;
+  }
+}
+
+// state[head]: 0 while the head still rotates, 1 once it has converged (set here, read by later
+// launches); log[head][round][slot] = (cos, sin) of this sweep; n_logged[head] = rounds logged
+// by this launch (0 or kJacRounds).
+__global__ __launch_bounds__(kJacThreads) void jacobi_sweep_kernel(double* __restrict__ a_all,
+                                                                   double2* __restrict__ log_all,
+                                                                   int* __restrict__ state,
+                                                                   int* __restrict__ n_logged, int sweep) {
   extern __shared__ __align__(16) unsigned char jac_smem[];
   double* A = reinterpret_cast<double*>(jac_smem);  // [128][kJacPitch]
   __shared__ double s_c[kD / 2], s_s[kD / 2];
   __shared__ int s_p[kD / 2], s_q[kD / 2];
   __shared__ double s_red[kJacThreads / 64];
-  __shared__ double s_off, s_diag;
-  __shared__ int s_rank[kD];
 
   const int tid = threadIdx.x, head = blockIdx.x;
-  double* Vt = vt_all + (size_t)head * kD * kD;  // Vt[j][i] = component j, entry i
-  for (int e = tid; e < kD * kD; e += kJacThreads) {
-    A[(e / kD) * kJacPitch + e % kD] = cov[(size_t)head * kD * kD + e];
-    Vt[e] = (e / kD == e % kD) ? 1.0 : 0.0;
+  if (sweep == 0 && tid == 0) state[head] = 0;
+  if (sweep > 0 && state[head] != 0) {  // (uniform; written by an earlier launch)
+    if (tid == 0) n_logged[head] = 0;
+    return;
   }
+  double* Ag = a_all + (size_t)head * kD * kD;
+  double2* log = log_all + (size_t)head * kJacRounds * (kD / 2);
+  for (int e = tid; e < kD * kD; e += kJacThreads) A[(e / kD) * kJacPitch + e % kD] = Ag[e];
   __syncthreads();
 
   auto block_sum = [&](double x) -> double {
@@ -206,87 +243,124 @@ __global__ __launch_bounds__(kJacThreads) void jacobi_kernel(const double* __res
     return t;
   };
 
-  for (int sweep = 0; sweep < kJacMaxSweeps; ++sweep) {
-    // converged when the off-diagonal mass is at rounding level of the diagonal's
-    double off = 0.0, dg = 0.0;
-    for (int e = tid; e < kD * kD; e += kJacThreads) {
-      const double x = A[(e / kD) * kJacPitch + e % kD];
-      if (e / kD == e % kD) dg += x * x; else off += x * x;
+  // converged when the off-diagonal mass is at rounding level of the diagonal's
+  double off = 0.0, dg = 0.0;
+  for (int e = tid; e < kD * kD; e += kJacThreads) {
+    const double x = A[(e / kD) * kJacPitch + e % kD];
+    if (e / kD == e % kD) dg += x * x; else off += x * x;
+  }
+  off = block_sum(off);
+  dg = block_sum(dg);
+  if (off <= 1e-28 * dg || dg == 0.0) {  // uniform: every thread holds the same sums
+    if (tid == 0) {
+      state[head] = 1;
+      n_logged[head] = 0;
     }
-    off = block_sum(off);
-    dg = block_sum(dg);
-    if (off <= 1e-28 * dg || dg == 0.0) break;  // uniform: every thread holds the same sums
-
-    for (int round = 0; round < kD - 1; ++round) {
-      // round-robin pairing of 128 indices: (127, round) and ((round + t) % 127, (round - t) % 127)
-      if (tid < kD / 2) {
-        int p, q;
-        if (tid == 0) {
-          p = round;
-          q = kD - 1;
-        } else {
-          p = (round + tid) % (kD - 1);
-          q = (round - tid + (kD - 1)) % (kD - 1);
-        }
-        if (p > q) { const int t = p; p = q; q = t; }
-        const double app = A[p * kJacPitch + p], aqq = A[q * kJacPitch + q], apq = A[p * kJacPitch + q];
-        double cs = 1.0, sn = 0.0;
-        if (fabs(apq) > 1e-300) {
-          const double theta = (aqq - app) / (2.0 * apq);
-          const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
-          cs = 1.0 / sqrt(t * t + 1.0);
-          sn = t * cs;
-        }
-        s_p[tid] = p; s_q[tid] = q; s_c[tid] = cs; s_s[tid] = sn;
-      }
-      __syncthreads();
-      // rows: A <- J^T A
-      for (int it = tid; it < (kD / 2) * kD; it += kJacThreads) {
-        const int pr = it / kD, j = it % kD;
-        const int p = s_p[pr], q = s_q[pr];
-        const double cs = s_c[pr], sn = s_s[pr];
-        const double x = A[p * kJacPitch + j], y = A[q * kJacPitch + j];
-        A[p * kJacPitch + j] = cs * x - sn * y;
-        A[q * kJacPitch + j] = sn * x + cs * y;
-      }
-      __syncthreads();
-      // columns: A <- A J, and the same rotation on the eigenvector rows of Vt
-      for (int it = tid; it < (kD / 2) * kD; it += kJacThreads) {
-        const int pr = it / kD, i = it % kD;
-        const int p = s_p[pr], q = s_q[pr];
-        const double cs = s_c[pr], sn = s_s[pr];
-        const double x = A[i * kJacPitch + p], y = A[i * kJacPitch + q];
-        A[i * kJacPitch + p] = cs * x - sn * y;
-        A[i * kJacPitch + q] = sn * x + cs * y;
-        const double vx = Vt[p * kD + i], vy = Vt[q * kD + i];
-        Vt[p * kD + i] = cs * vx - sn * vy;
-        Vt[q * kD + i] = sn * vx + cs * vy;
-      }
-      __syncthreads();
-    }
+    return;
   }
 
-  // decreasing eigenvalue order (ties: lower index first); largest entry of a component positive
-  if (tid < kD) {
-    const double mine = A[tid * kJacPitch + tid];
-    int rank = 0;
-    for (int j = 0; j < kD; ++j) {
-      const double other = A[j * kJacPitch + j];
-      rank += (other > mine || (other == mine && j < tid)) ? 1 : 0;
+  for (int round = 0; round < kJacRounds; ++round) {
+    if (tid < kD / 2) {
+      int p, q;
+      jacobi_pair(round, tid, p, q);
+      const double app = A[p * kJacPitch + p], aqq = A[q * kJacPitch + q], apq = A[p * kJacPitch + q];
+      double cs = 1.0, sn = 0.0;
+      if (fabs(apq) > 1e-300) {
+        const double theta = (aqq - app) / (2.0 * apq);
+        const double t = (theta >= 0.0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+        cs = 1.0 / sqrt(t * t + 1.0);
+        sn = t * cs;
+      }
+      s_p[tid] = p; s_q[tid] = q; s_c[tid] = cs; s_s[tid] = sn;
+      log[round * (kD / 2) + tid] = make_double2(cs, sn);
     }
-    s_rank[tid] = rank;
-    eigenvalues[(size_t)head * kD + rank] = (float)mine;
+    __syncthreads();
+    // A <- J^T A J, one 2 x 2 block (row pair, column pair) at a time: the rows are rotated
+    // first and the columns after, element by element the same operations as two whole-matrix
+    // passes, with every element read and written once
+    for (int it = tid; it < (kD / 2) * (kD / 2); it += kJacThreads) {
+      const int pr = it / (kD / 2), pc = it % (kD / 2);
+      const int p = s_p[pr], q = s_q[pr], p2 = s_p[pc], q2 = s_q[pc];
+      const double cs = s_c[pr], sn = s_s[pr], cs2 = s_c[pc], sn2 = s_s[pc];
+      const double xpp = A[p * kJacPitch + p2], xpq = A[p * kJacPitch + q2];
+      const double xqp = A[q * kJacPitch + p2], xqq = A[q * kJacPitch + q2];
+      const double tpp = cs * xpp - sn * xqp, tqp = sn * xpp + cs * xqp;  // rows p, q at column p2
+      const double tpq = cs * xpq - sn * xqq, tqq = sn * xpq + cs * xqq;  // rows p, q at column q2
+      A[p * kJacPitch + p2] = cs2 * tpp - sn2 * tpq;
+      A[p * kJacPitch + q2] = sn2 * tpp + cs2 * tpq;
+      A[q * kJacPitch + p2] = cs2 * tqp - sn2 * tqq;
+      A[q * kJacPitch + q2] = sn2 * tqp + cs2 * tqq;
+    }
+    __syncthreads();
+  }
+  for (int e = tid; e < kD * kD; e += kJacThreads) Ag[e] = A[(e / kD) * kJacPitch + e % kD];
+  if (tid == 0) n_logged[head] = kJacRounds;
+}
+
+// Vt[j][i] = component j, entry i.  Block (slice, head) owns entries i in [16 slice, 16 slice + 16)
+// of every component; the rotation of components p and q is the same on every entry.  The first
+// sweep starts from the identity.
+__global__ __launch_bounds__(kJacApplyThreads) void jacobi_apply_kernel(double* __restrict__ vt_all,
+                                                                        const double2* __restrict__ log_all,
+                                                                        const int* __restrict__ n_logged,
+                                                                        int sweep) {
+  __shared__ double s_v[kD][kJacSliceCols + 1];
+  const int tid = threadIdx.x, slice = blockIdx.x, head = blockIdx.y;
+  const int n_rounds = n_logged[head];
+  if (n_rounds == 0 && sweep > 0) return;  // (uniform) nothing to replay: Vt stays as it is
+  double* Vt = vt_all + (size_t)head * kD * kD;
+  const double2* log = log_all + (size_t)head * kJacRounds * (kD / 2);
+  const int i0 = slice * kJacSliceCols;
+  for (int e = tid; e < kD * kJacSliceCols; e += kJacApplyThreads) {
+    const int j = e / kJacSliceCols, c = e % kJacSliceCols;
+    s_v[j][c] = sweep == 0 ? (j == i0 + c ? 1.0 : 0.0) : Vt[(size_t)j * kD + i0 + c];
   }
   __syncthreads();
-  if (tid < kD) {
-    const double* vrow = Vt + (size_t)tid * kD;
-    double best = 0.0;
-    for (int i = 0; i < kD; ++i)
-      if (fabs(vrow[i]) > fabs(best)) best = vrow[i];
-    const double sgn = best < 0.0 ? -1.0 : 1.0;
-    float* Pc = P + (size_t)head * kD * kD + s_rank[tid];  // column = component
-    for (int i = 0; i < kD; ++i) Pc[(size_t)i * kD] = (float)(sgn * vrow[i]);
+  // thread t: pair slot t / 4, columns 4 (t % 4) .. + 3 of the slice
+  const int slot = tid >> 2, c0 = 4 * (tid & 3);
+  for (int round = 0; round < n_rounds; ++round) {
+    int p, q;
+    jacobi_pair(round, slot, p, q);
+    const double2 r = log[round * (kD / 2) + slot];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const double vx = s_v[p][c0 + c], vy = s_v[q][c0 + c];
+      s_v[p][c0 + c] = r.x * vx - r.y * vy;
+      s_v[q][c0 + c] = r.y * vx + r.x * vy;
+    }
+    __syncthreads();
   }
+  for (int e = tid; e < kD * kJacSliceCols; e += kJacApplyThreads) {
+    const int j = e / kJacSliceCols, c = e % kJacSliceCols;
+    Vt[(size_t)j * kD + i0 + c] = s_v[j][c];
+  }
+}
+
+// decreasing eigenvalue order (ties: lower index first); largest entry of a component positive
+__global__ __launch_bounds__(kD) void jacobi_finish_kernel(const double* __restrict__ a_all,
+                                                           const double* __restrict__ vt_all,
+                                                           float* __restrict__ P,
+                                                           float* __restrict__ eigenvalues) {
+  __shared__ double s_diag[kD];
+  const int tid = threadIdx.x, head = blockIdx.x;
+  const double* Ag = a_all + (size_t)head * kD * kD;
+  const double* Vt = vt_all + (size_t)head * kD * kD;
+  s_diag[tid] = Ag[(size_t)tid * kD + tid];
+  __syncthreads();
+  const double mine = s_diag[tid];
+  int rank = 0;
+  for (int j = 0; j < kD; ++j) {
+    const double other = s_diag[j];
+    rank += (other > mine || (other == mine && j < tid)) ? 1 : 0;
+  }
+  eigenvalues[(size_t)head * kD + rank] = (float)mine;
+  const double* vrow = Vt + (size_t)tid * kD;
+  double best = 0.0;
+  for (int i = 0; i < kD; ++i)
+    if (fabs(vrow[i]) > fabs(best)) best = vrow[i];
+  const double sgn = best < 0.0 ? -1.0 : 1.0;
+  float* Pc = P + (size_t)head * kD * kD + rank;  // column = component
+  for (int i = 0; i < kD; ++i) Pc[(size_t)i * kD] = (float)(sgn * vrow[i]);
 }
 
 // Eq. 2: the smallest d whose leading normalised eigenvalues sum to at least v percent.
@@ -384,6 +458,8 @@ size_t pca_workspace_bytes(int Hkv, long long N) {
   b = (b + 255) / 256 * 256;
   b += (size_t)Hkv * kD * kD * sizeof(double);      // covariance
   b += (size_t)Hkv * kD * kD * sizeof(double);      // eigenvector accumulator
+  b += (size_t)Hkv * kJacRounds * (kD / 2) * sizeof(double2);  // one sweep's rotations
+  b += (size_t)2 * Hkv * sizeof(int);               // converged flags, rounds logged
   return b;
 }
 
@@ -410,11 +486,22 @@ hipError_t launch_pca_stage(int stage, int Hkv, int dtype, const void* keys, lon
     hipLaunchKernelGGL(cov_reduce_kernel, dim3(Hkv, kD * kD / 1024), dim3(1024), 0, st, gram_part,
                        sum_part, cov, N, nc);
   } else {
+    double2* log = reinterpret_cast<double2*>(vt + (size_t)Hkv * kD * kD);
+    int* state = reinterpret_cast<int*>(log + (size_t)Hkv * kJacRounds * (kD / 2));
+    int* n_logged = state + Hkv;
     const size_t lds = (size_t)kD * kJacPitch * sizeof(double);
     static std::atomic<unsigned long long> lds_allowed{0};  // devices already set up
-    const hipError_t ea = allow_dynamic_lds(reinterpret_cast<const void*>(jacobi_kernel), (int)lds, lds_allowed);
+    const hipError_t ea =
+        allow_dynamic_lds(reinterpret_cast<const void*>(jacobi_sweep_kernel), (int)lds, lds_allowed);
     if (ea != hipSuccess) return ea;
-    hipLaunchKernelGGL(jacobi_kernel, dim3(Hkv), dim3(kJacThreads), lds, st, cov, vt, P, eigenvalues);
+    // the covariance array is rotated in place, sweep by sweep
+    for (int sweep = 0; sweep < kJacMaxSweeps; ++sweep) {
+      hipLaunchKernelGGL(jacobi_sweep_kernel, dim3(Hkv), dim3(kJacThreads), lds, st, cov, log, state,
+                         n_logged, sweep);
+      hipLaunchKernelGGL(jacobi_apply_kernel, dim3(kJacSlices, Hkv), dim3(kJacApplyThreads), 0, st, vt, log,
+                         n_logged, sweep);
+    }
+    hipLaunchKernelGGL(jacobi_finish_kernel, dim3(Hkv), dim3(kD), 0, st, cov, vt, P, eigenvalues);
   }
   return hipGetLastError();
 }

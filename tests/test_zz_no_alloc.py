@@ -51,8 +51,10 @@ def _both(w, mode):
     return o_ref, i_ref, o_st, i_st
 
 
-@pytest.mark.parametrize("mode", [api.PATH_SPLIT | 0, 1])
+@pytest.mark.parametrize("mode", [api.PATH_SPLIT | 0, 1, api.PATH_CLUSTER | 1])
 def test_static_scratch_entry_point_matches_decode_attn(mode):
+    # (with cooperating blocks per unit the built-in buffer also holds the blocks' meeting flags:
+    # it starts as zeros, every launch leaves them zero, and no clearing kernel runs in front)
     big = synth.Workload("na_big", 2, 8, 2, 128, 3000, "bf16", 32, 500, seed=7700)
     small = synth.Workload("na_small", 1, 8, 2, 128, 700, "bf16", 32, 90, seed=7701)
     for w in (big, small):  # two calls in a row on the shared buffer, the second one smaller

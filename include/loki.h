@@ -367,6 +367,15 @@ int loki_profile_read(loki_profile* p, int* n_kernels, float* ms, const char** n
 int loki_debug_cluster_spin_limit(unsigned polls);
 
 /*
+ * Whether a LOKI_PATH_CLUSTER launch on this workspace gave up waiting since its control words
+ * were last cleared (by the clearing kernel in front of every launch without
+ * LOKI_WORKSPACE_ZEROED, else by the caller's zero fill): *gave_up = 1 or 0 (host pointer).
+ * Copies one word from the workspace after everything enqueued on `stream` so far has finished;
+ * returns when the answer is there.  `workspace` as passed to the decode call.
+ */
+int loki_cluster_gave_up(const void* workspace, int* gave_up, void* stream);
+
+/*
  * Measurement aid, not part of the method: enqueues one trivial kernel that reads
  * `bytes` bytes (a multiple of 16, 16-byte aligned device pointer) with coalesced
  * 16-byte loads and discards them.  Its duration over as many bytes as a decode step

@@ -93,6 +93,8 @@ def lib() -> ctypes.CDLL:
     L.loki_profile_attach.argtypes = [vp]
     L.loki_debug_cluster_spin_limit.restype = i32
     L.loki_debug_cluster_spin_limit.argtypes = [ctypes.c_uint]
+    L.loki_cluster_gave_up.restype = i32
+    L.loki_cluster_gave_up.argtypes = [vp, ctypes.POINTER(i32), vp]
     L.loki_stream_read.restype = i32
     L.loki_stream_read.argtypes = [vp, sz, vp]
     L.loki_profile_read.restype = i32
@@ -409,6 +411,15 @@ def loki_debug_cluster_spin_limit(polls: int) -> None:
     """Sets how many polls a block of a PATH_CLUSTER launch waits for its unit's other blocks
     (0 restores the default)."""
     _check(lib().loki_debug_cluster_spin_limit(int(polls)), "loki_debug_cluster_spin_limit")
+
+
+def loki_cluster_gave_up(workspace: torch.Tensor, stream=None) -> bool:
+    """True if a PATH_CLUSTER launch on this workspace gave up waiting since its control words
+    were last cleared (synchronises with the stream)."""
+    flag = ctypes.c_int32(0)
+    _check(lib().loki_cluster_gave_up(ctypes.c_void_p(workspace.data_ptr()), ctypes.byref(flag),
+                                      _stream_ptr(stream)), "loki_cluster_gave_up")
+    return bool(flag.value)
 
 
 def loki_stream_read(buf: torch.Tensor, nbytes: int, stream=None) -> None:

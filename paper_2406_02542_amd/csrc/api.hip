@@ -689,6 +689,19 @@ int loki_debug_cluster_spin_limit(unsigned polls) {
   return LOKI_OK;
 }
 
+int loki_cluster_gave_up(const void* workspace, int* gave_up, void* stream) {
+  if (!workspace || !gave_up) return LOKI_ERR_INVALID_ARG;
+  if (!aligned256(workspace)) return LOKI_ERR_ALIGNMENT;
+  // the error word sits behind the control words of the last unit, at the start of the workspace
+  const uint32_t* word = static_cast<const uint32_t*>(workspace) + (size_t)kClusterMaxUnits * kClusterCounterStride;
+  uint32_t v = 0;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hipMemcpyAsync(&v, word, sizeof(v), hipMemcpyDeviceToHost, st) != hipSuccess) return LOKI_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return LOKI_ERR_HIP;
+  *gave_up = v != 0u ? 1 : 0;
+  return LOKI_OK;
+}
+
 int loki_stream_read(const void* buf, size_t bytes, void* stream) {
   if (!buf || bytes == 0 || (bytes & 15) || (reinterpret_cast<uintptr_t>(buf) & 15))
     return LOKI_ERR_INVALID_ARG;

@@ -102,6 +102,10 @@ def test_rejects_bad_arguments_before_launch():
     assert L.dense_decode_attn(by(lay), p, p, p, 0, p, 1 << 30, p, None) == 1
     assert L.dense_decode_attn(by(lay), p, p + 2, p, 512, p, 1 << 30, p, None) == 3
     assert L.dense_decode_attn(by(lay), p, p, p, 512, p, 0, p, None) == 4
+    flag = ctypes.c_int32(7)
+    assert L.loki_cluster_gave_up(None, ctypes.byref(flag), None) == 1
+    assert L.loki_cluster_gave_up(p, None, None) == 1
+    assert L.loki_cluster_gave_up(p + 8, ctypes.byref(flag), None) == 3
     assert L.loki_stream_read(None, 1024, None) == 1
     assert L.loki_stream_read(p, 0, None) == 1
     assert L.loki_stream_read(p, 1000, None) == 1    # not a multiple of 16

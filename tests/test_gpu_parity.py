@@ -368,15 +368,19 @@ def test_cluster_wait_gives_up_cleanly():
         return o.float().cpu().numpy().astype(np.float64)
 
     assert np.array_equal(run_vouched(), ref)
+    assert not api.loki_cluster_gave_up(ws)
     api.loki_debug_cluster_spin_limit(1)
     try:
         o1 = run_vouched()
     finally:
         api.loki_debug_cluster_spin_limit(0)
+    # the library says so itself: the mark is there exactly when some unit came back as NaN
+    assert api.loki_cluster_gave_up(ws) == bool(np.isnan(o1).any())
     if np.isnan(o1).any():
         assert np.all(np.isnan(run_vouched()))
         ws.zero_()
     assert np.array_equal(run_vouched(), ref)
+    assert not api.loki_cluster_gave_up(ws)
 
 
 def test_heavy_hitters_are_selected():

@@ -83,7 +83,8 @@ enum { LOKI_SELECT_PER_QUERY_HEAD = 0, LOKI_SELECT_PER_KV_GROUP = 1 };
  * LOKI_ERR_UNSUPPORTED).  CLUSTER: the grouped-heads kernel of FUSED with 2, 4 or 8 cooperating
  * blocks per (batch, KV head) unit, each on a slice of the unit's rows, for batches with too few
  * units to fill the chip with one block each: the same conditions as FUSED for grouped heads
- * except that B * Hkv (rounded up to a multiple of 8) is at most half the device's compute units,
+ * except that B * Hkv (rounded up to a multiple of 8) is at most half the device's compute units
+ * (and at most 128),
  * and S / blocks <= 16384, min(k, S / blocks) <= 8192 (so S up to 131072 and k up to 8192 with
  * 8 blocks).  Its blocks wait for each other inside the
  * launch: every wait is bounded, and a block that gives up (see loki_debug_cluster_spin_limit)
